@@ -1,0 +1,136 @@
+"""ctypes front end of the CPU checker -- TEST INFRASTRUCTURE ONLY.
+
+Loads `libthemis_oracle.so` (built from the two C files in this directory by
+`build()`) and marshals numpy arrays.  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import this module; the GPU library never
+does and shares nothing with it.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libthemis_oracle.so")
+_SOURCES = [os.path.join(_HERE, f) for f in ("themis_oracle.c", "themis_bruteforce.c")]
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the checker with gcc (-O2, no intrinsics, single-threaded code)."""
+    if not force and os.path.exists(_LIB_PATH):
+        newest = max(os.path.getmtime(s) for s in _SOURCES)
+        if os.path.getmtime(_LIB_PATH) >= newest:
+            return _LIB_PATH
+    cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared",
+           "-o", _LIB_PATH] + _SOURCES
+    subprocess.run(cmd, check=True)
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = ctypes.CDLL(_LIB_PATH)
+        i32, p = ctypes.c_int32, ctypes.c_void_p
+        _lib.themis_oracle_candidates.restype = ctypes.c_int
+        _lib.themis_oracle_candidates.argtypes = [i32, i32, i32, p, i32, i32, i32, i32,
+                                                  p, p, p, p, i32, i32, p, p, p]
+        _lib.themis_oracle_solve.restype = ctypes.c_int
+        _lib.themis_oracle_solve.argtypes = [i32, i32, i32, p, i32, i32, i32, i32,
+                                             p, p, p, p, i32, i32, p, p, p, p]
+        _lib.themis_bruteforce.restype = ctypes.c_int
+        _lib.themis_bruteforce.argtypes = [i32, i32, i32, p, i32, i32, p, i32, i32, p,
+                                           p, p, p, p]
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _common(w):
+    bs = np.asarray(w.batch_sizes, dtype=np.int32)
+    return bs, _i32(w.coef), _i32(w.lam), _i32(w.slo_us), _i32(w.r_fixed)
+
+
+def candidates(w):
+    """Candidate tables (lt, cost, r), each int32 [N][S][K]; -1 marks infeasible."""
+    lib = _load()
+    bs, coef, lam, slo, rf = _common(w)
+    shape = (w.n_inst, w.n_stage, w.n_cand)
+    lt = np.empty(shape, np.int32)
+    cost = np.empty(shape, np.int32)
+    r = np.empty(shape, np.int32)
+    rc = lib.themis_oracle_candidates(w.n_stage, w.c_max, len(bs), _ptr(bs), w.r_max,
+                                      w.tick_us, w.slo_max_us, int(w.coef_shared),
+                                      _ptr(coef), _ptr(lam), _ptr(slo), _ptr(rf),
+                                      0, w.n_inst, _ptr(lt), _ptr(cost), _ptr(r))
+    if rc != 0:
+        raise RuntimeError(f"themis_oracle_candidates failed: {rc}")
+    return lt, cost, r
+
+
+def solve(w, threads: int = 1):
+    """Solve every instance; returns (status[N], cost[N], ticks[N], cfg[N][S][3]).
+
+    `threads` > 1 only shards the instance range over a thread pool; each
+    shard runs the same single-threaded C routine.
+    """
+    lib = _load()
+    bs, coef, lam, slo, rf = _common(w)
+    n, s = w.n_inst, w.n_stage
+    status = np.empty(n, np.int32)
+    cost = np.empty(n, np.int32)
+    ticks = np.empty(n, np.int32)
+    cfg = np.empty((n, s, 3), np.int32)
+
+    def run(lo, hi):
+        rc = lib.themis_oracle_solve(s, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us,
+                                     w.slo_max_us, int(w.coef_shared), _ptr(coef),
+                                     _ptr(lam), _ptr(slo), _ptr(rf), lo, hi,
+                                     _ptr(status[lo:]), _ptr(cost[lo:]),
+                                     _ptr(ticks[lo:]), _ptr(cfg[lo:]))
+        if rc != 0:
+            raise RuntimeError(f"themis_oracle_solve failed: {rc}")
+
+    threads = max(1, min(threads, n))
+    if threads == 1:
+        run(0, n)
+    else:
+        # small shards so that uneven instances still balance
+        step = max(1, n // (threads * 16))
+        spans = [(lo, min(n, lo + step)) for lo in range(0, n, step)]
+        with ThreadPoolExecutor(threads) as pool:
+            list(pool.map(lambda ab: run(*ab), spans))
+    return status, cost, ticks, cfg
+
+
+def bruteforce(w, i: int = 0):
+    """Exhaustive enumeration for instance i: (status, cost, ticks, cfg[S][3], visited)."""
+    lib = _load()
+    bs, coef, lam, slo, rf = _common(w)
+    cf = coef if w.coef_shared else coef[i]
+    cf = np.ascontiguousarray(cf)
+    rfi = None if rf is None else np.ascontiguousarray(rf[i])
+    cost = ctypes.c_int32(0)
+    ticks = ctypes.c_int32(0)
+    visited = ctypes.c_int64(0)
+    cfg = np.zeros((w.n_stage, 3), np.int32)
+    rc = lib.themis_bruteforce(w.n_stage, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us,
+                               _ptr(cf), int(lam[i]), int(slo[i]), _ptr(rfi),
+                               ctypes.byref(cost), ctypes.byref(ticks), _ptr(cfg),
+                               ctypes.byref(visited))
+    if rc < 0:
+        raise RuntimeError(f"themis_bruteforce failed: {rc}")
+    return rc, cost.value, ticks.value, cfg, visited.value

@@ -1,0 +1,276 @@
+/*
+ * CPU checker for the batched autoscaling solve -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, single-threaded C.  Nothing in the product path may call this
+ * file; it exists so that tests and the benchmark's CPU-baseline leg have an
+ * independent answer to compare the GPU library with.  It shares no source,
+ * header, table or helper with the GPU code.
+ *
+ * What it computes (per instance = one pipeline at one arrival rate):
+ * the integer program of Section 4.3 (Eq. 6)
+ *
+ *     minimise   sum_s n_s * c_s
+ *     subject to sum_s l_s(b_s,c_s) + q_s(b_s) <= SLO          (Eq. 5)
+ *                lambda <= h_s(b_s,c_s) * n_s   for every s
+ *                b_s, c_s, n_s positive integers
+ *
+ * solved the way Section 4.4 solves it: a dynamic program that adds the
+ * pipeline's models one at a time and, for every latency budget on a grid,
+ * splits the budget between the current model and the rest (Algorithm 1 for
+ * the vertical case where n_s is given, Algorithm 2 for the derived instance
+ * count; the joint solve is Algorithm 1's (c,b) loop with Algorithm 2's
+ * instance count folded into each candidate).  Like the paper's tables, the
+ * DP here is over EXACT latency sums: g[s][t] is the least total cores of
+ * models s..S-1 whose latencies add up to exactly t grid ticks (the paper's
+ * dp[][] reachability flag is "g < INF", its best[][][0] is g).  The answer
+ * scan walks the budgets upward and only accepts a strictly smaller total,
+ * which yields least cost first and least latency second, as in the scan
+ * that follows Algorithm 1's main loop.
+ *
+ * Readings where the paper is silent or garbled:
+ *   - integer stand-in for the fitted profile of Eq. 1:
+ *       proc(c,b) = ceil((a + k*b + q*b*b) / min(c,p)) + o   microseconds
+ *     (epsilon->a, gamma->k, eta->o, plus the quadratic batch term Section 4.1
+ *     mentions and a core cap p for the parallelism limit);
+ *   - throughput h = b / proc, constraint non-strict as in Eq. 6, so the
+ *     derived instance count is n = ceil(lambda*proc / (b*1e6)), never
+ *     the floor printed in Algorithm 2 (a floor would break the constraint);
+ *   - the candidate filter in both listings is read as "skip when the
+ *     throughput is insufficient or the latency exceeds the budget", which is
+ *     what the prose after Algorithm 1 says;
+ *   - queueing delay: the batch-fill wait of Eq. 4, (b-1)/lambda, taken per
+ *     replica (each of the n replicas sees lambda/n):
+ *       queue = ceil((b-1) * 1e6 * n / lambda)   microseconds;
+ *   - every rounding is upward; a stage's latency is put on the grid by
+ *     lt = ceil((proc+queue)/tick) and the budget is T = floor(SLO/tick);
+ *   - ties: least cost, then least total ticks, then the lexicographically
+ *     smallest ((c,b,n) of model 0, (c,b,n) of model 1, ...).  Running the
+ *     recurrence over suffixes and rebuilding forward from model 0, taking
+ *     the first (c ascending, then b ascending) candidate that attains the
+ *     optimum at each step, realises that order.
+ *
+ * Parity pins (tests/test_oracle_pins.py): exhaustive enumeration of Eq. 6
+ * in oracle/themis_bruteforce.c on tiny pipelines, a hand-worked example,
+ * the separable closed form under a loose SLO, monotonicity and refinement
+ * invariants, and an independent push-style transcription of Algorithm 1.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_INF ((int64_t)1 << 60)
+
+static int64_t ceildiv64(int64_t x, int64_t d) { return (x + d - 1) / d; }
+
+/* One candidate (c, b) of one model: Section 4.4, the "calculate l, q, h" step. */
+typedef struct {
+    int feasible;
+    int64_t r;      /* instances n_s                        */
+    int64_t lt;     /* latency in grid ticks                */
+    int64_t cost;   /* n_s * c_s                            */
+    int64_t lat_us; /* proc + queue, microseconds           */
+} orc_cand;
+
+static orc_cand eval_candidate(const int32_t *cf, int64_t lambda, int64_t T,
+                               int64_t tick, int64_t c, int64_t b,
+                               int64_t r_max, int64_t r_given /* <=0: derive */)
+{
+    orc_cand out;
+    int64_t a = cf[0], k = cf[1], q = cf[2], p = cf[3], o = cf[4];
+    int64_t div = c < p ? c : p;
+    int64_t proc = ceildiv64(a + k * b + q * b * b, div) + o;
+    int64_t r;
+    memset(&out, 0, sizeof out);
+    if (r_given <= 0) {
+        /* least n with lambda <= n * b / proc  (per second = 1e6 us) */
+        r = ceildiv64(lambda * proc, b * 1000000);
+        if (r < 1) r = 1;
+        if (r > r_max) return out;
+    } else {
+        r = r_given;
+        if (lambda * proc > r * b * 1000000) return out;
+    }
+    {
+        int64_t queue = ceildiv64((b - 1) * 1000000 * r, lambda);
+        int64_t lat = proc + queue;
+        int64_t lt = ceildiv64(lat, tick);
+        if (lt > T) return out;
+        out.feasible = 1;
+        out.r = r;
+        out.lt = lt;
+        out.cost = r * c;
+        out.lat_us = lat;
+    }
+    return out;
+}
+
+/*
+ * Input ranges an instance must respect (an interface rule, not the paper's):
+ * 1 <= lambda <= 2^20, 0 <= SLO <= slo_max, 0 <= a,k,q <= 2^20,
+ * 1 <= o <= 2^20, p >= 1, and 1 <= given instances <= r_max.  They keep every
+ * product below 2^63 for batch sizes up to 1024 and make every stage latency
+ * at least one microsecond.
+ */
+#define ORC_VAL_MAX (1 << 20)
+
+static int instance_valid(int64_t lambda, int64_t slo, int64_t slo_max,
+                          const int32_t *cf, int S,
+                          const int32_t *rfix, int64_t r_max)
+{
+    int s, j;
+    if (lambda < 1 || lambda > ORC_VAL_MAX || slo < 0 || slo > slo_max) return 0;
+    for (s = 0; s < S; ++s) {
+        for (j = 0; j < 3; ++j)
+            if (cf[5 * s + j] < 0 || cf[5 * s + j] > ORC_VAL_MAX) return 0;
+        if (cf[5 * s + 3] < 1) return 0;
+        if (cf[5 * s + 4] < 1 || cf[5 * s + 4] > ORC_VAL_MAX) return 0;
+        if (rfix && (rfix[s] < 1 || rfix[s] > r_max)) return 0;
+    }
+    return 1;
+}
+
+/*
+ * Candidate tables of instances [i0, i1): lt/cost/r are [i1-i0][S][K] with
+ * K = c_max*n_batch and index (c-1)*n_batch + j; infeasible entries hold -1.
+ * r_fixed == NULL selects the joint evaluation.
+ */
+int themis_oracle_candidates(int32_t n_stage, int32_t c_max, int32_t n_batch,
+                             const int32_t *batch_sizes, int32_t r_max,
+                             int32_t tick_us, int32_t slo_max_us, int32_t coef_shared,
+                             const int32_t *coef, const int32_t *lambda,
+                             const int32_t *slo_us, const int32_t *r_fixed,
+                             int32_t i0, int32_t i1,
+                             int32_t *lt_out, int32_t *cost_out, int32_t *r_out)
+{
+    int S = n_stage, K = c_max * n_batch;
+    int i, s, c, j;
+    for (i = i0; i < i1; ++i) {
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        const int32_t *rf = r_fixed ? r_fixed + (size_t)i * S : NULL;
+        int ok = instance_valid(lambda[i], slo_us[i], slo_max_us, cf, S, rf, r_max);
+        int64_t T = ok ? slo_us[i] / tick_us : 0;
+        for (s = 0; s < S; ++s)
+            for (c = 1; c <= c_max; ++c)
+                for (j = 0; j < n_batch; ++j) {
+                    size_t at = ((size_t)(i - i0) * S + s) * K + (size_t)(c - 1) * n_batch + j;
+                    orc_cand cd;
+                    memset(&cd, 0, sizeof cd);
+                    if (ok)
+                        cd = eval_candidate(cf + 5 * s, lambda[i], T, tick_us, c,
+                                            batch_sizes[j], r_max, rf ? rf[s] : 0);
+                    lt_out[at] = cd.feasible ? (int32_t)cd.lt : -1;
+                    cost_out[at] = cd.feasible ? (int32_t)cd.cost : -1;
+                    r_out[at] = cd.feasible ? (int32_t)cd.r : -1;
+                }
+    }
+    return 0;
+}
+
+/*
+ * Solve instances [i0, i1).  Outputs are indexed from i0:
+ *   status 0 solved, 1 no configuration meets the SLO, 2 invalid input;
+ *   cost = total cores, ticks = total latency on the grid (both -1 unless
+ *   solved); cfg[.][s] = (c, b, n) per model (zeros unless solved).
+ */
+int themis_oracle_solve(int32_t n_stage, int32_t c_max, int32_t n_batch,
+                        const int32_t *batch_sizes, int32_t r_max,
+                        int32_t tick_us, int32_t slo_max_us, int32_t coef_shared,
+                        const int32_t *coef, const int32_t *lambda,
+                        const int32_t *slo_us, const int32_t *r_fixed,
+                        int32_t i0, int32_t i1,
+                        int32_t *status, int32_t *cost, int32_t *ticks, int32_t *cfg)
+{
+    int S = n_stage, K = c_max * n_batch;
+    int i, s, k;
+    orc_cand *cand = (orc_cand *)malloc(sizeof(orc_cand) * (size_t)S * K);
+    int64_t *g = NULL;
+    size_t g_cap = 0;
+    if (!cand) return -1;
+
+    for (i = i0; i < i1; ++i) {
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        const int32_t *rf = r_fixed ? r_fixed + (size_t)i * S : NULL;
+        int32_t *o_cfg = cfg + (size_t)(i - i0) * S * 3;
+        int64_t T, t, best_cost, best_t;
+        size_t row;
+
+        status[i - i0] = 1;
+        cost[i - i0] = -1;
+        ticks[i - i0] = -1;
+        memset(o_cfg, 0, sizeof(int32_t) * S * 3);
+        if (!instance_valid(lambda[i], slo_us[i], slo_max_us, cf, S, rf, r_max)) {
+            status[i - i0] = 2;
+            continue;
+        }
+        T = slo_us[i] / tick_us;
+        row = (size_t)T + 1;
+
+        /* the candidates of every model, in (c ascending, b ascending) order */
+        for (s = 0; s < S; ++s)
+            for (k = 0; k < K; ++k)
+                cand[(size_t)s * K + k] =
+                    eval_candidate(cf + 5 * s, lambda[i], T, tick_us,
+                                   k / n_batch + 1, batch_sizes[k % n_batch],
+                                   r_max, rf ? rf[s] : 0);
+
+        if ((size_t)(S + 1) * row > g_cap) {
+            free(g);
+            g_cap = (size_t)(S + 1) * row;
+            g = (int64_t *)malloc(sizeof(int64_t) * g_cap);
+            if (!g) { free(cand); return -1; }
+        }
+        /* no models left: only the empty split (zero latency) is reachable */
+        for (t = 0; t <= T; ++t) g[(size_t)S * row + t] = ORC_INF;
+        g[(size_t)S * row + 0] = 0;
+
+        /* add models one at a time; split budget t between model s and the rest */
+        for (s = S - 1; s >= 0; --s)
+            for (t = 0; t <= T; ++t) {
+                int64_t m = ORC_INF;
+                for (k = 0; k < K; ++k) {
+                    const orc_cand *cd = &cand[(size_t)s * K + k];
+                    int64_t rest;
+                    if (!cd->feasible || cd->lt > t) continue;
+                    rest = g[(size_t)(s + 1) * row + (t - cd->lt)];
+                    if (rest >= ORC_INF) continue;
+                    if (cd->cost + rest < m) m = cd->cost + rest;
+                }
+                g[(size_t)s * row + t] = m;
+            }
+
+        /* answer scan: budgets upward, strictly smaller total replaces */
+        best_cost = ORC_INF;
+        best_t = -1;
+        for (t = 0; t <= T; ++t)
+            if (g[t] < best_cost) { best_cost = g[t]; best_t = t; }
+        if (best_t < 0) continue;
+
+        /* rebuild forward; first candidate in (c,b) order that attains g */
+        t = best_t;
+        for (s = 0; s < S; ++s) {
+            int found = 0;
+            for (k = 0; k < K && !found; ++k) {
+                const orc_cand *cd = &cand[(size_t)s * K + k];
+                int64_t rest;
+                if (!cd->feasible || cd->lt > t) continue;
+                rest = g[(size_t)(s + 1) * row + (t - cd->lt)];
+                if (rest >= ORC_INF) continue;
+                if (cd->cost + rest == g[(size_t)s * row + t]) {
+                    o_cfg[3 * s + 0] = k / n_batch + 1;
+                    o_cfg[3 * s + 1] = batch_sizes[k % n_batch];
+                    o_cfg[3 * s + 2] = (int32_t)cd->r;
+                    t -= cd->lt;
+                    found = 1;
+                }
+            }
+            if (!found) { free(cand); free(g); return -2; }
+        }
+        if (t != 0) { free(cand); free(g); return -3; }
+        status[i - i0] = 0;
+        cost[i - i0] = (int32_t)best_cost;
+        ticks[i - i0] = (int32_t)best_t;
+    }
+    free(cand);
+    free(g);
+    return 0;
+}
