@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched autoscaling solve on one MI355X.
+
+A step is one pass of the whole solve (candidate tables -> min-plus DP ->
+selection and reconstruction) over one batch of synthetic instances whose
+inputs are already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..4] [--others]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X figures used as roofline denominators.
+HBM_PEAK_GBS = 8000.0
+N_CU, CLOCK_GHZ = 256, 2.4
+LDS_BYTES_PER_CLK_CU = 128          # ds_read path per compute unit
+LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
+VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def run_workload(themis, wl, idx, steps, warmup, n_inst=None):
+    """Time `steps` solves of workload idx; returns a dict of measurements."""
+    import numpy as np
+    import torch
+
+    w = wl.workload(idx, n_inst)
+    passes = [w]
+    if idx == 4:
+        passes = [w, None]          # second pass is built from the first one's output
+    out = {"workload": w.name, "n_inst": w.n_inst, "n_stage": w.n_stage, "n_cand": w.n_cand}
+    total_ms = 0.0
+    k_ms = [0.0, 0.0, 0.0]
+    cells = 0
+    relax = 0
+    solved = 0
+    for pi, wp in enumerate(passes):
+        if wp is None:
+            # trace sweep, vertical pass: replicas carried forward from the
+            # joint pass this same library just produced
+            st, _, _, cfg = first_results
+            wp = w.with_r_fixed(wl.replicas_carried_forward(st, cfg))
+        b = themis.DeviceBatch(wp, "cuda:0")
+        p = b.p
+        stream = torch.cuda.current_stream()
+
+        def step(ev=None):
+            themis.themis_stage_candidates(p, b.coef, b.lam, b.slo_us, b.r_fixed, b.workspace, stream)
+            if ev:
+                ev[1].record(stream)
+            themis.themis_stage_minplus(p, b.workspace, stream)
+            if ev:
+                ev[2].record(stream)
+            themis.themis_stage_backtrack(p, b.status, b.cost, b.ticks, b.cfg, b.workspace, stream)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        evs = [_events(4) for _ in range(steps)]
+        t0 = time.perf_counter()
+        for e in evs:
+            e[0].record(stream)
+            step(e)
+            e[3].record(stream)
+        torch.cuda.synchronize()
+        total_ms += (time.perf_counter() - t0) * 1e3
+        for e in evs:
+            for j in range(3):
+                k_ms[j] += e[j].elapsed_time(e[j + 1])
+
+        res = b.results()
+        if pi == 0:
+            first_results = res
+        solved += int((res[0] == 0).sum())
+        cnt = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        themis.themis_count_relaxations(p, b.workspace, cnt)
+        torch.cuda.synchronize()
+        relax += int(cnt.item())
+        Ti = (wp.slo_us.astype(np.int64) // wp.tick_us)
+        cells += int(((Ti + 1) * wp.n_stage).sum())
+        del b
+        torch.cuda.empty_cache()
+
+    n_solves = w.n_inst * len(passes)
+    ms_per_step = total_ms / steps
+    k_ms = [x / steps for x in k_ms]
+    out.update({
+        "solves_per_step": n_solves,
+        "ms_per_step": ms_per_step,
+        "solves_per_s": n_solves / (ms_per_step * 1e-3),
+        "dp_cells_per_s": cells / (ms_per_step * 1e-3),
+        "relaxations_per_s": relax / (ms_per_step * 1e-3),
+        "dp_cells": cells,
+        "relaxations_executed": relax,
+        "relaxations_nominal": cells * w.n_cand,
+        "feasible_fraction": solved / n_solves,
+        "kernel_ms": {"candidates": k_ms[0], "minplus": k_ms[1], "backtrack": k_ms[2]},
+    })
+    # stage 1: 8 bytes written per candidate (+ 20 bytes of coefficients per model)
+    cand = w.n_inst * w.n_stage * w.n_cand * len(passes)
+    k1_bytes = cand * 8 + w.n_inst * w.n_stage * 20 * len(passes)
+    out["candidates_GBs"] = k1_bytes / (k_ms[0] * 1e-3) / 1e9 if k_ms[0] > 0 else None
+    # stage 2: 4 bytes read per relaxation + 4 bytes written per cell (int32-equivalent),
+    # of which this kernel physically moves 2 + 2*2 (16-bit cells, two copies written)
+    out["minplus_alg_bytes"] = relax * 4 + cells * 4
+    out["minplus_phys_bytes"] = relax * 2 + cells * 4
+    return out
+
+
+def cpu_baseline(wl, idx, max_inst):
+    """The CPU checker, as it stands, timed on this machine's host cores."""
+    from oracle import oracle
+    oracle.build(force=False)
+    w = wl.workload(idx, max_inst)
+    threads = min(os.cpu_count() or 1, 16)
+    oracle.solve(w.head(min(8, w.n_inst)))       # load + touch
+    t0 = time.perf_counter()
+    oracle.solve(w, threads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": w.n_inst / dt, "unit": "solves/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {w.n_inst} instances of {w.name}, instance range sharded over "
+                      f"{threads} threads, {dt:.2f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=1)
+    ap.add_argument("--others", action="store_true",
+                    help="also time the other numbered workloads (fewer steps)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this solve runs on one GPU; instances are independent, so N GPUs "
+              "would each take a contiguous shard. Only --gpus 1 is measured.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    from paper_2407_14843_amd import themis, workloads as wl
+    themis.lib()
+
+    m = run_workload(themis, wl, a.workload, a.steps, a.warmup)
+    k2_ms = m["kernel_ms"]["minplus"]
+    k2_gbs = m["minplus_alg_bytes"] / (k2_ms * 1e-3) / 1e9
+    line = {
+        "metric": "joint-scaling DP solves/sec",
+        "value": m["solves_per_s"],
+        "unit": "solves/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": m["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u16",
+        "data": "synthetic",
+        "config": {"workload": m["workload"], "n_inst": m["n_inst"], "n_stage": m["n_stage"],
+                   "candidates_per_stage": m["n_cand"]},
+        "dp_cells_per_s": m["dp_cells_per_s"],
+        "relaxations_per_s": m["relaxations_per_s"],
+        "feasible_fraction": m["feasible_fraction"],
+        "kernel_ms": m["kernel_ms"],
+        "roofline": {
+            "kernel": "k2_minplus", "bound": "lds", "achieved": k2_gbs, "peak": LDS_PEAK_GBS,
+            "unit": "GB/s", "frac": k2_gbs / LDS_PEAK_GBS, "traffic": None,
+            "bytes_per_launch": m["minplus_alg_bytes"],
+            "physical_bytes_per_launch": m["minplus_phys_bytes"],
+            "physical_frac": m["minplus_phys_bytes"] / (k2_ms * 1e-3) / 1e9 / LDS_PEAK_GBS,
+            "valu_frac": (m["relaxations_executed"] / (k2_ms * 1e-3) / 1e9) / VALU_PEAK_GOPS,
+        },
+        "roofline_candidates": {
+            "kernel": "k1_candidates", "bound": "hbm", "achieved": m["candidates_GBs"],
+            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": None if m["candidates_GBs"] is None else m["candidates_GBs"] / HBM_PEAK_GBS,
+            "traffic": None,
+        },
+    }
+    if a.others:
+        others = {}
+        for idx in range(5):
+            if idx == a.workload:
+                continue
+            o = run_workload(themis, wl, idx, max(3, a.steps // 4), 1)
+            others[o["workload"]] = {k: o[k] for k in (
+                "solves_per_s", "dp_cells_per_s", "relaxations_per_s", "ms_per_step",
+                "feasible_fraction", "kernel_ms", "candidates_GBs")}
+            others[o["workload"]]["minplus_lds_frac"] = (
+                o["minplus_alg_bytes"] / (o["kernel_ms"]["minplus"] * 1e-3) / 1e9 / LDS_PEAK_GBS)
+        line["other_workloads"] = others
+    if not a.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(wl, a.workload, 4096)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,200 @@
+/*
+ * themis.h -- C ABI of the batched autoscaling solve for AMD MI355X (gfx950).
+ *
+ * One "instance" is one inference pipeline (a chain of n_stage models) at one
+ * request arrival rate lambda under one end-to-end latency objective.  For
+ * every instance the library solves the integer program of Section 4.3
+ * (Eq. 6): choose, per model s, cores per replica c_s, batch size b_s and
+ * replica count n_s so that the total cores sum_s n_s*c_s are least while
+ *
+ *     sum_s [ l_s(b_s,c_s) + q_s(b_s) ] <= SLO                 (Eq. 5)
+ *     lambda <= h_s(b_s,c_s) * n_s      for every model s
+ *
+ * using the stage-by-stage dynamic program over a latency-budget grid that
+ * Section 4.4 describes (Algorithm 1 with the replicas given = "vertical";
+ * Algorithm 1's (c,b) search with Algorithm 2's derived replica count folded
+ * into every candidate = "joint").  Thousands of independent instances are
+ * solved per call, one after the other in HBM, all on one GPU.
+ *
+ * Integer model (all times in microseconds, every rounding upward).  For
+ * model s with profile coefficients (a,k,q,p,o), cores c and batch b:
+ *     proc  = ceil((a + k*b + q*b*b) / min(c,p)) + o        after Eq. 1
+ *     n     = ceil(lambda*proc / (b*1e6))  (joint; infeasible if n > r_max)
+ *             given r_fixed[s]             (vertical; infeasible unless
+ *                                           lambda*proc <= n*b*1e6)
+ *     queue = ceil((b-1)*1e6*n / lambda)                    after Eq. 4
+ *     lt    = ceil((proc+queue) / tick_us)   grid ticks
+ *     cost  = n*c
+ * and the budget of an instance is T = floor(slo_us / tick_us) ticks.
+ * A candidate is the pair (c,b); its index is k = (c-1)*n_batch + j for
+ * b = batch_sizes[j], so index order is (c ascending, b ascending).
+ *
+ * Result per instance: the feasible assignment with the smallest
+ *     ( total cost, total ticks, (c,b,n) of model 0, (c,b,n) of model 1, ... )
+ * compared left to right.  Exactly one assignment is smallest, so results
+ * are reproducible bit for bit.
+ *
+ * Conventions common to all entry points
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; p is a HOST
+ *     pointer.  The library allocates nothing, frees nothing and keeps no
+ *     state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; the call returns without synchronising.
+ *   - Return value: THEMIS_OK, or a negative THEMIS_ERR_* found on the host
+ *     before anything is launched.  Nothing is printed; no exception crosses
+ *     the boundary.
+ *   - Per-instance trouble is reported in d_status, never as a return code.
+ */
+#ifndef THEMIS_H
+#define THEMIS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define THEMIS_MAX_BATCH 16      /* entries in batch_sizes[]                    */
+#define THEMIS_MAX_BATCH_SIZE 1024
+#define THEMIS_VALUE_MAX (1 << 20) /* upper bound on lambda and on a,k,q,o      */
+#define THEMIS_COST_LIMIT 32767  /* n_stage*r_max*c_max must not exceed this    */
+#define THEMIS_MAX_TICKS 32767   /* floor(slo_max_us/tick_us) must not exceed   */
+
+/* return codes */
+#define THEMIS_OK 0
+#define THEMIS_ERR_NULL (-1)      /* a required pointer is NULL                 */
+#define THEMIS_ERR_SHAPE (-2)     /* a count or size is out of range            */
+#define THEMIS_ERR_BATCH (-3)     /* batch list not strictly increasing in 1..1024 */
+#define THEMIS_ERR_RANGE (-4)     /* cost or tick range exceeds the limits above */
+#define THEMIS_ERR_WORKSPACE (-5) /* workspace missing, misaligned or too small */
+#define THEMIS_ERR_LAUNCH (-6)    /* the HIP runtime refused a launch           */
+
+/* per-instance status written to d_status */
+#define THEMIS_SOLVED 0
+#define THEMIS_INFEASIBLE 1 /* no assignment meets both constraints            */
+#define THEMIS_INVALID 2    /* input out of range, see below                   */
+#define THEMIS_INTERNAL 3   /* reconstruction failed; never expected           */
+
+/*
+ * The search space shared by every instance of a call.
+ *
+ * An instance is THEMIS_INVALID when lambda is outside 1..THEMIS_VALUE_MAX,
+ * slo_us is outside 0..slo_max_us, any of a,k,q is outside
+ * 0..THEMIS_VALUE_MAX, o is outside 1..THEMIS_VALUE_MAX (so every stage takes
+ * at least one tick), p < 1, or (vertical) a given replica count is outside
+ * 1..r_max.
+ */
+typedef struct themis_problem {
+    int32_t n_inst;     /* N >= 1 instances                                    */
+    int32_t n_stage;    /* S >= 1 models per pipeline                          */
+    int32_t c_max;      /* cores per replica range over 1..c_max               */
+    int32_t n_batch;    /* 1..THEMIS_MAX_BATCH                                 */
+    int32_t batch_sizes[THEMIS_MAX_BATCH]; /* strictly increasing, 1..1024     */
+    int32_t r_max;      /* replicas range over 1..r_max (vertical: bound on r_fixed) */
+    int32_t tick_us;    /* grid resolution, >= 1                               */
+    int32_t slo_max_us; /* caller's bound on every slo_us entry, >= 0          */
+    int32_t coef_shared;/* 1: d_coef is [S][5]; 0: [N][S][5]; order a,k,q,p,o  */
+    int32_t reserved[4];/* must be zero                                        */
+} themis_problem_t;
+
+/* Library version, major*100 + minor. */
+int themis_version(void);
+
+/*
+ * Check a problem description on the host.  Returns THEMIS_OK or the
+ * THEMIS_ERR_* the solve calls would return for it.
+ */
+int themis_check_problem(const themis_problem_t *p);
+
+/*
+ * Bytes of device workspace the solve and stage calls need for `p`
+ * (0 if `p` is not acceptable).  The workspace holds the candidate tables
+ * (Section 4.4, the per-candidate l, q, h evaluation hoisted out of the
+ * budget loop), the DP rows of every model, and one word per instance.
+ * It must be 256-byte aligned.  Contents need not be initialised.
+ */
+size_t themis_workspace_bytes(const themis_problem_t *p);
+
+/*
+ * Joint horizontal+vertical solve (Eq. 6 with n_s derived per candidate).
+ *   d_coef    int32, [S][5] or [N][S][5] per coef_shared
+ *   d_lambda  int32 [N]   requests per second
+ *   d_slo_us  int32 [N]
+ *   d_status  int32 [N]   THEMIS_SOLVED / INFEASIBLE / INVALID
+ *   d_cost    int32 [N]   total cores, -1 unless solved
+ *   d_ticks   int32 [N]   total latency in ticks, -1 unless solved
+ *   d_cfg     int32 [N][S][3] = (c, b, n) per model, zeros unless solved
+ * Runs the three stages below back to back on `stream`.
+ */
+int themis_solve_joint(const themis_problem_t *p, const int32_t *d_coef,
+                       const int32_t *d_lambda, const int32_t *d_slo_us,
+                       int32_t *d_status, int32_t *d_cost, int32_t *d_ticks,
+                       int32_t *d_cfg, void *d_workspace, size_t workspace_bytes,
+                       void *stream);
+
+/*
+ * Vertical-only solve (Algorithm 1): replicas are given, d_r_fixed int32
+ * [N][S], every entry in 1..r_max; cores and batch are chosen; cost is
+ * r_fixed*c per model.  Other arguments as for themis_solve_joint.
+ */
+int themis_solve_vertical(const themis_problem_t *p, const int32_t *d_coef,
+                          const int32_t *d_lambda, const int32_t *d_slo_us,
+                          const int32_t *d_r_fixed,
+                          int32_t *d_status, int32_t *d_cost, int32_t *d_ticks,
+                          int32_t *d_cfg, void *d_workspace, size_t workspace_bytes,
+                          void *stream);
+
+/*
+ * Stage 1 alone: evaluate every candidate of every model of every instance
+ * (the "calculate l, q, h" step of Algorithms 1 and 2, done once instead of
+ * once per budget cell) into the workspace.  d_r_fixed NULL = joint.
+ */
+int themis_stage_candidates(const themis_problem_t *p, const int32_t *d_coef,
+                            const int32_t *d_lambda, const int32_t *d_slo_us,
+                            const int32_t *d_r_fixed, void *d_workspace,
+                            size_t workspace_bytes, void *stream);
+
+/*
+ * Stage 2 alone: the min-plus recurrence over the budget grid,
+ *   f[S][t] = 0,  f[s][t] = min over candidates k with lt <= t of
+ *                           cost[s][k] + f[s+1][t - lt[s][k]],
+ * for the tables stage 1 left in the workspace (Section 4.4: add the models
+ * one at a time and split each budget between the current model and the
+ * rest).  Leaves every row f[s][0..T] in the workspace.
+ */
+int themis_stage_minplus(const themis_problem_t *p, void *d_workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
+ * Stage 3 alone: answer selection (least cost, then least ticks) and forward
+ * reconstruction of the per-model choices from the rows of stage 2
+ * (the scan and the recursive read-out that follow Algorithm 1's main loop).
+ */
+int themis_stage_backtrack(const themis_problem_t *p, int32_t *d_status,
+                           int32_t *d_cost, int32_t *d_ticks, int32_t *d_cfg,
+                           void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Copy stage 1's tables out of the workspace for inspection:
+ * d_lt, d_cost int32 [N][S][K], K = c_max*n_batch; infeasible entries are -1
+ * in both.  The replica count of a feasible entry is cost / c.
+ */
+int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
+                             size_t workspace_bytes, int32_t *d_lt, int32_t *d_cost,
+                             void *stream);
+
+/*
+ * Number of min-plus relaxations stage 2 executes for the tables currently
+ * in the workspace, summed over all instances, written to d_count[0]
+ * (uint64): for every valid instance, model and feasible candidate,
+ * T + 1 - lt.  For throughput accounting only.
+ */
+int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
+                             size_t workspace_bytes, unsigned long long *d_count,
+                             void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THEMIS_H */

@@ -1,0 +1,207 @@
+// Stage 1: candidate tables.
+//
+// Algorithms 1 and 2 (Section 4.4) recompute a candidate's latency l, queueing
+// delay q and throughput h inside the budget loop although none of them depends
+// on the budget.  This kernel evaluates each (model, cores, batch) candidate of
+// each instance exactly once and writes its latency in grid ticks and its cost
+// (replicas * cores) to HBM, candidate index fastest so that a wavefront writes
+// 256 contiguous bytes per table.
+//
+// Integer model (microseconds, all roundings upward), after Eq. 1, Eq. 4 and
+// the throughput constraint of Eq. 6:
+//   proc  = ceil((a + k b + q b^2) / min(c,p)) + o
+//   n     = ceil(lambda proc / (b 1e6))   joint,  or the given replicas
+//   queue = ceil((b-1) 1e6 n / lambda)
+//   lt    = ceil((proc + queue) / tick),  cost = n c
+// A candidate is dropped (lt = cost = -1) when n exceeds r_max, when the given
+// replicas cannot carry lambda, or when lt exceeds the instance's budget T.
+#include "themis_internal.h"
+
+namespace themis {
+namespace {
+
+// floor(n / d) for n < 2^53, 1 <= d < 2^32, quotient < 2^32.
+// A double-precision estimate (exact conversion, reciprocal refined by one
+// Newton step) is corrected by exact 64-bit integer arithmetic, so the result
+// does not depend on how the estimate rounds.  *rem receives n - q*d.
+__device__ __forceinline__ uint32_t floor_div_u64(uint64_t n, uint32_t d, uint64_t* rem)
+{
+    double dd = (double)d;
+    double r = __builtin_amdgcn_rcp(dd);
+    r = __builtin_fma(__builtin_fma(-dd, r, 1.0), r, r);
+    uint64_t q = (uint64_t)((double)n * r);
+    uint64_t prod = q * (uint64_t)d;
+    while (prod > n) { --q; prod -= d; }
+    while (n - prod >= d) { ++q; prod += d; }
+    *rem = n - prod;
+    return (uint32_t)q;
+}
+
+__device__ __forceinline__ uint32_t ceil_div_u64(uint64_t n, uint32_t d)
+{
+    uint64_t rem;
+    uint32_t q = floor_div_u64(n, d, &rem);
+    return q + (rem != 0);
+}
+
+struct Cand {
+    int32_t lt, cost;
+};
+
+// r_given <= 0: derive the replica count (joint); otherwise use it (vertical).
+__device__ __forceinline__ Cand eval_candidate(uint32_t a, uint32_t k, uint32_t q,
+                                               uint32_t p, uint32_t o, uint32_t lambda,
+                                               uint32_t slo_us, uint32_t T, uint32_t tick,
+                                               uint32_t c, uint32_t b, uint32_t r_max,
+                                               int32_t r_given)
+{
+    const Cand none{-1, -1};
+    // Anything whose latency exceeds slo_us also exceeds T ticks, so the tests
+    // against slo_us below only cut candidates that lt > T would cut anyway;
+    // they keep every later quotient inside 32 bits.
+    if (o > slo_us) return none;
+    uint64_t num = (uint64_t)a + (uint64_t)k * b + (uint64_t)q * b * b;
+    uint32_t d = c < p ? c : p;
+    if (num > (uint64_t)(slo_us - o) * d) return none;      // proc > slo_us
+    uint32_t proc = ceil_div_u64(num, d) + o;                // <= slo_us
+    uint64_t lp = (uint64_t)lambda * proc;                   // < 2^51
+    uint32_t M = b * 1000000u;                               // < 2^30
+    uint32_t n;
+    if (r_given <= 0) {
+        if (lp > (uint64_t)r_max * M) return none;           // needs > r_max replicas
+        n = ceil_div_u64(lp, M);
+        if (n < 1) n = 1;
+    } else {
+        n = (uint32_t)r_given;
+        if (lp > (uint64_t)n * M) return none;               // throughput too low
+    }
+    uint64_t qn = (uint64_t)(b - 1) * 1000000u * n;          // < 2^45
+    if (qn > (uint64_t)(slo_us - proc) * lambda) return none; // proc + queue > slo_us
+    uint32_t lat = proc + ceil_div_u64(qn, lambda);          // <= slo_us < 2^31
+    uint32_t lt = (lat + tick - 1) / tick;
+    if (lt > T) return none;
+    return Cand{(int32_t)lt, (int32_t)(n * c)};
+}
+
+__device__ __forceinline__ bool in_range(int32_t v, int32_t lo, int32_t hi)
+{
+    return v >= lo && v <= hi;
+}
+
+// Input check, one thread per instance: tmeta[i] = budget T in ticks, or -1
+// when any input of the instance is out of range.
+__global__ __launch_bounds__(256) void k1_validate(
+    const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
+    const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
+    int32_t* __restrict__ tmeta, uint32_t N, uint32_t S, int32_t r_max, uint32_t tick,
+    int32_t slo_max, int coef_shared)
+{
+    uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= N) return;
+    int32_t lam = lambda[i], slo = slo_us[i];
+    const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5);
+    bool ok = in_range(lam, 1, THEMIS_VALUE_MAX) && in_range(slo, 0, slo_max);
+    for (uint32_t z = 0; z < S; ++z) {
+        const int32_t* cz = cf + z * 5;
+        ok = ok && in_range(cz[0], 0, THEMIS_VALUE_MAX) && in_range(cz[1], 0, THEMIS_VALUE_MAX) &&
+             in_range(cz[2], 0, THEMIS_VALUE_MAX) && cz[3] >= 1 &&
+             in_range(cz[4], 1, THEMIS_VALUE_MAX);
+        if (r_fixed) ok = ok && in_range(r_fixed[(size_t)i * S + z], 1, r_max);
+    }
+    tmeta[i] = ok ? (int32_t)((uint32_t)slo / tick) : -1;
+}
+
+// One thread per candidate, flat index over [N][S][K].
+__global__ __launch_bounds__(256) void k1_candidates(
+    const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
+    const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
+    const int32_t* __restrict__ tmeta, int32_t* __restrict__ lt_tab,
+    int32_t* __restrict__ cost_tab, BatchList bl, uint32_t N, uint32_t S, uint32_t K,
+    uint32_t r_max, uint32_t tick, int coef_shared)
+{
+    uint32_t g = blockIdx.x * 256u + threadIdx.x;
+    uint32_t total = N * S * K;
+    if (g >= total) return;
+    uint32_t row = g / K, kk = g - row * K;
+    uint32_t i = row / S, s = row - i * S;
+
+    int32_t T = tmeta[i];
+    Cand cd{-1, -1};
+    if (T >= 0) {
+        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
+        uint32_t c = kk / (uint32_t)bl.n + 1, j = kk % (uint32_t)bl.n;
+        cd = eval_candidate(cf[0], cf[1], cf[2], cf[3], cf[4], lambda[i], slo_us[i],
+                            (uint32_t)T, tick, c, bl.b[j], r_max,
+                            r_fixed ? r_fixed[(size_t)i * S + s] : 0);
+    }
+    lt_tab[g] = cd.lt;
+    cost_tab[g] = cd.cost;
+}
+
+__global__ void k_zero64(unsigned long long* p) { *p = 0ull; }
+
+// Sum over valid instances, models and feasible candidates of (T + 1 - lt).
+__global__ __launch_bounds__(256) void k_count_relax(const int32_t* __restrict__ lt_tab,
+                                                     const int32_t* __restrict__ tmeta,
+                                                     unsigned long long* __restrict__ out,
+                                                     uint32_t N, uint32_t SK)
+{
+    __shared__ unsigned long long part[256];
+    unsigned long long acc = 0;
+    for (uint32_t i = blockIdx.x; i < N; i += gridDim.x) {
+        int32_t T = tmeta[i];
+        if (T < 0) continue;
+        for (uint32_t e = threadIdx.x; e < SK; e += 256) {
+            int32_t lt = lt_tab[(size_t)i * SK + e];
+            if (lt >= 0) acc += (unsigned long long)(T + 1 - lt);
+        }
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) atomicAdd(out, part[0]);
+}
+
+}  // namespace
+
+hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
+                             const int32_t* d_coef, const int32_t* d_lambda,
+                             const int32_t* d_slo_us, const int32_t* d_r_fixed,
+                             char* ws, hipStream_t st)
+{
+    BatchList bl{};
+    bl.n = p.n_batch;
+    for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
+    int32_t* tmeta = (int32_t*)(ws + L.tmeta_off);
+    hipLaunchKernelGGL(k1_validate, dim3((L.N + 255) / 256), dim3(256), 0, st, d_coef,
+                       d_lambda, d_slo_us, d_r_fixed, tmeta, (uint32_t)L.N, (uint32_t)L.S,
+                       p.r_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    uint32_t total = (uint32_t)L.N * L.S * L.K;
+    uint32_t blocks = (total + 255u) / 256u;
+    hipLaunchKernelGGL(k1_candidates, dim3(blocks), dim3(256), 0, st, d_coef, d_lambda,
+                       d_slo_us, d_r_fixed, (const int32_t*)tmeta,
+                       (int32_t*)(ws + L.lt_off), (int32_t*)(ws + L.cost_off), bl,
+                       (uint32_t)L.N, (uint32_t)L.S, (uint32_t)L.K, (uint32_t)p.r_max,
+                       (uint32_t)p.tick_us, p.coef_shared);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_relaxations(const Layout& L, const char* ws,
+                                    unsigned long long* d_count, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_zero64, dim3(1), dim3(1), 0, st, d_count);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    uint32_t blocks = (uint32_t)(L.N < 4096 ? L.N : 4096);
+    hipLaunchKernelGGL(k_count_relax, dim3(blocks), dim3(256), 0, st,
+                       (const int32_t*)(ws + L.lt_off), (const int32_t*)(ws + L.tmeta_off),
+                       d_count, (uint32_t)L.N, (uint32_t)(L.S * L.K));
+    return hipGetLastError();
+}
+
+}  // namespace themis

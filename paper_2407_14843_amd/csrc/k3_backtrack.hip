@@ -1,0 +1,136 @@
+// Stage 3: answer selection and forward reconstruction.
+//
+// After Algorithm 1's main loop the paper scans the budgets upward and keeps a
+// strictly smaller total (least cost, then least latency), then reads the
+// per-model choices back out of its tables.  Here the rows f[s][0..T] of the
+// suffix recurrence are in HBM.  f[0][.] never increases with t, so the least
+// cost is f[0][T] and the least latency is the first t that attains it.  From
+// there the choices are rebuilt forward: at model s with t ticks left, take the
+// first candidate k (cores ascending, then batch ascending) with
+//     cost[s][k] + f[s+1][t - lt[s][k]] == f[s][t],
+// which yields the lexicographically smallest optimal assignment, model 0 most
+// significant.  One wavefront per instance: the 64 lanes test 64 candidates at
+// a time and a ballot picks the first hit.
+#include "themis_internal.h"
+
+namespace themis {
+namespace {
+
+__global__ __launch_bounds__(256) void k3_backtrack(
+    const int32_t* __restrict__ lt_tab, const int32_t* __restrict__ cost_tab,
+    const int32_t* __restrict__ tmeta, const uint16_t* __restrict__ frow,
+    int32_t* __restrict__ status, int32_t* __restrict__ cost_out,
+    int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg, BatchList bl, int N, int S,
+    int K, int row_stride)
+{
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= N) return;
+
+    int32_t* my_cfg = cfg + (size_t)i * S * 3;
+
+    const int T = tmeta[i];
+    const uint16_t* row0 = frow + (size_t)i * S * row_stride;
+    uint32_t best = F_INF;
+    if (T >= 0) best = row0[T];
+    if (T < 0 || best >= F_INF) {
+        for (int x = lane; x < S * 3; x += 64) my_cfg[x] = 0;
+        if (lane == 0) {
+            status[i] = T < 0 ? THEMIS_INVALID : THEMIS_INFEASIBLE;
+            cost_out[i] = -1;
+            ticks_out[i] = -1;
+        }
+        return;
+    }
+
+    // first t with f[0][t] == best: 64-ary search on a non-increasing row.
+    // invariant: f[0][hi] == best, and f[0][t] > best for every t < lo.
+    int lo = 0, hi = T;
+    while (lo < hi) {
+        const int span = hi - lo;  // probe lo + ceil-ish steps, last lane lands below hi
+        int probe = lo + (int)(((long long)span * lane) >> 6);
+        const bool hit = row0[probe] == best;
+        const unsigned long long m = __ballot(hit);
+        if (m == 0ull) {
+            // even the last probe is above best: answer lies beyond it
+            lo = lo + (int)(((long long)span * 63) >> 6) + 1;
+        } else {
+            const int first = __builtin_ctzll(m);
+            const int new_hi = lo + (int)(((long long)span * first) >> 6);
+            const int new_lo = first == 0 ? lo : lo + (int)(((long long)span * (first - 1)) >> 6) + 1;
+            hi = new_hi;
+            lo = new_lo;
+        }
+    }
+    const int t_star = lo;
+
+    int t = t_star;
+    bool fail = false;
+    for (int s = 0; s < S && !fail; ++s) {
+        const uint32_t target = s == 0 ? best : (uint32_t)row0[(size_t)s * row_stride + t];
+        const uint16_t* next = row0 + (size_t)(s + 1) * row_stride;  // only read if s+1 < S
+        const int32_t* ltp = lt_tab + ((size_t)i * S + s) * K;
+        const int32_t* cop = cost_tab + ((size_t)i * S + s) * K;
+        int found_k = -1, found_lt = 0, found_cost = 0;
+        for (int k0 = 0; k0 < K; k0 += 64) {
+            const int k = k0 + lane;
+            bool hit = false;
+            int lt = 0, co = 0;
+            if (k < K) {
+                lt = ltp[k];
+                co = cop[k];
+                if (lt >= 0 && lt <= t) {
+                    const uint32_t rest = (s + 1 < S) ? (uint32_t)next[t - lt] : 0u;
+                    hit = rest < F_INF && (uint32_t)co + rest == target;
+                }
+            }
+            const unsigned long long m = __ballot(hit);
+            if (m != 0ull) {
+                const int src = __builtin_ctzll(m);
+                found_k = k0 + src;
+                found_lt = __shfl(lt, src, 64);
+                found_cost = __shfl(co, src, 64);
+                break;
+            }
+        }
+        if (found_k < 0) {
+            fail = true;
+            break;
+        }
+        if (lane == 0) {
+            const int c = found_k / bl.n + 1;
+            my_cfg[3 * s + 0] = c;
+            my_cfg[3 * s + 1] = bl.b[found_k % bl.n];
+            my_cfg[3 * s + 2] = found_cost / c;
+        }
+        t -= found_lt;
+    }
+    if (t != 0) fail = true;  // the optimum at t_star uses exactly t_star ticks
+
+    if (lane == 0) {
+        // lane 0 wrote the choices above, so it also takes them back
+        if (fail)
+            for (int x = 0; x < S * 3; ++x) my_cfg[x] = 0;
+        status[i] = fail ? THEMIS_INTERNAL : THEMIS_SOLVED;
+        cost_out[i] = fail ? -1 : (int32_t)best;
+        ticks_out[i] = fail ? -1 : t_star;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t* d_status,
+                            int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg, char* ws,
+                            hipStream_t st)
+{
+    BatchList bl{};
+    bl.n = p.n_batch;
+    for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
+    hipLaunchKernelGGL(k3_backtrack, dim3((L.N + 3) / 4), dim3(256), 0, st,
+                       (const int32_t*)(ws + L.lt_off), (const int32_t*)(ws + L.cost_off),
+                       (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
+                       d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.K, L.row_stride);
+    return hipGetLastError();
+}
+
+}  // namespace themis

@@ -1,0 +1,173 @@
+// Host side of the C ABI declared in include/themis.h: argument checks and
+// launches.  No allocation, no synchronisation, no state.
+#include "themis_internal.h"
+
+using namespace themis;
+
+namespace {
+
+int check(const themis_problem_t* p)
+{
+    if (!p) return THEMIS_ERR_NULL;
+    if (p->n_inst < 1 || p->n_stage < 1 || p->c_max < 1 || p->r_max < 1 || p->tick_us < 1 ||
+        p->slo_max_us < 0 || (p->coef_shared != 0 && p->coef_shared != 1))
+        return THEMIS_ERR_SHAPE;
+    for (int z = 0; z < 4; ++z)
+        if (p->reserved[z] != 0) return THEMIS_ERR_SHAPE;
+    if (p->n_batch < 1 || p->n_batch > THEMIS_MAX_BATCH) return THEMIS_ERR_BATCH;
+    for (int j = 0; j < p->n_batch; ++j) {
+        if (p->batch_sizes[j] < 1 || p->batch_sizes[j] > THEMIS_MAX_BATCH_SIZE)
+            return THEMIS_ERR_BATCH;
+        if (j > 0 && p->batch_sizes[j] <= p->batch_sizes[j - 1]) return THEMIS_ERR_BATCH;
+    }
+    // 16-bit DP values: the largest total must stay below the "none" marker
+    long long cost_bound = (long long)p->n_stage * p->r_max * p->c_max;
+    if (p->c_max > THEMIS_COST_LIMIT || p->r_max > THEMIS_COST_LIMIT ||
+        cost_bound > THEMIS_COST_LIMIT)
+        return THEMIS_ERR_RANGE;
+    if (p->slo_max_us / p->tick_us > THEMIS_MAX_TICKS) return THEMIS_ERR_RANGE;
+    // flat candidate index is 32-bit
+    long long nsk = (long long)p->n_inst * p->n_stage * p->c_max * p->n_batch;
+    if (nsk >= (1ll << 31)) return THEMIS_ERR_SHAPE;
+    return THEMIS_OK;
+}
+
+int check_ws(const themis_problem_t* p, const void* ws, size_t bytes, Layout* L)
+{
+    int rc = check(p);
+    if (rc != THEMIS_OK) return rc;
+    *L = make_layout(*p);
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || bytes < L->total)
+        return THEMIS_ERR_WORKSPACE;
+    return THEMIS_OK;
+}
+
+int solve(const themis_problem_t* p, const int32_t* d_coef, const int32_t* d_lambda,
+          const int32_t* d_slo_us, const int32_t* d_r_fixed, int32_t* d_status,
+          int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg, void* ws, size_t bytes,
+          void* stream)
+{
+    if (!d_coef || !d_lambda || !d_slo_us || !d_status || !d_cost || !d_ticks || !d_cfg)
+        return THEMIS_ERR_NULL;
+    Layout L;
+    int rc = check_ws(p, ws, bytes, &L);
+    if (rc != THEMIS_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* w = static_cast<char*>(ws);
+    if (launch_candidates(*p, L, d_coef, d_lambda, d_slo_us, d_r_fixed, w, st) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    if (launch_minplus(*p, L, w, st) != hipSuccess) return THEMIS_ERR_LAUNCH;
+    if (launch_backtrack(*p, L, d_status, d_cost, d_ticks, d_cfg, w, st) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    return THEMIS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int themis_version(void) { return 100; }
+
+int themis_check_problem(const themis_problem_t* p) { return check(p); }
+
+size_t themis_workspace_bytes(const themis_problem_t* p)
+{
+    if (check(p) != THEMIS_OK) return 0;
+    return make_layout(*p).total;
+}
+
+int themis_solve_joint(const themis_problem_t* p, const int32_t* d_coef,
+                       const int32_t* d_lambda, const int32_t* d_slo_us, int32_t* d_status,
+                       int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg, void* d_workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    return solve(p, d_coef, d_lambda, d_slo_us, nullptr, d_status, d_cost, d_ticks, d_cfg,
+                 d_workspace, workspace_bytes, stream);
+}
+
+int themis_solve_vertical(const themis_problem_t* p, const int32_t* d_coef,
+                          const int32_t* d_lambda, const int32_t* d_slo_us,
+                          const int32_t* d_r_fixed, int32_t* d_status, int32_t* d_cost,
+                          int32_t* d_ticks, int32_t* d_cfg, void* d_workspace,
+                          size_t workspace_bytes, void* stream)
+{
+    if (!d_r_fixed) return THEMIS_ERR_NULL;
+    return solve(p, d_coef, d_lambda, d_slo_us, d_r_fixed, d_status, d_cost, d_ticks, d_cfg,
+                 d_workspace, workspace_bytes, stream);
+}
+
+int themis_stage_candidates(const themis_problem_t* p, const int32_t* d_coef,
+                            const int32_t* d_lambda, const int32_t* d_slo_us,
+                            const int32_t* d_r_fixed, void* d_workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    if (!d_coef || !d_lambda || !d_slo_us) return THEMIS_ERR_NULL;
+    Layout L;
+    int rc = check_ws(p, d_workspace, workspace_bytes, &L);
+    if (rc != THEMIS_OK) return rc;
+    return launch_candidates(*p, L, d_coef, d_lambda, d_slo_us, d_r_fixed,
+                             static_cast<char*>(d_workspace),
+                             static_cast<hipStream_t>(stream)) == hipSuccess
+               ? THEMIS_OK
+               : THEMIS_ERR_LAUNCH;
+}
+
+int themis_stage_minplus(const themis_problem_t* p, void* d_workspace, size_t workspace_bytes,
+                         void* stream)
+{
+    Layout L;
+    int rc = check_ws(p, d_workspace, workspace_bytes, &L);
+    if (rc != THEMIS_OK) return rc;
+    return launch_minplus(*p, L, static_cast<char*>(d_workspace),
+                          static_cast<hipStream_t>(stream)) == hipSuccess
+               ? THEMIS_OK
+               : THEMIS_ERR_LAUNCH;
+}
+
+int themis_stage_backtrack(const themis_problem_t* p, int32_t* d_status, int32_t* d_cost,
+                           int32_t* d_ticks, int32_t* d_cfg, void* d_workspace,
+                           size_t workspace_bytes, void* stream)
+{
+    if (!d_status || !d_cost || !d_ticks || !d_cfg) return THEMIS_ERR_NULL;
+    Layout L;
+    int rc = check_ws(p, d_workspace, workspace_bytes, &L);
+    if (rc != THEMIS_OK) return rc;
+    return launch_backtrack(*p, L, d_status, d_cost, d_ticks, d_cfg,
+                            static_cast<char*>(d_workspace),
+                            static_cast<hipStream_t>(stream)) == hipSuccess
+               ? THEMIS_OK
+               : THEMIS_ERR_LAUNCH;
+}
+
+int themis_export_candidates(const themis_problem_t* p, const void* d_workspace,
+                             size_t workspace_bytes, int32_t* d_lt, int32_t* d_cost,
+                             void* stream)
+{
+    if (!d_lt || !d_cost) return THEMIS_ERR_NULL;
+    Layout L;
+    int rc = check_ws(p, d_workspace, workspace_bytes, &L);
+    if (rc != THEMIS_OK) return rc;
+    const char* w = static_cast<const char*>(d_workspace);
+    size_t bytes = (size_t)L.N * L.S * L.K * sizeof(int32_t);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(d_lt, w + L.lt_off, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    if (hipMemcpyAsync(d_cost, w + L.cost_off, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    return THEMIS_OK;
+}
+
+int themis_count_relaxations(const themis_problem_t* p, const void* d_workspace,
+                             size_t workspace_bytes, unsigned long long* d_count, void* stream)
+{
+    if (!d_count) return THEMIS_ERR_NULL;
+    Layout L;
+    int rc = check_ws(p, d_workspace, workspace_bytes, &L);
+    if (rc != THEMIS_OK) return rc;
+    return launch_count_relaxations(L, static_cast<const char*>(d_workspace), d_count,
+                                    static_cast<hipStream_t>(stream)) == hipSuccess
+               ? THEMIS_OK
+               : THEMIS_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,99 @@
+"""Host-side checks of the C ABI: the library loads, exports what the header
+declares, and rejects bad problem descriptions without touching a GPU."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "themis.h")
+
+
+@pytest.fixture(scope="module")
+def T():
+    from paper_2407_14843_amd import themis
+    if not os.path.exists(themis.LIB_PATH):
+        from paper_2407_14843_amd import build
+        build.build()
+    return themis
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(themis_[a-z_]+)\s*\(", src)))
+
+
+def test_exports_match_header(T):
+    names = _declared_functions()
+    assert len(names) >= 8
+    lib = ctypes.CDLL(T.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in themis.h but not exported"
+    assert sorted(T.EXPORTS) == names
+
+
+def test_struct_size_matches_header(T):
+    # 4 + 16 + 4 + 4 int32 fields
+    assert ctypes.sizeof(T.ThemisProblem) == 4 * (4 + 16 + 4 + 4)
+
+
+def test_version(T):
+    assert T.lib().themis_version() >= 100
+
+
+def _good(T):
+    return T.make_problem(64, 3, 8, [1, 2, 4, 8, 16], 8, 1000, 300_000)
+
+
+def test_check_problem_accepts_good(T):
+    p = _good(T)
+    assert T.check_problem(p) == T.OK
+    assert T.workspace_bytes(p) > 64 * 3 * 40 * 8
+
+
+@pytest.mark.parametrize("mutate,code", [
+    (lambda p: setattr(p, "n_inst", 0), "ERR_SHAPE"),
+    (lambda p: setattr(p, "n_stage", 0), "ERR_SHAPE"),
+    (lambda p: setattr(p, "c_max", 0), "ERR_SHAPE"),
+    (lambda p: setattr(p, "tick_us", 0), "ERR_SHAPE"),
+    (lambda p: setattr(p, "slo_max_us", -1), "ERR_SHAPE"),
+    (lambda p: setattr(p, "coef_shared", 2), "ERR_SHAPE"),
+    (lambda p: p.reserved.__setitem__(1, 7), "ERR_SHAPE"),
+    (lambda p: setattr(p, "n_batch", 0), "ERR_BATCH"),
+    (lambda p: setattr(p, "n_batch", 17), "ERR_BATCH"),
+    (lambda p: p.batch_sizes.__setitem__(2, 2), "ERR_BATCH"),       # not increasing
+    (lambda p: p.batch_sizes.__setitem__(4, 2048), "ERR_BATCH"),    # too large
+    (lambda p: p.batch_sizes.__setitem__(0, 0), "ERR_BATCH"),
+    (lambda p: setattr(p, "r_max", 2000), "ERR_RANGE"),             # 3*2000*8 > 32767
+    (lambda p: setattr(p, "tick_us", 1), "ERR_RANGE"),              # 300000 ticks
+    (lambda p: setattr(p, "n_inst", 2**31 // 100), "ERR_SHAPE"),    # flat index overflow
+])
+def test_check_problem_rejects(T, mutate, code):
+    p = _good(T)
+    mutate(p)
+    assert T.check_problem(p) == getattr(T, code)
+    assert T.workspace_bytes(p) == 0
+
+
+def test_null_problem(T):
+    assert T.lib().themis_check_problem(None) == T.ERR_NULL
+    assert T.lib().themis_workspace_bytes(None) == 0
+
+
+def test_limits_are_inclusive(T):
+    p = T.make_problem(1, 1, 1, [1], 32767, 1, 32767)
+    assert T.check_problem(p) == T.OK
+    p = T.make_problem(1, 1, 1, [1], 32767, 1, 32768)
+    assert T.check_problem(p) == T.ERR_RANGE
+    p = T.make_problem(1, 2, 1, [1], 32767, 1, 100)
+    assert T.check_problem(p) == T.ERR_RANGE
+
+
+def test_workspace_grows_with_problem(T):
+    a = T.workspace_bytes(T.make_problem(64, 3, 8, [1, 2], 8, 1000, 300_000))
+    b = T.workspace_bytes(T.make_problem(128, 3, 8, [1, 2], 8, 1000, 300_000))
+    c = T.workspace_bytes(T.make_problem(64, 3, 8, [1, 2], 8, 500, 300_000))
+    assert b > a and c > a and a % 256 == 0
