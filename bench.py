@@ -136,6 +136,30 @@ def cpu_baseline(wl, idx, max_inst):
                       f"{threads} threads, {dt:.2f} s wall"}
 
 
+def lds_probe():
+    """Measure LDS read bandwidth for each read width / alignment; prints one JSON line."""
+    import torch
+    from paper_2407_14843_amd import themis
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    blocks, iters = N_CU * 2 * 4, 2000
+    res = {}
+    for width, mis in ((4, 0), (4, 2), (8, 0), (8, 4), (8, 2), (16, 0), (16, 8), (16, 4), (16, 2)):
+        themis.themis_probe_lds_read(width, mis, 50, blocks, sink, stream)
+        torch.cuda.synchronize()
+        e0, e1 = _events(2)
+        e0.record(stream)
+        themis.themis_probe_lds_read(width, mis, iters, blocks, sink, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        gbs = blocks * 1024 * iters * 4 * width / (ms * 1e-3) / 1e9
+        res[f"b{width * 8}+{mis}"] = {"ms": ms, "GB/s": gbs,
+                                       "bytes_per_clk_per_cu": gbs / N_CU / CLOCK_GHZ}
+    print(json.dumps({"lds_read_probe": res, "blocks": blocks, "threads": 1024, "iters": iters,
+                      "assumed_clock_ghz": CLOCK_GHZ}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,6 +169,8 @@ def main():
     ap.add_argument("--others", action="store_true",
                     help="also time the other numbered workloads (fewer steps)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    ap.add_argument("--lds-probe", action="store_true",
+                    help="only measure LDS read bandwidth (roofline denominator)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this solve runs on one GPU; instances are independent, so N GPUs "
@@ -155,6 +181,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     from paper_2407_14843_amd import themis, workloads as wl
     themis.lib()
+    if a.lds_probe:
+        lds_probe()
+        return
 
     m = run_workload(themis, wl, a.workload, a.steps, a.warmup)
     k2_ms = m["kernel_ms"]["minplus"]

@@ -194,6 +194,17 @@ int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
                              size_t workspace_bytes, unsigned long long *d_count,
                              void *stream);
 
+/*
+ * Measurement aid, not part of the solve: launch a kernel in which every lane
+ * does nothing but conflict-free LDS reads of `width` bytes (4, 8 or 16) at
+ * byte misalignment `misalign` (0, or 2/4/8 where smaller than the width).
+ * One launch reads blocks * 1024 * iters * 4 * width bytes; time it to obtain
+ * the LDS read bandwidth the min-plus stage is priced against.  d_sink is
+ * one uint32 of device memory.  Unsupported combinations: THEMIS_ERR_SHAPE.
+ */
+int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32_t *d_sink,
+                          void *stream);
+
 #ifdef __cplusplus
 }
 #endif

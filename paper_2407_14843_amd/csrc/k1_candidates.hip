@@ -4,8 +4,8 @@
 // delay q and throughput h inside the budget loop although none of them depends
 // on the budget.  This kernel evaluates each (model, cores, batch) candidate of
 // each instance exactly once and writes its latency in grid ticks and its cost
-// (replicas * cores) to HBM, candidate index fastest so that a wavefront writes
-// 256 contiguous bytes per table.
+// (replicas * cores) to HBM as one 8-byte entry, candidate index fastest, so
+// that a wavefront writes 512 contiguous bytes.
 //
 // Integer model (microseconds, all roundings upward), after Eq. 1, Eq. 4 and
 // the throughput constraint of Eq. 6:
@@ -88,60 +88,96 @@ __device__ __forceinline__ bool in_range(int32_t v, int32_t lo, int32_t hi)
     return v >= lo && v <= hi;
 }
 
-// Input check, one thread per instance: tmeta[i] = budget T in ticks, or -1
-// when any input of the instance is out of range.
+// Input check and work classification, one thread per instance:
+// tmeta[i] = budget T in ticks, or -1 when any input of the instance is out of
+// range; valid instances are appended to the list of their work class.  Lanes
+// of a wavefront that fall into the same class share one atomic.
 __global__ __launch_bounds__(256) void k1_validate(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
-    int32_t* __restrict__ tmeta, uint32_t N, uint32_t S, int32_t r_max, uint32_t tick,
-    int32_t slo_max, int coef_shared)
+    int32_t* __restrict__ tmeta, int32_t* __restrict__ order, int32_t* __restrict__ ctrl,
+    uint32_t N, uint32_t S, int32_t r_max, uint32_t tick, int32_t slo_max, int coef_shared)
 {
     uint32_t i = blockIdx.x * 256u + threadIdx.x;
-    if (i >= N) return;
-    int32_t lam = lambda[i], slo = slo_us[i];
-    const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5);
-    bool ok = in_range(lam, 1, THEMIS_VALUE_MAX) && in_range(slo, 0, slo_max);
-    for (uint32_t z = 0; z < S; ++z) {
-        const int32_t* cz = cf + z * 5;
-        ok = ok && in_range(cz[0], 0, THEMIS_VALUE_MAX) && in_range(cz[1], 0, THEMIS_VALUE_MAX) &&
-             in_range(cz[2], 0, THEMIS_VALUE_MAX) && cz[3] >= 1 &&
-             in_range(cz[4], 1, THEMIS_VALUE_MAX);
-        if (r_fixed) ok = ok && in_range(r_fixed[(size_t)i * S + z], 1, r_max);
+    int cls = -1;
+    if (i < N) {
+        int32_t lam = lambda[i], slo = slo_us[i];
+        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5);
+        bool ok = in_range(lam, 1, THEMIS_VALUE_MAX) && in_range(slo, 0, slo_max);
+        for (uint32_t z = 0; z < S; ++z) {
+            const int32_t* cz = cf + z * 5;
+            ok = ok && in_range(cz[0], 0, THEMIS_VALUE_MAX) &&
+                 in_range(cz[1], 0, THEMIS_VALUE_MAX) && in_range(cz[2], 0, THEMIS_VALUE_MAX) &&
+                 cz[3] >= 1 && in_range(cz[4], 1, THEMIS_VALUE_MAX);
+            if (r_fixed) ok = ok && in_range(r_fixed[(size_t)i * S + z], 1, r_max);
+        }
+        int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
+        tmeta[i] = T;
+        if (ok) cls = class_of_budget(T);
     }
-    tmeta[i] = ok ? (int32_t)((uint32_t)slo / tick) : -1;
+    const unsigned lane = threadIdx.x & 63u;
+    for (int c = 0; c < N_CLS; ++c) {
+        const unsigned long long m = __ballot(cls == c);
+        if (m == 0ull) continue;
+        int base = 0;
+        const int leader = __builtin_ctzll(m);
+        if ((int)lane == leader) base = atomicAdd(&ctrl[c], __builtin_popcountll(m));
+        base = __shfl(base, leader, 64);
+        if (cls == c)
+            order[(size_t)c * N + base + __builtin_popcountll(m & ((1ull << lane) - 1ull))] = (int32_t)i;
+    }
 }
 
-// One thread per candidate, flat index over [N][S][K].
+// ctrl[0..N_CLS) = instances per class, ctrl[N_CLS..2 N_CLS) = queue cursors
+__global__ void k1_reset_ctrl(int32_t* ctrl)
+{
+    if (threadIdx.x < 2 * N_CLS) ctrl[threadIdx.x] = 0;
+}
+
+// One thread per table entry, flat index over [N][S][Kp]; entries kk >= K pad
+// a row to a multiple of eight and are infeasible.
 __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
-    const int32_t* __restrict__ tmeta, int32_t* __restrict__ lt_tab,
-    int32_t* __restrict__ cost_tab, BatchList bl, uint32_t N, uint32_t S, uint32_t K,
-    uint32_t r_max, uint32_t tick, int coef_shared)
+    const int32_t* __restrict__ tmeta, CandEntry* __restrict__ cand, BatchList bl, uint32_t N,
+    uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, int coef_shared)
 {
     uint32_t g = blockIdx.x * 256u + threadIdx.x;
-    uint32_t total = N * S * K;
+    uint32_t total = N * S * Kp;
     if (g >= total) return;
-    uint32_t row = g / K, kk = g - row * K;
+    uint32_t row = g / Kp, kk = g - row * Kp;
     uint32_t i = row / S, s = row - i * S;
 
     int32_t T = tmeta[i];
     Cand cd{-1, -1};
-    if (T >= 0) {
+    if (T >= 0 && kk < K) {
         const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
         uint32_t c = kk / (uint32_t)bl.n + 1, j = kk % (uint32_t)bl.n;
         cd = eval_candidate(cf[0], cf[1], cf[2], cf[3], cf[4], lambda[i], slo_us[i],
                             (uint32_t)T, tick, c, bl.b[j], r_max,
                             r_fixed ? r_fixed[(size_t)i * S + s] : 0);
     }
-    lt_tab[g] = cd.lt;
-    cost_tab[g] = cd.cost;
+    cand[g] = CandEntry{cd.lt, cd.cost};
 }
 
 __global__ void k_zero64(unsigned long long* p) { *p = 0ull; }
 
+// Split the interleaved table into separate lt / cost arrays [N][S][K].
+__global__ __launch_bounds__(256) void k_export(const CandEntry* __restrict__ cand,
+                                                int32_t* __restrict__ lt,
+                                                int32_t* __restrict__ cost, uint32_t rows,
+                                                uint32_t K, uint32_t Kp)
+{
+    uint32_t g = blockIdx.x * 256u + threadIdx.x;
+    if (g >= rows * K) return;
+    uint32_t row = g / K, kk = g - row * K;
+    CandEntry e = cand[(size_t)row * Kp + kk];
+    lt[g] = e.lt;
+    cost[g] = e.cost;
+}
+
 // Sum over valid instances, models and feasible candidates of (T + 1 - lt).
-__global__ __launch_bounds__(256) void k_count_relax(const int32_t* __restrict__ lt_tab,
+__global__ __launch_bounds__(256) void k_count_relax(const CandEntry* __restrict__ cand,
                                                      const int32_t* __restrict__ tmeta,
                                                      unsigned long long* __restrict__ out,
                                                      uint32_t N, uint32_t SK)
@@ -152,7 +188,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const int32_t* __restrict__
         int32_t T = tmeta[i];
         if (T < 0) continue;
         for (uint32_t e = threadIdx.x; e < SK; e += 256) {
-            int32_t lt = lt_tab[(size_t)i * SK + e];
+            int32_t lt = cand[(size_t)i * SK + e].lt;
             if (lt >= 0) acc += (unsigned long long)(T + 1 - lt);
         }
     }
@@ -176,18 +212,32 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     bl.n = p.n_batch;
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
     int32_t* tmeta = (int32_t*)(ws + L.tmeta_off);
+    int32_t* ctrl = (int32_t*)(ws + L.ctrl_off);
+    hipLaunchKernelGGL(k1_reset_ctrl, dim3(1), dim3(64), 0, st, ctrl);
     hipLaunchKernelGGL(k1_validate, dim3((L.N + 255) / 256), dim3(256), 0, st, d_coef,
-                       d_lambda, d_slo_us, d_r_fixed, tmeta, (uint32_t)L.N, (uint32_t)L.S,
-                       p.r_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared);
+                       d_lambda, d_slo_us, d_r_fixed, tmeta, (int32_t*)(ws + L.order_off), ctrl,
+                       (uint32_t)L.N, (uint32_t)L.S, p.r_max, (uint32_t)p.tick_us,
+                       p.slo_max_us, p.coef_shared);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    uint32_t total = (uint32_t)L.N * L.S * L.K;
+    uint32_t total = (uint32_t)L.N * L.S * L.Kp;
     uint32_t blocks = (total + 255u) / 256u;
     hipLaunchKernelGGL(k1_candidates, dim3(blocks), dim3(256), 0, st, d_coef, d_lambda,
                        d_slo_us, d_r_fixed, (const int32_t*)tmeta,
-                       (int32_t*)(ws + L.lt_off), (int32_t*)(ws + L.cost_off), bl,
-                       (uint32_t)L.N, (uint32_t)L.S, (uint32_t)L.K, (uint32_t)p.r_max,
-                       (uint32_t)p.tick_us, p.coef_shared);
+                       (CandEntry*)(ws + L.cand_off), bl, (uint32_t)L.N, (uint32_t)L.S,
+                       (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us,
+                       p.coef_shared);
+    return hipGetLastError();
+}
+
+hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_lt,
+                                    int32_t* d_cost, hipStream_t st)
+{
+    uint32_t rows = (uint32_t)L.N * L.S;
+    uint32_t blocks = (rows * (uint32_t)L.K + 255u) / 256u;
+    hipLaunchKernelGGL(k_export, dim3(blocks), dim3(256), 0, st,
+                       (const CandEntry*)(ws + L.cand_off), d_lt, d_cost, rows, (uint32_t)L.K,
+                       (uint32_t)L.Kp);
     return hipGetLastError();
 }
 
@@ -199,8 +249,8 @@ hipError_t launch_count_relaxations(const Layout& L, const char* ws,
     if (e != hipSuccess) return e;
     uint32_t blocks = (uint32_t)(L.N < 4096 ? L.N : 4096);
     hipLaunchKernelGGL(k_count_relax, dim3(blocks), dim3(256), 0, st,
-                       (const int32_t*)(ws + L.lt_off), (const int32_t*)(ws + L.tmeta_off),
-                       d_count, (uint32_t)L.N, (uint32_t)(L.S * L.K));
+                       (const CandEntry*)(ws + L.cand_off), (const int32_t*)(ws + L.tmeta_off),
+                       d_count, (uint32_t)L.N, (uint32_t)(L.S * L.Kp));
     return hipGetLastError();
 }
 

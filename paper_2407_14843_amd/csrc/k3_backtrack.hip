@@ -17,11 +17,10 @@ namespace themis {
 namespace {
 
 __global__ __launch_bounds__(256) void k3_backtrack(
-    const int32_t* __restrict__ lt_tab, const int32_t* __restrict__ cost_tab,
-    const int32_t* __restrict__ tmeta, const uint16_t* __restrict__ frow,
+    const CandEntry* __restrict__ cand, const int32_t* __restrict__ tmeta, const uint16_t* __restrict__ frow,
     int32_t* __restrict__ status, int32_t* __restrict__ cost_out,
     int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg, BatchList bl, int N, int S,
-    int K, int row_stride)
+    int K, int Kp, int row_stride)
 {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -69,16 +68,16 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     for (int s = 0; s < S && !fail; ++s) {
         const uint32_t target = s == 0 ? best : (uint32_t)row0[(size_t)s * row_stride + t];
         const uint16_t* next = row0 + (size_t)(s + 1) * row_stride;  // only read if s+1 < S
-        const int32_t* ltp = lt_tab + ((size_t)i * S + s) * K;
-        const int32_t* cop = cost_tab + ((size_t)i * S + s) * K;
+        const CandEntry* ep = cand + ((size_t)i * S + s) * Kp;
         int found_k = -1, found_lt = 0, found_cost = 0;
         for (int k0 = 0; k0 < K; k0 += 64) {
             const int k = k0 + lane;
             bool hit = false;
             int lt = 0, co = 0;
             if (k < K) {
-                lt = ltp[k];
-                co = cop[k];
+                const CandEntry e = ep[k];
+                lt = e.lt;
+                co = e.cost;
                 if (lt >= 0 && lt <= t) {
                     const uint32_t rest = (s + 1 < S) ? (uint32_t)next[t - lt] : 0u;
                     hit = rest < F_INF && (uint32_t)co + rest == target;
@@ -127,9 +126,9 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
     bl.n = p.n_batch;
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
     hipLaunchKernelGGL(k3_backtrack, dim3((L.N + 3) / 4), dim3(256), 0, st,
-                       (const int32_t*)(ws + L.lt_off), (const int32_t*)(ws + L.cost_off),
-                       (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
-                       d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.K, L.row_stride);
+                       (const CandEntry*)(ws + L.cand_off), (const int32_t*)(ws + L.tmeta_off),
+                       (const uint16_t*)(ws + L.frow_off), d_status, d_cost, d_ticks, d_cfg, bl,
+                       L.N, L.S, L.K, L.Kp, L.row_stride);
     return hipGetLastError();
 }
 

@@ -1,0 +1,91 @@
+// LDS read-bandwidth probe.  Not part of the solve: it measures the figure the
+// min-plus kernel's roofline is priced against.  Every lane of every wavefront
+// streams ds_read instructions of one width and alignment over a 64 KB window,
+// lanes contiguous (conflict-free), and nothing else; the caller times the
+// launch and divides the bytes read by the duration.
+#include "themis_internal.h"
+
+namespace themis {
+namespace {
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int PROBE_THREADS = 1024;
+constexpr int PROBE_LDS = 65536 + 256;
+
+// WIDTH: bytes per lane per read (4, 8 or 16).  MIS: byte offset added to every
+// address (0 = naturally aligned).
+template <int WIDTH, int MIS>
+__global__ __launch_bounds__(PROBE_THREADS) void k_lds_probe(uint32_t* __restrict__ sink,
+                                                             int iters)
+{
+    extern __shared__ uint32_t lds[];
+    for (int x = threadIdx.x; x < PROBE_LDS / 4; x += PROBE_THREADS) lds[x] = x;
+    __syncthreads();
+    // 1024 lanes * WIDTH bytes per sweep; four sweeps 16 KB apart per block of reads
+    const uint32_t addr = (uint32_t)(uintptr_t)lds + (threadIdx.x * WIDTH) % 16384 + MIS;
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        if constexpr (WIDTH == 4) {
+            uint32_t a, b, c, d;
+            asm volatile(
+                "ds_read_b32 %0, %4\n ds_read_b32 %1, %4 offset:16384\n"
+                "ds_read_b32 %2, %4 offset:32768\n ds_read_b32 %3, %4 offset:49152\n"
+                "s_waitcnt lgkmcnt(0)"
+                : "=v"(a), "=v"(b), "=v"(c), "=v"(d) : "v"(addr));
+            acc ^= a ^ b ^ c ^ d;
+        } else if constexpr (WIDTH == 8) {
+            u32x2 a, b, c, d;
+            asm volatile(
+                "ds_read_b64 %0, %4\n ds_read_b64 %1, %4 offset:16384\n"
+                "ds_read_b64 %2, %4 offset:32768\n ds_read_b64 %3, %4 offset:49152\n"
+                "s_waitcnt lgkmcnt(0)"
+                : "=v"(a), "=v"(b), "=v"(c), "=v"(d) : "v"(addr));
+            acc ^= a.x ^ b.x ^ c.x ^ d.x;
+        } else {
+            u32x4 a, b, c, d;
+            asm volatile(
+                "ds_read_b128 %0, %4\n ds_read_b128 %1, %4 offset:16384\n"
+                "ds_read_b128 %2, %4 offset:32768\n ds_read_b128 %3, %4 offset:49152\n"
+                "s_waitcnt lgkmcnt(0)"
+                : "=v"(a), "=v"(b), "=v"(c), "=v"(d) : "v"(addr));
+            acc ^= a.x ^ b.x ^ c.x ^ d.x;
+        }
+    }
+    if (acc == 0x12345678u) sink[0] = acc;  // keeps the reads alive
+}
+
+template <int WIDTH, int MIS>
+hipError_t launch_probe(uint32_t* sink, int iters, int blocks, hipStream_t st)
+{
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_lds_probe<WIDTH, MIS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, PROBE_LDS);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_lds_probe<WIDTH, MIS>), dim3(blocks), dim3(PROBE_THREADS), PROBE_LDS,
+                       st, sink, iters);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// bytes read by one launch: blocks * 1024 lanes * iters * 4 reads * width
+hipError_t launch_lds_probe(int width, int misalign, int iters, int blocks, uint32_t* sink,
+                            hipStream_t st)
+{
+#define PROBE_CASE(W, M) \
+    if (width == W && misalign == M) return launch_probe<W, M>(sink, iters, blocks, st)
+    PROBE_CASE(4, 0);
+    PROBE_CASE(4, 2);
+    PROBE_CASE(8, 0);
+    PROBE_CASE(8, 4);
+    PROBE_CASE(8, 2);
+    PROBE_CASE(16, 0);
+    PROBE_CASE(16, 8);
+    PROBE_CASE(16, 4);
+    PROBE_CASE(16, 2);
+#undef PROBE_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace themis

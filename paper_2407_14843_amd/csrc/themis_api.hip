@@ -27,7 +27,7 @@ int check(const themis_problem_t* p)
         return THEMIS_ERR_RANGE;
     if (p->slo_max_us / p->tick_us > THEMIS_MAX_TICKS) return THEMIS_ERR_RANGE;
     // flat candidate index is 32-bit
-    long long nsk = (long long)p->n_inst * p->n_stage * p->c_max * p->n_batch;
+    long long nsk = (long long)p->n_inst * p->n_stage * ((p->c_max * p->n_batch + 7) / 8 * 8);
     if (nsk >= (1ll << 31)) return THEMIS_ERR_SHAPE;
     return THEMIS_OK;
 }
@@ -147,14 +147,10 @@ int themis_export_candidates(const themis_problem_t* p, const void* d_workspace,
     Layout L;
     int rc = check_ws(p, d_workspace, workspace_bytes, &L);
     if (rc != THEMIS_OK) return rc;
-    const char* w = static_cast<const char*>(d_workspace);
-    size_t bytes = (size_t)L.N * L.S * L.K * sizeof(int32_t);
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(d_lt, w + L.lt_off, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
-        return THEMIS_ERR_LAUNCH;
-    if (hipMemcpyAsync(d_cost, w + L.cost_off, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
-        return THEMIS_ERR_LAUNCH;
-    return THEMIS_OK;
+    return launch_export_candidates(L, static_cast<const char*>(d_workspace), d_lt, d_cost,
+                                    static_cast<hipStream_t>(stream)) == hipSuccess
+               ? THEMIS_OK
+               : THEMIS_ERR_LAUNCH;
 }
 
 int themis_count_relaxations(const themis_problem_t* p, const void* d_workspace,
@@ -168,6 +164,17 @@ int themis_count_relaxations(const themis_problem_t* p, const void* d_workspace,
                                     static_cast<hipStream_t>(stream)) == hipSuccess
                ? THEMIS_OK
                : THEMIS_ERR_LAUNCH;
+}
+
+int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32_t* d_sink,
+                          void* stream)
+{
+    if (!d_sink) return THEMIS_ERR_NULL;
+    if (iters < 1 || blocks < 1 || blocks > 65536) return THEMIS_ERR_SHAPE;
+    hipError_t e = launch_lds_probe(width, misalign, iters, blocks, d_sink,
+                                    static_cast<hipStream_t>(stream));
+    if (e == hipErrorInvalidValue) return THEMIS_ERR_SHAPE;
+    return e == hipSuccess ? THEMIS_OK : THEMIS_ERR_LAUNCH;
 }
 
 }  // extern "C"

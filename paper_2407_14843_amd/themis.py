@@ -25,7 +25,7 @@ EXPORTS = [
     "themis_version", "themis_check_problem", "themis_workspace_bytes",
     "themis_solve_joint", "themis_solve_vertical", "themis_stage_candidates",
     "themis_stage_minplus", "themis_stage_backtrack", "themis_export_candidates",
-    "themis_count_relaxations",
+    "themis_count_relaxations", "themis_probe_lds_read",
 ]
 
 
@@ -72,6 +72,8 @@ def lib():
         L.themis_export_candidates.argtypes = [P, vp, sz, vp, vp, vp]
         L.themis_count_relaxations.restype = ctypes.c_int
         L.themis_count_relaxations.argtypes = [P, vp, sz, vp, vp]
+        L.themis_probe_lds_read.restype = ctypes.c_int
+        L.themis_probe_lds_read.argtypes = [ctypes.c_int] * 4 + [vp, vp]
         _lib = L
     return _lib
 
@@ -175,6 +177,12 @@ def themis_count_relaxations(p, workspace, count, stream=None):
     _chk("themis_count_relaxations", lib().themis_count_relaxations(
         ctypes.byref(p), _dp(workspace, torch.uint8), workspace.numel(),
         _dp(count, torch.int64), _stream(stream)))
+
+
+def themis_probe_lds_read(width, misalign, iters, blocks, sink, stream=None):
+    _chk("themis_probe_lds_read", lib().themis_probe_lds_read(
+        int(width), int(misalign), int(iters), int(blocks), _dp(sink, torch.int32),
+        _stream(stream)))
 
 
 # ---------------------------------------------------------------- conveniences
