@@ -57,6 +57,7 @@ extern "C" {
 
 #define THEMIS_MAX_BATCH 16      /* entries in batch_sizes[]                    */
 #define THEMIS_MAX_BATCH_SIZE 1024
+#define THEMIS_MAX_CANDIDATES 8192 /* c_max*n_batch, rounded up to 8, must not exceed */
 #define THEMIS_VALUE_MAX (1 << 20) /* upper bound on lambda and on a,k,q,o      */
 #define THEMIS_COST_LIMIT 32767  /* n_stage*r_max*c_max must not exceed this    */
 #define THEMIS_MAX_TICKS 32767   /* floor(slo_max_us/tick_us) must not exceed   */

@@ -4,8 +4,8 @@
 // delay q and throughput h inside the budget loop although none of them depends
 // on the budget.  This kernel evaluates each (model, cores, batch) candidate of
 // each instance exactly once and writes its latency in grid ticks and its cost
-// (replicas * cores) to HBM as one 8-byte entry, candidate index fastest, so
-// that a wavefront writes 512 contiguous bytes.
+// (replicas * cores) to HBM, packed into one word, each row ordered by latency
+// bucket so that the min-plus stage can work on prefixes of a row.
 //
 // Integer model (microseconds, all roundings upward), after Eq. 1, Eq. 4 and
 // the throughput constraint of Eq. 6:
@@ -134,50 +134,113 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
     if (threadIdx.x < 2 * N_CLS) ctrl[threadIdx.x] = 0;
 }
 
-// One thread per table entry, flat index over [N][S][Kp]; entries kk >= K pad
-// a row to a multiple of eight and are infeasible.
+// Candidate evaluation plus a counting sort of each row by bucket.
+//
+// A workgroup of 256 threads handles R = 256/G rows ((instance, model) pairs),
+// G threads per row, G = Kp rounded up to a power of two (at most 256; longer
+// rows are walked in steps of G).  Pass 1 evaluates every candidate, parks its
+// (lt, cost) in LDS and counts its bucket; after a prefix sum over the
+// buckets, pass 2 hands every entry a slot inside its bucket's range and
+// writes it to HBM in the two forms the later stages read.  The order inside a bucket is whatever
+// the LDS atomics yield; nothing downstream depends on it.
 __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
-    const int32_t* __restrict__ tmeta, CandEntry* __restrict__ cand, BatchList bl, uint32_t N,
-    uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, int coef_shared)
+    const int32_t* __restrict__ tmeta, StepEntry* __restrict__ step_tab,
+    uint32_t* __restrict__ tag_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
+    uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, int coef_shared,
+    uint32_t G, uint32_t nb, uint32_t nbs)
 {
-    uint32_t g = blockIdx.x * 256u + threadIdx.x;
-    uint32_t total = N * S * Kp;
-    if (g >= total) return;
-    uint32_t row = g / Kp, kk = g - row * Kp;
-    uint32_t i = row / S, s = row - i * S;
+    extern __shared__ uint32_t smem[];
+    const uint32_t R = 256u / G;
+    // per local row: hist[MAX_BUCKETS + 1], cursor[MAX_BUCKETS + 1], then staging[Kp]
+    constexpr uint32_t HB = MAX_BUCKETS + 1;
+    uint32_t* const hist_all = smem;
+    uint32_t* const cur_all = smem + R * HB;
+    uint32_t* const stage_all = smem + 2 * R * HB;
 
-    int32_t T = tmeta[i];
-    Cand cd{-1, -1};
-    if (T >= 0 && kk < K) {
+    const uint32_t rl = threadIdx.x / G, g = threadIdx.x - rl * G;
+    const uint32_t row = blockIdx.x * R + rl;
+    const bool live = row < rows;
+    uint32_t* const hist = hist_all + rl * HB;
+    uint32_t* const cur = cur_all + rl * HB;
+    uint32_t* const stage = stage_all + rl * Kp;
+
+    for (uint32_t x = threadIdx.x; x < 2 * R * HB; x += 256u) smem[x] = 0u;
+    __syncthreads();
+
+    int32_t T = -1;
+    if (live) {
+        const uint32_t i = row / S, s = row - i * S;
+        T = tmeta[i];
         const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
-        uint32_t c = kk / (uint32_t)bl.n + 1, j = kk % (uint32_t)bl.n;
-        cd = eval_candidate(cf[0], cf[1], cf[2], cf[3], cf[4], lambda[i], slo_us[i],
-                            (uint32_t)T, tick, c, bl.b[j], r_max,
-                            r_fixed ? r_fixed[(size_t)i * S + s] : 0);
+        const uint32_t a = cf[0], kc = cf[1], q = cf[2], pcap = cf[3], o = cf[4];
+        const uint32_t lam = lambda[i], slo = slo_us[i];
+        const int32_t rgiven = r_fixed ? r_fixed[(size_t)i * S + s] : 0;
+        for (uint32_t kk = g; kk < Kp; kk += G) {
+            uint32_t w0 = TAG_NONE;  // lt | cost << 16
+            if (T >= 0 && kk < K) {
+                const uint32_t c = kk / (uint32_t)bl.n + 1, j = kk % (uint32_t)bl.n;
+                const Cand cd = eval_candidate(a, kc, q, pcap, o, lam, slo, (uint32_t)T, tick, c,
+                                               bl.b[j], r_max, rgiven);
+                if (cd.lt >= 0) w0 = (uint32_t)cd.lt | ((uint32_t)cd.cost << 16);
+            }
+            stage[kk] = w0;
+            const uint32_t b = w0 == TAG_NONE ? nb : (w0 & 0xFFFFu) >> BUCKET_SHIFT;
+            atomicAdd(&hist[b], 1u);
+        }
     }
-    cand[g] = CandEntry{cd.lt, cd.cost};
+    __syncthreads();
+    if (live) {
+        // exclusive prefix over the buckets; bucket nb (infeasible) comes last
+        for (uint32_t j = g; j <= nb; j += G) {
+            uint32_t c = 0;
+            for (uint32_t b = 0; b < j; ++b) c += hist[b];
+            cur[j] = c;
+            bcum[(size_t)row * nbs + j] = (uint16_t)c;
+        }
+    }
+    __syncthreads();
+    if (live) {
+        // the LDS geometry the min-plus stage will use for this instance
+        const int cls = T >= 0 ? class_of_budget(T) : 0;
+        const int copy_bytes = wide_copy_bytes(CLS_WAVES[cls == NARROW_CLS ? 0 : cls]);
+        for (uint32_t kk = g; kk < Kp; kk += G) {
+            const uint32_t w0 = stage[kk];
+            const bool none = w0 == TAG_NONE;
+            const uint32_t lt = w0 & 0xFFFFu;
+            const uint32_t b = none ? nb : lt >> BUCKET_SHIFT;
+            const uint32_t slot = atomicAdd(&cur[b], 1u);
+            StepEntry se;
+            se.shift = none ? 0u : (cls == NARROW_CLS ? narrow_shift(lt) : wide_shift(lt, copy_bytes));
+            se.cost2 = none ? 0u : (w0 >> 16) * 0x10001u;
+            step_tab[(size_t)row * Kp + slot] = se;
+            tag_tab[(size_t)row * Kp + slot] = lt | (kk << 16);
+        }
+    }
 }
 
 __global__ void k_zero64(unsigned long long* p) { *p = 0ull; }
 
-// Split the interleaved table into separate lt / cost arrays [N][S][K].
-__global__ __launch_bounds__(256) void k_export(const CandEntry* __restrict__ cand,
+// Undo the bucket order: separate lt / cost arrays [N][S][K], index k.
+__global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ step_tab,
+                                                const uint32_t* __restrict__ tag_tab,
                                                 int32_t* __restrict__ lt,
                                                 int32_t* __restrict__ cost, uint32_t rows,
                                                 uint32_t K, uint32_t Kp)
 {
     uint32_t g = blockIdx.x * 256u + threadIdx.x;
-    if (g >= rows * K) return;
-    uint32_t row = g / K, kk = g - row * K;
-    CandEntry e = cand[(size_t)row * Kp + kk];
-    lt[g] = e.lt;
-    cost[g] = e.cost;
+    if (g >= rows * Kp) return;
+    uint32_t row = g / Kp;
+    uint32_t tag = tag_tab[g], k = tag >> 16;
+    if (k >= K) return;  // padding entry
+    const bool none = (tag & 0xFFFFu) == TAG_NONE;
+    lt[(size_t)row * K + k] = none ? -1 : (int32_t)(tag & 0xFFFFu);
+    cost[(size_t)row * K + k] = none ? -1 : (int32_t)(step_tab[g].cost2 & 0xFFFFu);
 }
 
 // Sum over valid instances, models and feasible candidates of (T + 1 - lt).
-__global__ __launch_bounds__(256) void k_count_relax(const CandEntry* __restrict__ cand,
+__global__ __launch_bounds__(256) void k_count_relax(const uint32_t* __restrict__ tag_tab,
                                                      const int32_t* __restrict__ tmeta,
                                                      unsigned long long* __restrict__ out,
                                                      uint32_t N, uint32_t SK)
@@ -188,8 +251,8 @@ __global__ __launch_bounds__(256) void k_count_relax(const CandEntry* __restrict
         int32_t T = tmeta[i];
         if (T < 0) continue;
         for (uint32_t e = threadIdx.x; e < SK; e += 256) {
-            int32_t lt = cand[(size_t)i * SK + e].lt;
-            if (lt >= 0) acc += (unsigned long long)(T + 1 - lt);
+            uint32_t lt = tag_tab[(size_t)i * SK + e] & 0xFFFFu;
+            if (lt != TAG_NONE) acc += (unsigned long long)(T + 1 - (int32_t)lt);
         }
     }
     part[threadIdx.x] = acc;
@@ -220,13 +283,18 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                        p.slo_max_us, p.coef_shared);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    uint32_t total = (uint32_t)L.N * L.S * L.Kp;
-    uint32_t blocks = (total + 255u) / 256u;
-    hipLaunchKernelGGL(k1_candidates, dim3(blocks), dim3(256), 0, st, d_coef, d_lambda,
-                       d_slo_us, d_r_fixed, (const int32_t*)tmeta,
-                       (CandEntry*)(ws + L.cand_off), bl, (uint32_t)L.N, (uint32_t)L.S,
-                       (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us,
-                       p.coef_shared);
+
+    uint32_t G = 64;
+    while (G < 256u && G < (uint32_t)L.Kp) G <<= 1;
+    const uint32_t R = 256u / G;
+    const uint32_t rows = (uint32_t)L.N * L.S;
+    const size_t lds = (size_t)(2 * R * (MAX_BUCKETS + 1) + R * L.Kp) * sizeof(uint32_t);
+    hipLaunchKernelGGL(k1_candidates, dim3((rows + R - 1) / R), dim3(256), lds, st, d_coef,
+                       d_lambda, d_slo_us, d_r_fixed, (const int32_t*)tmeta,
+                       (StepEntry*)(ws + L.step_off), (uint32_t*)(ws + L.tag_off),
+                       (uint16_t*)(ws + L.bcum_off), bl, rows, (uint32_t)L.S, (uint32_t)L.K,
+                       (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us, p.coef_shared, G,
+                       (uint32_t)L.nb, (uint32_t)L.nbs);
     return hipGetLastError();
 }
 
@@ -234,10 +302,10 @@ hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_
                                     int32_t* d_cost, hipStream_t st)
 {
     uint32_t rows = (uint32_t)L.N * L.S;
-    uint32_t blocks = (rows * (uint32_t)L.K + 255u) / 256u;
+    uint32_t blocks = (rows * (uint32_t)L.Kp + 255u) / 256u;
     hipLaunchKernelGGL(k_export, dim3(blocks), dim3(256), 0, st,
-                       (const CandEntry*)(ws + L.cand_off), d_lt, d_cost, rows, (uint32_t)L.K,
-                       (uint32_t)L.Kp);
+                       (const StepEntry*)(ws + L.step_off), (const uint32_t*)(ws + L.tag_off), d_lt,
+                       d_cost, rows, (uint32_t)L.K, (uint32_t)L.Kp);
     return hipGetLastError();
 }
 
@@ -249,7 +317,7 @@ hipError_t launch_count_relaxations(const Layout& L, const char* ws,
     if (e != hipSuccess) return e;
     uint32_t blocks = (uint32_t)(L.N < 4096 ? L.N : 4096);
     hipLaunchKernelGGL(k_count_relax, dim3(blocks), dim3(256), 0, st,
-                       (const CandEntry*)(ws + L.cand_off), (const int32_t*)(ws + L.tmeta_off),
+                       (const uint32_t*)(ws + L.tag_off), (const int32_t*)(ws + L.tmeta_off),
                        d_count, (uint32_t)L.N, (uint32_t)(L.S * L.Kp));
     return hipGetLastError();
 }

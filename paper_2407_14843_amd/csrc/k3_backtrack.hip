@@ -6,21 +6,24 @@
 // suffix recurrence are in HBM.  f[0][.] never increases with t, so the least
 // cost is f[0][T] and the least latency is the first t that attains it.  From
 // there the choices are rebuilt forward: at model s with t ticks left, take the
-// first candidate k (cores ascending, then batch ascending) with
+// candidate with the smallest index k (cores ascending, then batch ascending)
+// among those with
 //     cost[s][k] + f[s+1][t - lt[s][k]] == f[s][t],
 // which yields the lexicographically smallest optimal assignment, model 0 most
-// significant.  One wavefront per instance: the 64 lanes test 64 candidates at
-// a time and a ballot picks the first hit.
+// significant.  One wavefront per instance: the 64 lanes test 64 table entries
+// at a time (the table is ordered by latency bucket, not by k) and a butterfly
+// reduction picks the smallest k.
 #include "themis_internal.h"
 
 namespace themis {
 namespace {
 
 __global__ __launch_bounds__(256) void k3_backtrack(
-    const CandEntry* __restrict__ cand, const int32_t* __restrict__ tmeta, const uint16_t* __restrict__ frow,
-    int32_t* __restrict__ status, int32_t* __restrict__ cost_out,
-    int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg, BatchList bl, int N, int S,
-    int K, int Kp, int row_stride)
+    const StepEntry* __restrict__ step_tab, const uint32_t* __restrict__ tag_tab,
+    const uint16_t* __restrict__ bcum, const int32_t* __restrict__ tmeta,
+    const uint16_t* __restrict__ frow, int32_t* __restrict__ status,
+    int32_t* __restrict__ cost_out, int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg,
+    BatchList bl, int N, int S, int Kp, int nbs, int row_stride)
 {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -46,12 +49,12 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     // invariant: f[0][hi] == best, and f[0][t] > best for every t < lo.
     int lo = 0, hi = T;
     while (lo < hi) {
-        const int span = hi - lo;  // probe lo + ceil-ish steps, last lane lands below hi
-        int probe = lo + (int)(((long long)span * lane) >> 6);
+        const int span = hi - lo;  // probes lo + span*lane/64 all lie below hi
+        const int probe = lo + (int)(((long long)span * lane) >> 6);
         const bool hit = row0[probe] == best;
         const unsigned long long m = __ballot(hit);
         if (m == 0ull) {
-            // even the last probe is above best: answer lies beyond it
+            // even the last probe is above best: the answer lies beyond it
             lo = lo + (int)(((long long)span * 63) >> 6) + 1;
         } else {
             const int first = __builtin_ctzll(m);
@@ -65,37 +68,45 @@ __global__ __launch_bounds__(256) void k3_backtrack(
 
     int t = t_star;
     bool fail = false;
-    for (int s = 0; s < S && !fail; ++s) {
+    for (int s = 0; s < S; ++s) {
         const uint32_t target = s == 0 ? best : (uint32_t)row0[(size_t)s * row_stride + t];
         const uint16_t* next = row0 + (size_t)(s + 1) * row_stride;  // only read if s+1 < S
-        const CandEntry* ep = cand + ((size_t)i * S + s) * Kp;
-        int found_k = -1, found_lt = 0, found_cost = 0;
-        for (int k0 = 0; k0 < K; k0 += 64) {
-            const int k = k0 + lane;
-            bool hit = false;
-            int lt = 0, co = 0;
-            if (k < K) {
-                const CandEntry e = ep[k];
-                lt = e.lt;
-                co = e.cost;
-                if (lt >= 0 && lt <= t) {
+        const size_t row = (size_t)i * S + s;
+        const StepEntry* sp = step_tab + row * Kp;
+        const uint32_t* tp = tag_tab + row * Kp;
+        // only entries whose bucket does not exceed t's can fit
+        const int n = bcum[row * nbs + (t >> BUCKET_SHIFT) + 1];
+        // smallest index k among the entries that attain the target; lt and cost
+        // ride along in the low bits of the key
+        unsigned long long key = ~0ull;
+        for (int e0 = 0; e0 < n; e0 += 64) {
+            const int e = e0 + lane;
+            if (e < n) {
+                const uint32_t tag = tp[e];
+                const int lt = (int)(tag & 0xFFFFu);  // every entry below n is feasible
+                if (lt <= t) {
+                    const uint32_t co = sp[e].cost2 & 0xFFFFu;
                     const uint32_t rest = (s + 1 < S) ? (uint32_t)next[t - lt] : 0u;
-                    hit = rest < F_INF && (uint32_t)co + rest == target;
+                    if (rest < F_INF && co + rest == target) {
+                        const unsigned long long cand =
+                            ((unsigned long long)(tag >> 16) << 32) | (co << 16) | (uint32_t)lt;
+                        key = cand < key ? cand : key;
+                    }
                 }
             }
-            const unsigned long long m = __ballot(hit);
-            if (m != 0ull) {
-                const int src = __builtin_ctzll(m);
-                found_k = k0 + src;
-                found_lt = __shfl(lt, src, 64);
-                found_cost = __shfl(co, src, 64);
-                break;
-            }
         }
-        if (found_k < 0) {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const unsigned long long other = __shfl_xor(key, d, 64);
+            key = other < key ? other : key;
+        }
+        if (key == ~0ull) {
             fail = true;
             break;
         }
+        const int found_k = (int)(key >> 32);
+        const int found_lt = (int)(key & 0xFFFFu);
+        const int found_cost = (int)((key >> 16) & 0xFFFFu);
         if (lane == 0) {
             const int c = found_k / bl.n + 1;
             my_cfg[3 * s + 0] = c;
@@ -126,9 +137,10 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
     bl.n = p.n_batch;
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
     hipLaunchKernelGGL(k3_backtrack, dim3((L.N + 3) / 4), dim3(256), 0, st,
-                       (const CandEntry*)(ws + L.cand_off), (const int32_t*)(ws + L.tmeta_off),
+                       (const StepEntry*)(ws + L.step_off), (const uint32_t*)(ws + L.tag_off),
+                       (const uint16_t*)(ws + L.bcum_off), (const int32_t*)(ws + L.tmeta_off),
                        (const uint16_t*)(ws + L.frow_off), d_status, d_cost, d_ticks, d_cfg, bl,
-                       L.N, L.S, L.K, L.Kp, L.row_stride);
+                       L.N, L.S, L.Kp, L.nbs, L.row_stride);
     return hipGetLastError();
 }
 

@@ -27,7 +27,9 @@ int check(const themis_problem_t* p)
         return THEMIS_ERR_RANGE;
     if (p->slo_max_us / p->tick_us > THEMIS_MAX_TICKS) return THEMIS_ERR_RANGE;
     // flat candidate index is 32-bit
-    long long nsk = (long long)p->n_inst * p->n_stage * ((p->c_max * p->n_batch + 7) / 8 * 8);
+    long long kp = ((long long)p->c_max * p->n_batch + 7) / 8 * 8;
+    if (kp > MAX_CAND) return THEMIS_ERR_SHAPE;
+    long long nsk = (long long)p->n_inst * p->n_stage * kp;
     if (nsk >= (1ll << 31)) return THEMIS_ERR_SHAPE;
     return THEMIS_OK;
 }

@@ -16,22 +16,35 @@ namespace themis {
 constexpr uint32_t F_INF = 0x8000u;
 constexpr uint32_t F_INF2 = 0x80008000u;
 
-// One candidate as stage 1 leaves it for stages 2 and 3.
-struct __attribute__((aligned(8))) CandEntry {
-    int32_t lt;    // latency in ticks, -1 = infeasible
-    int32_t cost;  // replicas * cores,  -1 = infeasible
+// Stage 1 leaves two tables, both ordered within a row by latency bucket
+// lt >> BUCKET_SHIFT (infeasible candidates last), so that the candidates that
+// can reach a given stretch of the budget grid form a prefix of the row:
+//   StepEntry  what the min-plus loop needs with no further scalar arithmetic:
+//              the byte offset that turns "my place in row copy 0" into "the
+//              aligned place lt cells below, in the copy whose shift fits"
+//              (it depends on the LDS layout of the instance's work class),
+//              and the cost replicated into both halves of a dword;
+//   tag        lt | k << 16 for reconstruction (lt = TAG_NONE if infeasible).
+struct __attribute__((aligned(8))) StepEntry {
+    uint32_t shift;  // see wide_shift() / narrow_shift()
+    uint32_t cost2;  // cost * 0x10001; 0 for an infeasible candidate
 };
+constexpr uint32_t TAG_NONE = 0xFFFFu;
+constexpr int BUCKET_SHIFT = 9;                 // 512 cells per bucket
+constexpr int BUCKET_CELLS = 1 << BUCKET_SHIFT;
+constexpr int MAX_BUCKETS = (THEMIS_MAX_TICKS >> BUCKET_SHIFT) + 1;   // 64
+constexpr int MAX_CAND = THEMIS_MAX_CANDIDATES; // candidates per model (LDS staging, 13-bit k)
 
 // ---- work classes of the min-plus stage ---------------------------------
 // An instance with budget T owns T+1 cells.  The "wide" kernel gives every
-// wavefront a chunk of WIDE_CHUNK cells (64 lanes x 4 quads of 4 cells), so an
-// instance needs ceil((T+1)/WIDE_CHUNK) wavefronts; instances are grouped by
-// that count (rounded up to the next entry of CLS_WAVES) and each group is
-// launched with a workgroup of exactly that many wavefronts and the LDS that
-// goes with it.  Budgets beyond 16 chunks go to the "narrow" kernel, which
-// keeps two instead of four row copies and so fits rows twice as long.
-constexpr int WIDE_V = 4;                        // quads (4 cells) per lane
-constexpr int WIDE_CHUNK = 64 * 4 * WIDE_V;      // 1024 cells per wavefront
+// wavefront WIDE_CHUNK cells (two positions of 512: 64 lanes x 2 quads of 4
+// cells each), so an instance needs ceil((T+1)/WIDE_CHUNK) wavefronts;
+// instances are grouped by that count (rounded up to the next entry of
+// CLS_WAVES) and each group is launched with a workgroup of exactly that many
+// wavefronts and the LDS that goes with it.  Budgets beyond 16 chunks go to
+// the "narrow" kernel, which keeps two instead of four row copies and so fits
+// rows twice as long.
+constexpr int WIDE_CHUNK = 1024;                 // cells per wavefront
 constexpr int N_WIDE_CLS = 10;
 constexpr int CLS_WAVES[N_WIDE_CLS] = {1, 2, 3, 4, 6, 8, 10, 12, 14, 16};
 constexpr int NARROW_CLS = N_WIDE_CLS;           // class index of the narrow kernel
@@ -48,15 +61,49 @@ __host__ __device__ inline int class_of_budget(int T)
     return c;
 }
 
+// ---- LDS geometry of the min-plus stage (stage 1 bakes it into StepEntry) --
+// Wide kernel: four copies of the row, copy m holds cell t at half-word
+// (WIDE_PAD_BYTES/2 + t - m); each copy is WIDE_PAD_BYTES of F_INF followed by
+// two positions (2 * 512 cells) per wavefront of the class.
+constexpr int WIDE_PAD_BYTES = BUCKET_CELLS * 2;
+
+__host__ __device__ inline int wide_copy_bytes(int waves)
+{
+    return WIDE_PAD_BYTES + waves * WIDE_CHUNK * 2;
+}
+
+// lt = 4h - m: read copy m, h quads (8 bytes each) below the lane's own quad.
+__host__ __device__ inline uint32_t wide_shift(uint32_t lt, int copy_bytes)
+{
+    return ((0u - lt) & 3u) * (uint32_t)copy_bytes - 8u * ((lt + 3u) >> 2);
+}
+
+// Narrow kernel: 16 wavefronts x 1024 dwords; copy A holds cells (2j, 2j+1) in
+// dword j, copy B cells (2j+1, 2j+2); each copy is preceded by one wavefront's
+// worth of F_INF.
+constexpr int NAR_WAVES = 16;
+constexpr int NAR_CHUNK_DW = 1024;                       // dwords per wavefront
+constexpr int NAR_COPY_DW = (NAR_WAVES + 1) * NAR_CHUNK_DW;
+
+// even lt = 2h: A[j - h]; odd lt = 2h + 1: B[j - h - 1]; in bytes from LDS start
+__host__ __device__ inline uint32_t narrow_shift(uint32_t lt)
+{
+    const uint32_t h = lt >> 1;
+    return 4u * ((lt & 1u) ? (uint32_t)(NAR_COPY_DW + NAR_CHUNK_DW - 1) - h
+                           : (uint32_t)NAR_CHUNK_DW - h);
+}
+
 // Workspace carve-up.  Every region starts on a 256-byte boundary.
-//   cand   CandEntry [N][S][Kp]   Kp = K rounded up to 8; pad entries infeasible
+//   step   StepEntry [N*S][Kp] bucket-ordered; Kp = K rounded up to 8
+//   tag    u32 [N*S][Kp]       lt | k << 16 of the entry in the same slot
+//   bcum   u16 [N*S][nbs]      bcum[j] = entries of the row with bucket < j, j = 0..nb
 //   frow   u16 [N][S][row_stride] f[s][t] of the min-plus recurrence
-//   tmeta  int32 [N]              budget T of the instance, -1 = invalid instance
-//   order  int32 [N_CLS][N]       instance ids grouped by work class
-//   ctrl   int32 [2][N_CLS]       per class: number of instances, queue cursor
+//   tmeta  int32 [N]           budget T of the instance, -1 = invalid instance
+//   order  int32 [N_CLS][N]    instance ids grouped by work class
+//   ctrl   int32 [2][N_CLS]    per class: number of instances, queue cursor
 struct Layout {
-    size_t cand_off, frow_off, tmeta_off, order_off, ctrl_off, total;
-    int32_t N, S, K, Kp, t_max, row_stride;
+    size_t step_off, tag_off, bcum_off, frow_off, tmeta_off, order_off, ctrl_off, total;
+    int32_t N, S, K, Kp, t_max, row_stride, nb, nbs;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -69,12 +116,18 @@ inline Layout make_layout(const themis_problem_t& p)
     L.K = p.c_max * p.n_batch;
     L.Kp = (L.K + 7) / 8 * 8;
     L.t_max = p.slo_max_us / p.tick_us;
+    L.nb = (L.t_max >> BUCKET_SHIFT) + 1;
+    L.nbs = (L.nb + 1 + 1) / 2 * 2;
     // a lane stores the four cells of a quad at once, so up to three cells
     // past T are written; rows start 256-byte aligned
     L.row_stride = (int32_t)((L.t_max + 4 + 127) / 128 * 128);
+    size_t rows = (size_t)L.N * L.S;
     size_t at = 0;
-    L.cand_off = at;  at = align256(at + (size_t)L.N * L.S * L.Kp * sizeof(CandEntry));
-    L.frow_off = at;  at = align256(at + (size_t)L.N * L.S * L.row_stride * sizeof(uint16_t));
+    // one spare batch after the last row: the min-plus loop fetches one batch ahead
+    L.step_off = at;  at = align256(at + (rows * L.Kp + 8) * sizeof(StepEntry));
+    L.tag_off = at;   at = align256(at + rows * L.Kp * sizeof(uint32_t));
+    L.bcum_off = at;  at = align256(at + rows * L.nbs * sizeof(uint16_t));
+    L.frow_off = at;  at = align256(at + rows * L.row_stride * sizeof(uint16_t));
     L.tmeta_off = at; at = align256(at + (size_t)L.N * sizeof(int32_t));
     L.order_off = at; at = align256(at + (size_t)N_CLS * L.N * sizeof(int32_t));
     L.ctrl_off = at;  at = align256(at + (size_t)2 * N_CLS * sizeof(int32_t));
