@@ -144,7 +144,8 @@ def lds_probe():
     stream = torch.cuda.current_stream()
     blocks, iters = N_CU * 2 * 4, 2000
     res = {}
-    for width, mis in ((4, 0), (4, 2), (8, 0), (8, 4), (8, 2), (16, 0), (16, 8), (16, 4), (16, 2)):
+    for width, mis in ((4, 0), (4, 2), (8, 0), (8, 4), (8, 2), (8, -1), (8, -2), (16, 0), (16, 8),
+                       (16, 4), (16, 2)):
         themis.themis_probe_lds_read(width, mis, 50, blocks, sink, stream)
         torch.cuda.synchronize()
         e0, e1 = _events(2)
@@ -154,10 +155,29 @@ def lds_probe():
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1)
         gbs = blocks * 1024 * iters * 4 * width / (ms * 1e-3) / 1e9
-        res[f"b{width * 8}+{mis}"] = {"ms": ms, "GB/s": gbs,
+        name = {-1: "read2_b32 adjacent, 4-byte aligned", -2: "read2st64_b32"}.get(
+            mis, f"b{width * 8}+{mis}")
+        res[name] = {"ms": ms, "GB/s": gbs,
                                        "bytes_per_clk_per_cu": gbs / N_CU / CLOCK_GHZ}
-    print(json.dumps({"lds_read_probe": res, "blocks": blocks, "threads": 1024, "iters": iters,
-                      "assumed_clock_ghz": CLOCK_GHZ}), flush=True)
+    valu = {}
+    names = ["v_pk_add_u16", "v_pk_min_u16", "v_add_u32", "v_min_u32",
+             "v_pk_add_u16/v_pk_min_u16 alternating", "v_pk_add_u16 (sgpr operand)"]
+    vblocks, viters = N_CU * 8 * 4, 4000
+    for op, name in enumerate(names):
+        themis.themis_probe_valu(op, 10, vblocks, sink, stream)
+        torch.cuda.synchronize()
+        e0, e1 = _events(2)
+        e0.record(stream)
+        themis.themis_probe_valu(op, viters, vblocks, sink, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        gops = vblocks * 256 * viters * 16 / (ms * 1e-3) / 1e9
+        valu[name] = {"ms": ms, "G lane-instr/s": gops,
+                      "lanes_per_clk_per_cu": gops / N_CU / CLOCK_GHZ}
+    print(json.dumps({"lds_read_probe": res, "valu_probe": valu, "blocks": blocks,
+                      "threads": 1024, "iters": iters, "assumed_clock_ghz": CLOCK_GHZ}),
+          flush=True)
 
 
 def main():

@@ -198,13 +198,25 @@ int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
 /*
  * Measurement aid, not part of the solve: launch a kernel in which every lane
  * does nothing but conflict-free LDS reads of `width` bytes (4, 8 or 16) at
- * byte misalignment `misalign` (0, or 2/4/8 where smaller than the width).
+ * byte misalignment `misalign` (0, or 2/4/8 where smaller than the width;
+ * with width 8, -1 = two adjacent dwords by ds_read2_b32 at 4-byte alignment,
+ * -2 = ds_read2st64_b32).
  * One launch reads blocks * 1024 * iters * 4 * width bytes; time it to obtain
  * the LDS read bandwidth the min-plus stage is priced against.  d_sink is
  * one uint32 of device memory.  Unsupported combinations: THEMIS_ERR_SHAPE.
  */
 int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32_t *d_sink,
                           void *stream);
+
+/*
+ * Measurement aid, not part of the solve: launch a kernel in which every lane
+ * issues iters * 16 independent vector instructions of one kind and nothing
+ * else (op 0 v_pk_add_u16, 1 v_pk_min_u16, 2 v_add_u32, 3 v_min_u32,
+ * 4 v_pk_add_u16 / v_pk_min_u16 alternating, 5 v_pk_add_u16 with a scalar
+ * operand).  One launch issues blocks * 256 * iters * 16 lane-instructions;
+ * time it to obtain the vector-ALU rate the min-plus stage is priced against.
+ */
+int themis_probe_valu(int op, int iters, int blocks, uint32_t *d_sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ tmeta, StepEntry* __restrict__ step_tab,
     uint32_t* __restrict__ tag_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
     uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, int coef_shared,
-    uint32_t G, uint32_t nb, uint32_t nbs)
+    uint32_t G, uint32_t nb, uint32_t nbs, int copies_mask)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t R = 256u / G;
@@ -205,6 +205,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
         // the LDS geometry the min-plus stage will use for this instance
         const int cls = T >= 0 ? class_of_budget(T) : 0;
         const int copy_bytes = wide_copy_bytes(CLS_WAVES[cls == NARROW_CLS ? 0 : cls]);
+        const int copies = class_copies(cls, copies_mask);
         for (uint32_t kk = g; kk < Kp; kk += G) {
             const uint32_t w0 = stage[kk];
             const bool none = w0 == TAG_NONE;
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
             const uint32_t b = none ? nb : lt >> BUCKET_SHIFT;
             const uint32_t slot = atomicAdd(&cur[b], 1u);
             StepEntry se;
-            se.shift = none ? 0u : (cls == NARROW_CLS ? narrow_shift(lt) : wide_shift(lt, copy_bytes));
+            se.shift = none ? 0u : (cls == NARROW_CLS ? narrow_shift(lt) : wide_shift(lt, copies, copy_bytes));
             se.cost2 = none ? 0u : (w0 >> 16) * 0x10001u;
             step_tab[(size_t)row * Kp + slot] = se;
             tag_tab[(size_t)row * Kp + slot] = lt | (kk << 16);
@@ -294,7 +295,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                        (StepEntry*)(ws + L.step_off), (uint32_t*)(ws + L.tag_off),
                        (uint16_t*)(ws + L.bcum_off), bl, rows, (uint32_t)L.S, (uint32_t)L.K,
                        (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us, p.coef_shared, G,
-                       (uint32_t)L.nb, (uint32_t)L.nbs);
+                       (uint32_t)L.nb, (uint32_t)L.nbs, wide_copies_mask());
     return hipGetLastError();
 }
 

@@ -96,160 +96,195 @@ __device__ __forceinline__ int prefix_count(const AS_CONST uint16_t* bc, int las
 }
 
 // ------------------------------------------------------------------ wide kernel
-constexpr int QP = 2;                 // quads (4 cells) per lane per position
-constexpr int POSC = 64 * 4 * QP;     // cells per position
+// COPIES = 4: lane elements are quads (4 cells, 8 bytes), two per position,
+//             read with ds_read_b64 from the copy (-lt) mod 4;
+// COPIES = 2: lane elements are pairs (2 cells, 4 bytes), four per position,
+//             read with ds_read_b32 from the copy lt mod 2.  Half the LDS
+//             bandwidth per clock, but half the LDS footprint, so two
+//             workgroups of the longest rows share a compute unit.
+// Either way a position is 512 cells and a lane keeps 4 dwords of it.
+constexpr int POSC = BUCKET_CELLS;    // cells per position
 constexpr int PADB = WIDE_PAD_BYTES;  // bytes of F_INF in front of every copy
-static_assert(POSC == BUCKET_CELLS, "a position is one bucket of the candidate order");
+constexpr int AD = 4;                 // accumulator dwords per lane per position
+constexpr int CAND_BUF = 512;         // entries of a row staged in LDS at a time
 static_assert(WIDE_CHUNK == 2 * POSC, "a wavefront holds two positions");
 static_assert(PADB == POSC * 2, "the pad is as long as one position");
 
-// Sweep entries [k_begin, k_end) of a bucket-ordered row over the lane's lower
-// position (DO_LO), upper position (DO_HI) or both.  k_begin and k_end are
-// multiples of eight; entry k only counts for the lower position if k < n_lo
-// and for the upper one if k < n_hi, otherwise its read is parked on the F_INF
-// pad, where it changes nothing.
-//
-// The loop is software-pipelined by hand: the LDS reads of entry k+1 are
-// issued before the arithmetic of entry k, into the other half of a double
-// buffer, so a wavefront always has one entry's reads in flight while it
-// works.  The scheduling barriers keep the compiler from undoing that order.
-template <bool DO_LO, bool DO_HI>
-__device__ __forceinline__ void sweep(uint32_t (&alo)[2 * QP], uint32_t (&ahi)[2 * QP],
-                                      const char* ldsb, const AS_CONST u32x16* ep, int k_begin,
-                                      int k_end, int n_lo, int n_hi, uint32_t byte_lo,
-                                      uint32_t byte_hi, uint32_t park_lo, uint32_t park_hi)
-{
-    if (k_begin >= k_end) return;
-    u32x2 blo[2][QP], bhi[2][QP];
-    uint32_t bcost[2];
+template <int COPIES>
+struct Geo {
+    static constexpr int ELT = COPIES == 4 ? 8 : 4;   // bytes per lane element
+    static constexpr int NE = AD * 4 / ELT;           // lane elements per position
+    // byte offset (inside a copy) of a lane's first element of position pos
+    static __device__ __forceinline__ uint32_t lane_byte(int pos, int lane)
+    {
+        return (uint32_t)(PADB + ELT * (pos * (64 * NE) + lane));
+    }
+    // added to lane_byte: lands the position's reads on the F_INF pad of copy 0
+    static __device__ __forceinline__ uint32_t park(int pos)
+    {
+        return 0u - (uint32_t)(PADB + ELT * pos * (64 * NE));
+    }
+    static __device__ __forceinline__ void read(uint32_t (&dst)[AD], const char* at)
+    {
+        if constexpr (COPIES == 4) {
+            const u32x2* src = reinterpret_cast<const u32x2*>(at);
+#pragma unroll
+            for (int q = 0; q < NE; ++q) {
+                const u32x2 r = src[q * 64];
+                dst[2 * q] = r.x;
+                dst[2 * q + 1] = r.y;
+            }
+        } else {
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(at);
+#pragma unroll
+            for (int u = 0; u < NE; ++u) dst[u] = src[u * 64];
+        }
+    }
+};
 
-    // entry = (shift, cost2) as stage 1 prepared them
-    auto issue = [&](uint32_t shift, uint32_t cost2, int k, int slot) {
-        bcost[slot] = cost2;
-        if (DO_LO) {
-            const u32x2* src =
-                reinterpret_cast<const u32x2*>(ldsb + (byte_lo + (k < n_lo ? shift : park_lo)));
-#pragma unroll
-            for (int q = 0; q < QP; ++q) blo[slot][q] = src[q * 64];
-        }
-        if (DO_HI) {
-            const u32x2* src =
-                reinterpret_cast<const u32x2*>(ldsb + (byte_hi + (k < n_hi ? shift : park_hi)));
-#pragma unroll
-            for (int q = 0; q < QP; ++q) bhi[slot][q] = src[q * 64];
-        }
+// Sweep entries [kb, ke) of the staged part of a bucket-ordered row over one
+// position.  `ent` points at the staged entries in LDS; every lane reads the
+// same entry (a broadcast), so shift and cost arrive in VGPRs without touching
+// the scalar unit.
+//
+// The loop is software-pipelined by hand: the row reads of entry k+1 are issued
+// before the arithmetic of entry k, into the other half of a double buffer, and
+// the entries themselves are fetched two ahead, so a wavefront always has reads
+// in flight while it works.  The scheduling barriers keep the compiler from
+// undoing that order.  In the last steps the entries at or beyond ke are
+// parked on the F_INF pad, where they change nothing.
+template <int COPIES>
+__device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, const u32x2* ent,
+                                      int kb, int ke, uint32_t byte_pos, uint32_t park)
+{
+    using G = Geo<COPIES>;
+    if (kb >= ke) return;
+    uint32_t buf[2][AD], bcost[2];
+
+    auto issue = [&](u32x2 en, bool live, int slot) {
+        bcost[slot] = en.y;
+        G::read(buf[slot], ldsb + (byte_pos + (live ? en.x : park)));
     };
     auto consume = [&](int slot) {
         const uint32_t c = bcost[slot];
-        uint32_t t[4 * QP];
+        uint32_t t[AD];
         // all the adds, then all the mins: no add feeds the instruction after it
 #pragma unroll
-        for (int q = 0; q < QP; ++q) {
-            if (DO_LO) {
-                t[4 * q] = pk_add(blo[slot][q].x, c);
-                t[4 * q + 1] = pk_add(blo[slot][q].y, c);
-            }
-            if (DO_HI) {
-                t[4 * q + 2] = pk_add(bhi[slot][q].x, c);
-                t[4 * q + 3] = pk_add(bhi[slot][q].y, c);
-            }
-        }
+        for (int u = 0; u < AD; ++u) t[u] = pk_add(buf[slot][u], c);
 #pragma unroll
-        for (int q = 0; q < QP; ++q) {
-            if (DO_LO) {
-                alo[2 * q] = pk_min(alo[2 * q], t[4 * q]);
-                alo[2 * q + 1] = pk_min(alo[2 * q + 1], t[4 * q + 1]);
-            }
-            if (DO_HI) {
-                ahi[2 * q] = pk_min(ahi[2 * q], t[4 * q + 2]);
-                ahi[2 * q + 1] = pk_min(ahi[2 * q + 1], t[4 * q + 3]);
-            }
-        }
+        for (int u = 0; u < AD; ++u) acc[u] = pk_min(acc[u], t[u]);
     };
 
-    u32x16 e = ep[k_begin >> 3];  // eight entries, one scalar load
-    issue(e[0], e[1], k_begin, 0);
-    for (int k0 = k_begin; k0 < k_end; k0 += 8) {
-        // one batch ahead; past the prefix it fetches entries that get parked
-        const u32x16 en = ep[(k0 >> 3) + 1];
+    // ring of four entries: while entry k is being relaxed, the row reads of k+1
+    // are in flight and entry k+2 is being fetched
+    u32x2 e[4];
+    e[0] = ent[kb];
+    e[1] = ent[kb + 1];
+    issue(e[0], true, 0);
+    int k0 = kb;
+    // groups of four whose entries and the two after them all lie inside [kb, ke)
+    for (; k0 + 6 <= ke; k0 += 4) {
 #pragma unroll
-        for (int z = 0; z < 8; ++z) {
-            if (z < 7) {
-                issue(e[2 * z + 2], e[2 * z + 3], k0 + z + 1, (z + 1) & 1);
-            } else {
-                // first touch of the batch fetched above: pinned here so that the
-                // wait for that scalar load comes after seven entries of work
-                uint32_t sh = en[0], c2 = en[1];
-                asm volatile("" : "+s"(sh), "+s"(c2));
-                issue(sh, c2, k0 + 8, 0);
-            }
+        for (int z = 0; z < 4; ++z) {
+            e[(z + 2) & 3] = ent[k0 + z + 2];
+            issue(e[(z + 1) & 3], true, (z + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
             consume(z & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        e = en;
     }
-}
-
-// Clamp a finished position, store it to the HBM row (cells <= T only).
-__device__ __forceinline__ void finish_position(uint32_t (&acc)[2 * QP], uint16_t* out, int pos,
-                                                int lane, int T)
-{
+    // the rest: entries at or beyond ke are parked (k0 - kb is a multiple of
+    // four here, so the ring and the double buffer are back at slot 0)
+    for (; k0 < ke; k0 += 4) {
 #pragma unroll
-    for (int q = 0; q < QP; ++q) {
-        acc[2 * q] = pk_min(acc[2 * q], F_INF2);
-        acc[2 * q + 1] = pk_min(acc[2 * q + 1], F_INF2);
-        const int cell = 4 * (pos * (64 * QP) + q * 64 + lane);
-        if (cell <= T) {
-            u32x2 v;
-            v.x = acc[2 * q];
-            v.y = acc[2 * q + 1];
-            *reinterpret_cast<u32x2*>(out + cell) = v;
+        for (int z = 0; z < 4; ++z) {
+            e[(z + 2) & 3] = ent[k0 + z + 2];
+            issue(e[(z + 1) & 3], k0 + z + 1 < ke, (z + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(z & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
 
-// Write a finished position into the four shifted LDS copies.  `at` is the
-// byte address of the lane's first quad in copy 0; copy m holds cell t at
-// half-word (PADB/2 + t - m).  volatile: each store must stay a naturally
-// aligned access of exactly this width (merged neighbours would be misaligned).
-__device__ __forceinline__ void publish_position(const uint32_t (&acc)[2 * QP], char* at, int CSB)
+// Clamp a finished position and store it to the HBM row (cells <= T only).
+template <int COPIES>
+__device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* out, int pos,
+                                                int lane, int T)
 {
+    using G = Geo<COPIES>;
 #pragma unroll
-    for (int q = 0; q < QP; ++q) {
-        const uint32_t lo = acc[2 * q], hi = acc[2 * q + 1];         // cells c0 c1 | c2 c3
-        const uint32_t mid = __builtin_amdgcn_alignbit(hi, lo, 16);  // c1 c2
-        char* const p = at + q * 512;
-        u32x2 v;
-        v.x = lo;
-        v.y = hi;
-        *reinterpret_cast<volatile u32x2*>(p) = v;                                 // copy 0
-        *reinterpret_cast<volatile uint16_t*>(p + CSB - 2) = (uint16_t)lo;         // copy 1
-        *reinterpret_cast<volatile uint32_t*>(p + CSB) = mid;
-        *reinterpret_cast<volatile uint16_t*>(p + CSB + 4) = (uint16_t)(hi >> 16);
-        *reinterpret_cast<volatile uint32_t*>(p + 2 * CSB - 4) = lo;               // copy 2
-        *reinterpret_cast<volatile uint32_t*>(p + 2 * CSB) = hi;
-        *reinterpret_cast<volatile uint16_t*>(p + 3 * CSB - 6) = (uint16_t)lo;     // copy 3
-        *reinterpret_cast<volatile uint32_t*>(p + 3 * CSB - 4) = mid;
-        *reinterpret_cast<volatile uint16_t*>(p + 3 * CSB) = (uint16_t)(hi >> 16);
+    for (int u = 0; u < AD; ++u) acc[u] = pk_min(acc[u], F_INF2);
+#pragma unroll
+    for (int q = 0; q < G::NE; ++q) {
+        const int cell = (G::ELT / 2) * (pos * (64 * G::NE) + q * 64 + lane);
+        if (cell <= T) {
+            if constexpr (COPIES == 4) {
+                u32x2 v;
+                v.x = acc[2 * q];
+                v.y = acc[2 * q + 1];
+                *reinterpret_cast<u32x2*>(out + cell) = v;
+            } else {
+                *reinterpret_cast<uint32_t*>(out + cell) = acc[q];
+            }
+        }
     }
 }
 
+// Write one lane element of the new row into the shifted LDS copies.  `p` is
+// the element's byte address in copy 0; copy m holds cell t at half-word
+// (PADB/2 + t - m).  volatile: each store must stay a naturally aligned access
+// of exactly this width (merged neighbours would be misaligned).
+__device__ __forceinline__ void publish_quad(char* p, int CSB, uint32_t lo, uint32_t hi)
+{
+    const uint32_t mid = __builtin_amdgcn_alignbit(hi, lo, 16);  // cells c1 c2 of c0 c1 | c2 c3
+    u32x2 v;
+    v.x = lo;
+    v.y = hi;
+    *reinterpret_cast<volatile u32x2*>(p) = v;                                 // copy 0
+    *reinterpret_cast<volatile uint16_t*>(p + CSB - 2) = (uint16_t)lo;         // copy 1
+    *reinterpret_cast<volatile uint32_t*>(p + CSB) = mid;
+    *reinterpret_cast<volatile uint16_t*>(p + CSB + 4) = (uint16_t)(hi >> 16);
+    *reinterpret_cast<volatile uint32_t*>(p + 2 * CSB - 4) = lo;               // copy 2
+    *reinterpret_cast<volatile uint32_t*>(p + 2 * CSB) = hi;
+    *reinterpret_cast<volatile uint16_t*>(p + 3 * CSB - 6) = (uint16_t)lo;     // copy 3
+    *reinterpret_cast<volatile uint32_t*>(p + 3 * CSB - 4) = mid;
+    *reinterpret_cast<volatile uint16_t*>(p + 3 * CSB) = (uint16_t)(hi >> 16);
+}
+
+__device__ __forceinline__ void publish_pair(char* p, int CSB, uint32_t v)
+{
+    *reinterpret_cast<volatile uint32_t*>(p) = v;                              // copy 0
+    *reinterpret_cast<volatile uint16_t*>(p + CSB - 2) = (uint16_t)v;          // copy 1
+    *reinterpret_cast<volatile uint16_t*>(p + CSB) = (uint16_t)(v >> 16);
+}
+
+// The positions of a row cost very different amounts of work (position p is
+// reached by bcum[p+1] entries), so they are not dealt out in advance: the
+// wavefronts of the workgroup take them one at a time from a counter in LDS,
+// most expensive first.  A finished position goes straight to the HBM row;
+// once every wavefront is done with the old row, the workgroup reads the new
+// one back (it is still in L2) and spreads it over the LDS copies.
+template <int COPIES>
 __global__ __launch_bounds__(1024) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
     int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int N, int S, int Kp, int nbs,
     int row_stride, int cls)
 {
+    using G = Geo<COPIES>;
     extern __shared__ uint32_t lds[];
-    const int nwc = blockDim.x >> 6;             // wavefronts of this class
-    const int CSB = wide_copy_bytes(nwc);        // bytes per copy: pad + two positions per wave
+    const int CSB = wide_copy_bytes(CLS_WAVES[cls]);  // bytes per copy: pad + the longest row
     char* const ldsb = reinterpret_cast<char*>(lds);
-    volatile uint32_t* const slot = lds + CSB;   // one dword after the four copies
+    // after the copies: a dword for the instance queue, one for the position
+    // counter, then the staged entries
+    volatile uint32_t* const slot = lds + COPIES * (CSB / 4);
+    int* const next_pos = reinterpret_cast<int*>(lds + COPIES * (CSB / 4) + 1);
+    StepEntry* const cbuf = reinterpret_cast<StepEntry*>(ldsb + COPIES * CSB + 16);
+    const u32x2* const ent = reinterpret_cast<const u32x2*>(cbuf);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int count = as_constant(ctrl)[cls];
     const int32_t* const my_order = order + (size_t)cls * N;
 
@@ -258,62 +293,108 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
         if (i < 0) break;
         const int T = as_constant(tmeta)[i];
         const int npos = (T + POSC) / POSC;  // positions that hold cells 0..T
-        const int pos_lo = w, pos_hi = npos - 1 - w;
-        const bool has_lo = pos_lo <= pos_hi;  // an odd middle position is a "lo" without a "hi"
-        const bool has_hi = pos_lo < pos_hi;
-        // byte offset of this lane's first quad of each position inside a copy
-        const uint32_t byte_lo = (uint32_t)(PADB + 8 * (pos_lo * (64 * QP) + lane));
-        const uint32_t byte_hi = (uint32_t)(PADB + 8 * (pos_hi * (64 * QP) + lane));
-        // offset that sends a lane's position read to the F_INF pad of copy 0
-        const uint32_t park_lo = 0u - (uint32_t)(PADB + 8 * pos_lo * (64 * QP));
-        const uint32_t park_hi = 0u - (uint32_t)(PADB + 8 * pos_hi * (64 * QP));
 
         // rows before the first model: cells t < 0 are F_INF, cells t >= 0 are 0
-        for (int x = tid; x < CSB / 4; x += (int)blockDim.x) {
+        for (int x = tid; x < (PADB + npos * POSC * 2) / 4; x += (int)blockDim.x) {
 #pragma unroll
-            for (int m = 0; m < 4; ++m) {
+            for (int m = 0; m < COPIES; ++m) {
                 const uint32_t h0 = 2 * x < PADB / 2 - m ? F_INF : 0u;
                 const uint32_t h1 = 2 * x + 1 < PADB / 2 - m ? F_INF : 0u;
                 lds[m * (CSB / 4) + x] = h0 | (h1 << 16);
             }
         }
-        __syncthreads();
+        // (the barrier after staging the first model's entries also covers this)
 
         for (int s = S - 1; s >= 0; --s) {
-            uint32_t alo[2 * QP], ahi[2 * QP];
-#pragma unroll
-            for (int u = 0; u < 2 * QP; ++u) alo[u] = ahi[u] = 0xFFFFFFFFu;
-
             const size_t row = (size_t)i * S + s;
-            const AS_CONST u32x16* ep =
-                reinterpret_cast<const AS_CONST u32x16*>(as_constant(step_tab + row * Kp));
+            const StepEntry* const grow = step_tab + row * Kp;
             const AS_CONST uint16_t* bc = as_constant(bcum + row * nbs);
-            if (has_hi) {
-                const int n_lo = prefix_count(bc, (pos_lo + 1) * POSC - 1);
-                const int n_hi = prefix_count(bc, (pos_hi + 1) * POSC - 1);
-                const int k_both = (n_lo + 7) & ~7;
-                const int k_end = (n_hi + 7) & ~7;
-                // entries that reach both positions, then those that reach only the upper one
-                sweep<true, true>(alo, ahi, ldsb, ep, 0, k_both, n_lo, n_hi, byte_lo, byte_hi,
-                                  park_lo, park_hi);
-                sweep<false, true>(alo, ahi, ldsb, ep, k_both, k_end, n_lo, n_hi, byte_lo, byte_hi,
-                                   park_lo, park_hi);
-            } else if (has_lo) {
-                // a lone middle position
-                const int n_lo = prefix_count(bc, (pos_lo + 1) * POSC - 1);
-                sweep<true, false>(alo, ahi, ldsb, ep, 0, (n_lo + 7) & ~7, n_lo, 0, byte_lo, byte_hi,
-                                   park_lo, park_hi);
-            }
-
             uint16_t* const out = frow + row * row_stride;
-            if (has_lo) finish_position(alo, out, pos_lo, lane, T);
-            if (has_hi) finish_position(ahi, out, pos_hi, lane, T);
+            const int n_all = bc[npos];  // entries that reach the top position: all feasible ones
+
+            if (n_all <= CAND_BUF) {
+                // the whole row fits the staging buffer (the usual case)
+                for (int x = tid; x < n_all + 16; x += (int)blockDim.x) {
+                    StepEntry se;
+                    se.shift = 0u;
+                    se.cost2 = 0u;
+                    if (x < n_all) se = grow[x];
+                    cbuf[x] = se;  // 16 harmless entries behind the row feed the look-ahead
+                }
+                if (tid == 0) *next_pos = npos - 1;
+                __syncthreads();
+                for (;;) {
+                    int p = 0;
+                    if (lane == 0) p = atomicSub(next_pos, 1);
+                    p = __builtin_amdgcn_readfirstlane(p);
+                    if (p < 0) break;
+                    uint32_t acc[AD];
+#pragma unroll
+                    for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
+                    sweep<COPIES>(acc, ldsb, ent, 0, bc[p + 1], G::lane_byte(p, lane), G::park(p));
+                    finish_position<COPIES>(acc, out, p, lane, T);
+                }
+            } else {
+                // a long row goes through the buffer in parts; every wavefront keeps
+                // its positions (w, w + nw, ...) across the parts
+                const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+                const int nw = (int)blockDim.x >> 6;
+                for (int p0 = w; p0 < npos; p0 += nw) {
+                    uint32_t acc[AD];
+#pragma unroll
+                    for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
+                    finish_position<COPIES>(acc, out, p0, lane, T);  // start from "none"
+                }
+                for (int seg = 0; seg < n_all; seg += CAND_BUF) {
+                    const int cnt = n_all - seg < CAND_BUF ? n_all - seg : CAND_BUF;
+                    __syncthreads();  // sweeps of the previous part are done, stores are visible
+                    for (int x = tid; x < cnt + 16; x += (int)blockDim.x) {
+                        StepEntry se;
+                        se.shift = 0u;
+                        se.cost2 = 0u;
+                        if (x < cnt) se = grow[seg + x];
+                        cbuf[x] = se;
+                    }
+                    __syncthreads();
+                    for (int p0 = w; p0 < npos; p0 += nw) {
+                        const int n_p = bc[p0 + 1];
+                        const int ke = n_p - seg < 0 ? 0 : (n_p - seg < cnt ? n_p - seg : cnt);
+                        if (ke <= 0) continue;
+                        // resume from the partial minimum this wavefront stored earlier
+                        uint32_t acc[AD];
+#pragma unroll
+                        for (int q = 0; q < G::NE; ++q) {
+                            const int cell = (G::ELT / 2) * (p0 * (64 * G::NE) + q * 64 + lane);
+                            if constexpr (COPIES == 4) {
+                                u32x2 v;
+                                v.x = v.y = F_INF2;
+                                if (cell <= T) v = *reinterpret_cast<const u32x2*>(out + cell);
+                                acc[2 * q] = v.x;
+                                acc[2 * q + 1] = v.y;
+                            } else {
+                                acc[q] = cell <= T ? *reinterpret_cast<const uint32_t*>(out + cell)
+                                                   : F_INF2;
+                            }
+                        }
+                        sweep<COPIES>(acc, ldsb, ent, 0, ke, G::lane_byte(p0, lane), G::park(p0));
+                        finish_position<COPIES>(acc, out, p0, lane, T);
+                    }
+                }
+            }
             if (s == 0) break;  // nothing reads the LDS copies of the last row
 
-            __syncthreads();  // every wavefront is done reading the previous row
-            if (has_lo) publish_position(alo, ldsb + byte_lo, CSB);
-            if (has_hi) publish_position(ahi, ldsb + byte_hi, CSB);
-            __syncthreads();
+            __syncthreads();  // every wavefront is done with the old row; the new one is stored
+            // bring the new row back and spread it over the copies
+            for (int el = tid; el * (G::ELT / 2) <= T; el += (int)blockDim.x) {
+                char* const at = ldsb + PADB + G::ELT * el;
+                if constexpr (COPIES == 4) {
+                    const u32x2 v = *reinterpret_cast<const u32x2*>(out + 4 * el);
+                    publish_quad(at, CSB, v.x, v.y);
+                } else {
+                    publish_pair(at, CSB, *reinterpret_cast<const uint32_t*>(out + 2 * el));
+                }
+            }
+            // (the barrier after staging the next model's entries covers these writes)
         }
         __syncthreads();  // last row's reads are done before the LDS is re-initialised
     }
@@ -416,23 +497,39 @@ int cu_count()
 
 constexpr size_t LDS_PER_CU = 160 * 1024;
 
+
+template <int COPIES>
+hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int cus)
+{
+    const int nwc = CLS_WAVES[c];
+    const size_t lds_bytes =
+        (size_t)COPIES * wide_copy_bytes(nwc) + 16 + (CAND_BUF + 16) * sizeof(StepEntry);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_wide<COPIES>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)(LDS_PER_CU - 1024));
+    if (e != hipSuccess) return e;
+    int per_cu = (int)(LDS_PER_CU / lds_bytes);
+    if (per_cu > 32 / nwc) per_cu = 32 / nwc;
+    if (per_cu < 1) per_cu = 1;
+    long long grid = (long long)cus * per_cu;
+    if (grid > L_.N) grid = L_.N;
+    hipLaunchKernelGGL(k2_minplus_wide<COPIES>, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
+                       (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
+                       (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
+                       (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off), L_.N, L_.S,
+                       L_.Kp, L_.nbs, L_.row_stride, c);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_minplus(const themis_problem_t&, const Layout& L_, char* ws, hipStream_t st)
 {
-    const StepEntry* w0 = (const StepEntry*)(ws + L_.step_off);
-    const uint16_t* bcum = (const uint16_t*)(ws + L_.bcum_off);
-    const int32_t* tmeta = (const int32_t*)(ws + L_.tmeta_off);
-    const int32_t* order = (const int32_t*)(ws + L_.order_off);
-    int32_t* ctrl = (int32_t*)(ws + L_.ctrl_off);
-    uint16_t* frow = (uint16_t*)(ws + L_.frow_off);
     const int cus = cu_count();
     const int top = class_of_budget(L_.t_max);  // no instance can be in a higher class
     const int top_wide = top == NARROW_CLS ? N_WIDE_CLS - 1 : top;
-    hipError_t e = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&k2_minplus_wide), hipFuncAttributeMaxDynamicSharedMemorySize,
-        4 * (PADB + CLS_WAVES[top_wide] * WIDE_CHUNK * 2) + 16);
-    if (e != hipSuccess) return e;
+    const int mask = wide_copies_mask();
+    hipError_t e;
 
     // longest rows first: they take longest, so they should not start last
     if (top == NARROW_CLS) {
@@ -441,24 +538,18 @@ hipError_t launch_minplus(const themis_problem_t&, const Layout& L_, char* ws, h
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         int grid = L_.N < cus ? L_.N : cus;
-        hipLaunchKernelGGL(k2_minplus_narrow, dim3(grid), dim3(NAR_NW * 64), lds_bytes, st, w0,
-                           bcum, tmeta, order, ctrl, frow, L_.N, L_.S, L_.Kp, L_.nbs,
+        hipLaunchKernelGGL(k2_minplus_narrow, dim3(grid), dim3(NAR_NW * 64), lds_bytes, st,
+                           (const StepEntry*)(ws + L_.step_off),
+                           (const uint16_t*)(ws + L_.bcum_off), (const int32_t*)(ws + L_.tmeta_off),
+                           (const int32_t*)(ws + L_.order_off), (int32_t*)(ws + L_.ctrl_off),
+                           (uint16_t*)(ws + L_.frow_off), L_.N, L_.S, L_.Kp, L_.nbs,
                            L_.row_stride);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     for (int c = top_wide; c >= 0; --c) {
-        const int nwc = CLS_WAVES[c];
-        size_t lds_bytes = (size_t)4 * (PADB + nwc * WIDE_CHUNK * 2) + 16;
-        int per_cu = (int)(LDS_PER_CU / lds_bytes);
-        if (per_cu > 32 / nwc) per_cu = 32 / nwc;
-        if (per_cu < 1) per_cu = 1;
-        long long grid = (long long)cus * per_cu;
-        if (grid > L_.N) grid = L_.N;
-        hipLaunchKernelGGL(k2_minplus_wide, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st, w0,
-                           bcum, tmeta, order, ctrl, frow, L_.N, L_.S, L_.Kp, L_.nbs,
-                           L_.row_stride, c);
-        e = hipGetLastError();
+        e = class_copies(c, mask) == 2 ? launch_wide_class<2>(L_, ws, st, c, cus)
+                                       : launch_wide_class<4>(L_, ws, st, c, cus);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(PROBE_THREADS) void k_lds_probe(uint32_t* __restric
     for (int x = threadIdx.x; x < PROBE_LDS / 4; x += PROBE_THREADS) lds[x] = x;
     __syncthreads();
     // 1024 lanes * WIDTH bytes per sweep; four sweeps 16 KB apart per block of reads
-    const uint32_t addr = (uint32_t)(uintptr_t)lds + (threadIdx.x * WIDTH) % 16384 + MIS;
+    const uint32_t addr = (uint32_t)(uintptr_t)lds + (threadIdx.x * WIDTH) % 16384 + (MIS > 0 ? MIS : 0);
     uint32_t acc = 0;
     for (int it = 0; it < iters; ++it) {
         if constexpr (WIDTH == 4) {
@@ -35,6 +35,30 @@ __global__ __launch_bounds__(PROBE_THREADS) void k_lds_probe(uint32_t* __restric
                 "s_waitcnt lgkmcnt(0)"
                 : "=v"(a), "=v"(b), "=v"(c), "=v"(d) : "v"(addr));
             acc ^= a ^ b ^ c ^ d;
+        } else if constexpr (WIDTH == 8 && MIS == -1) {
+            // two adjacent dwords through ds_read2_b32, base only 4-byte aligned
+            u32x2 a, b, c, d;
+            const uint32_t ad = addr + 4;
+            asm volatile(
+                "ds_read2_b32 %0, %4 offset1:1\n ds_read2_b32 %1, %5 offset1:1\n"
+                "ds_read2_b32 %2, %6 offset1:1\n ds_read2_b32 %3, %7 offset1:1\n"
+                "s_waitcnt lgkmcnt(0)"
+                : "=v"(a), "=v"(b), "=v"(c), "=v"(d)
+                : "v"(ad), "v"(ad + 16384), "v"(ad + 32768), "v"(ad + 49152));
+            acc ^= a.x ^ b.x ^ c.x ^ d.x;
+        } else if constexpr (WIDTH == 8 && MIS == -2) {
+            // two dwords 256 bytes apart through ds_read2st64_b32 (what a 4-byte
+            // unit-stride loop unrolled by two compiles to)
+            u32x2 a, b, c, d;
+            const uint32_t ad = (uint32_t)(uintptr_t)lds + (threadIdx.x & 63) * 4 +
+                                (threadIdx.x >> 6) * 512;
+            asm volatile(
+                "ds_read2st64_b32 %0, %4 offset1:1\n ds_read2st64_b32 %1, %5 offset1:1\n"
+                "ds_read2st64_b32 %2, %6 offset1:1\n ds_read2st64_b32 %3, %7 offset1:1\n"
+                "s_waitcnt lgkmcnt(0)"
+                : "=v"(a), "=v"(b), "=v"(c), "=v"(d)
+                : "v"(ad), "v"(ad + 16384), "v"(ad + 32768), "v"(ad + 49152));
+            acc ^= a.x ^ b.x ^ c.x ^ d.x;
         } else if constexpr (WIDTH == 8) {
             u32x2 a, b, c, d;
             asm volatile(
@@ -54,6 +78,38 @@ __global__ __launch_bounds__(PROBE_THREADS) void k_lds_probe(uint32_t* __restric
         }
     }
     if (acc == 0x12345678u) sink[0] = acc;  // keeps the reads alive
+}
+
+// VALU issue-rate probe: every lane runs `iters` rounds of 16 independent
+// instructions of one kind (or add/min alternating), nothing else.
+template <int OP>
+__global__ __launch_bounds__(256) void k_valu_probe(uint32_t* __restrict__ sink, int iters,
+                                                    uint32_t seed)
+{
+    uint32_t r[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) r[j] = seed * (threadIdx.x + 1) + j;
+    const uint32_t c = seed | 0x00010001u;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if constexpr (OP == 0) asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+            if constexpr (OP == 1) asm volatile("v_pk_min_u16 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+            if constexpr (OP == 2) asm volatile("v_add_u32 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+            if constexpr (OP == 3) asm volatile("v_min_u32 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+            if constexpr (OP == 4) {
+                if (j & 1)
+                    asm volatile("v_pk_min_u16 %0, %0, %1" : "+v"(r[j]) : "v"(r[j - 1]));
+                else
+                    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+            }
+            if constexpr (OP == 5) asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(r[j]) : "s"(c));
+        }
+    }
+    uint32_t x = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) x ^= r[j];
+    if (x == 0x12345678u) sink[0] = x;
 }
 
 template <int WIDTH, int MIS>
@@ -80,11 +136,26 @@ hipError_t launch_lds_probe(int width, int misalign, int iters, int blocks, uint
     PROBE_CASE(8, 0);
     PROBE_CASE(8, 4);
     PROBE_CASE(8, 2);
+    PROBE_CASE(8, -1);
+    PROBE_CASE(8, -2);
     PROBE_CASE(16, 0);
     PROBE_CASE(16, 8);
     PROBE_CASE(16, 4);
     PROBE_CASE(16, 2);
 #undef PROBE_CASE
+    return hipErrorInvalidValue;
+}
+
+// one launch issues blocks * 256 lanes * iters * 16 instructions
+hipError_t launch_valu_probe(int op, int iters, int blocks, uint32_t* sink, hipStream_t st)
+{
+#define VALU_CASE(O) \
+    if (op == O) { \
+        hipLaunchKernelGGL(k_valu_probe<O>, dim3(blocks), dim3(256), 0, st, sink, iters, 3u); \
+        return hipGetLastError(); \
+    }
+    VALU_CASE(0) VALU_CASE(1) VALU_CASE(2) VALU_CASE(3) VALU_CASE(4) VALU_CASE(5)
+#undef VALU_CASE
     return hipErrorInvalidValue;
 }
 

@@ -2,7 +2,28 @@
 // launches.  No allocation, no synchronisation, no state.
 #include "themis_internal.h"
 
+#include <cstdlib>
+
 using namespace themis;
+
+namespace themis {
+
+// Classes 10..16 wavefronts (rows of more than 8192 cells) keep two row copies.
+// THEMIS_WIDE_COPIES_MASK overrides the choice for tuning runs.
+int wide_copies_mask()
+{
+    static const int mask = [] {
+        const char* e = std::getenv("THEMIS_WIDE_COPIES_MASK");
+        if (e && *e) return (int)std::strtol(e, nullptr, 0) & ((1 << N_WIDE_CLS) - 1);
+        int m = 0;
+        for (int c = 0; c < N_WIDE_CLS; ++c)
+            if (CLS_WAVES[c] > 8) m |= 1 << c;
+        return m;
+    }();
+    return mask;
+}
+
+}  // namespace themis
 
 namespace {
 
@@ -175,6 +196,15 @@ int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32
     if (iters < 1 || blocks < 1 || blocks > 65536) return THEMIS_ERR_SHAPE;
     hipError_t e = launch_lds_probe(width, misalign, iters, blocks, d_sink,
                                     static_cast<hipStream_t>(stream));
+    if (e == hipErrorInvalidValue) return THEMIS_ERR_SHAPE;
+    return e == hipSuccess ? THEMIS_OK : THEMIS_ERR_LAUNCH;
+}
+
+int themis_probe_valu(int op, int iters, int blocks, uint32_t* d_sink, void* stream)
+{
+    if (!d_sink) return THEMIS_ERR_NULL;
+    if (iters < 1 || blocks < 1 || blocks > 65536) return THEMIS_ERR_SHAPE;
+    hipError_t e = launch_valu_probe(op, iters, blocks, d_sink, static_cast<hipStream_t>(stream));
     if (e == hipErrorInvalidValue) return THEMIS_ERR_SHAPE;
     return e == hipSuccess ? THEMIS_OK : THEMIS_ERR_LAUNCH;
 }

@@ -72,10 +72,18 @@ __host__ __device__ inline int wide_copy_bytes(int waves)
     return WIDE_PAD_BYTES + waves * WIDE_CHUNK * 2;
 }
 
-// lt = 4h - m: read copy m, h quads (8 bytes each) below the lane's own quad.
-__host__ __device__ inline uint32_t wide_shift(uint32_t lt, int copy_bytes)
+// Row copies a work class keeps: four (64-bit reads) where two workgroups of
+// the class still fit a compute unit's LDS, two (32-bit reads) for the longest
+// rows, which would otherwise be alone on their compute unit.
+int wide_copies_mask();  // bit c set: wide class c keeps two copies
+__host__ __device__ inline int class_copies(int cls, int mask) { return (mask >> cls) & 1 ? 2 : 4; }
+
+// Four copies: lt = 4h - m, read copy m, h quads (8 bytes) below the lane's quad.
+// Two copies:  lt = 2h - m, read copy m, h pairs (4 bytes) below the lane's pair.
+__host__ __device__ inline uint32_t wide_shift(uint32_t lt, int copies, int copy_bytes)
 {
-    return ((0u - lt) & 3u) * (uint32_t)copy_bytes - 8u * ((lt + 3u) >> 2);
+    return copies == 4 ? ((0u - lt) & 3u) * (uint32_t)copy_bytes - 8u * ((lt + 3u) >> 2)
+                       : (lt & 1u) * (uint32_t)copy_bytes - 4u * ((lt + 1u) >> 1);
 }
 
 // Narrow kernel: 16 wavefronts x 1024 dwords; copy A holds cells (2j, 2j+1) in
@@ -157,5 +165,7 @@ hipError_t launch_count_relaxations(const Layout& L, const char* ws,
 
 hipError_t launch_lds_probe(int width, int misalign, int iters, int blocks, uint32_t* sink,
                             hipStream_t st);
+
+hipError_t launch_valu_probe(int op, int iters, int blocks, uint32_t* sink, hipStream_t st);
 
 }  // namespace themis

@@ -25,7 +25,7 @@ EXPORTS = [
     "themis_version", "themis_check_problem", "themis_workspace_bytes",
     "themis_solve_joint", "themis_solve_vertical", "themis_stage_candidates",
     "themis_stage_minplus", "themis_stage_backtrack", "themis_export_candidates",
-    "themis_count_relaxations", "themis_probe_lds_read",
+    "themis_count_relaxations", "themis_probe_lds_read", "themis_probe_valu",
 ]
 
 
@@ -74,6 +74,8 @@ def lib():
         L.themis_count_relaxations.argtypes = [P, vp, sz, vp, vp]
         L.themis_probe_lds_read.restype = ctypes.c_int
         L.themis_probe_lds_read.argtypes = [ctypes.c_int] * 4 + [vp, vp]
+        L.themis_probe_valu.restype = ctypes.c_int
+        L.themis_probe_valu.argtypes = [ctypes.c_int] * 3 + [vp, vp]
         _lib = L
     return _lib
 
@@ -183,6 +185,11 @@ def themis_probe_lds_read(width, misalign, iters, blocks, sink, stream=None):
     _chk("themis_probe_lds_read", lib().themis_probe_lds_read(
         int(width), int(misalign), int(iters), int(blocks), _dp(sink, torch.int32),
         _stream(stream)))
+
+
+def themis_probe_valu(op, iters, blocks, sink, stream=None):
+    _chk("themis_probe_valu", lib().themis_probe_valu(
+        int(op), int(iters), int(blocks), _dp(sink, torch.int32), _stream(stream)))
 
 
 # ---------------------------------------------------------------- conveniences

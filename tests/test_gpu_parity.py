@@ -159,6 +159,26 @@ def test_large_coefficients_and_batches(T, oracle):
     assert (want[0] == 0).any()
 
 
+def test_rows_longer_than_the_staging_buffer(T, oracle):
+    """More than 512 feasible candidates per model: the min-plus stage walks
+    such rows in parts."""
+    rng = np.random.default_rng(8)
+    n, S = 24, 3
+    coef = np.stack([rng.integers(500, 3000, size=(n, S)), rng.integers(50, 400, size=(n, S)),
+                     rng.integers(0, 3, size=(n, S)), rng.integers(20, 60, size=(n, S)),
+                     rng.integers(1, 200, size=(n, S))], axis=-1).astype(np.int32)
+    lam = rng.integers(5000, 40000, size=n).astype(np.int32)
+    slo = rng.integers(1_500, 9_000, size=n).astype(np.int32)
+    w = wl.Workload("longrows", wl.JOINT, n, S, 100, [1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32],
+                    100, 10, 9_000, False, coef, lam, slo)
+    lt, _, _ = oracle.candidates(w)
+    assert ((lt >= 0).sum(axis=2) > 512).any()
+    want = oracle.solve(w, threads=8)
+    got = gpu_solve(T, w)
+    assert_same(got, want)
+    assert (want[0] == 0).any()
+
+
 def test_shared_coefficients(T, oracle):
     w = wl.workload(4, 333)
     want = oracle.solve(w, threads=8)
