@@ -96,7 +96,8 @@ __global__ __launch_bounds__(256) void k1_validate(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     int32_t* __restrict__ tmeta, int32_t* __restrict__ order, int32_t* __restrict__ ctrl,
-    uint32_t N, uint32_t S, int32_t r_max, uint32_t tick, int32_t slo_max, int coef_shared)
+    uint32_t N, uint32_t S, int32_t r_max, uint32_t tick, int32_t slo_max, int coef_shared,
+    int merge_to)
 {
     uint32_t i = blockIdx.x * 256u + threadIdx.x;
     int cls = -1;
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(256) void k1_validate(
         }
         int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
         tmeta[i] = T;
-        if (ok) cls = class_of_budget(T);
+        if (ok) cls = effective_class(T, merge_to);
     }
     const unsigned lane = threadIdx.x & 63u;
     for (int c = 0; c < N_CLS; ++c) {
@@ -149,7 +150,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ tmeta, StepEntry* __restrict__ step_tab,
     uint32_t* __restrict__ tag_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
     uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, int coef_shared,
-    uint32_t G, uint32_t nb, uint32_t nbs, int copies_mask)
+    uint32_t G, uint32_t nb, uint32_t nbs, int copies_mask, int merge_to)
 {
     extern __shared__ uint32_t smem[];
     const uint32_t R = 256u / G;
@@ -203,7 +204,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     __syncthreads();
     if (live) {
         // the LDS geometry the min-plus stage will use for this instance
-        const int cls = T >= 0 ? class_of_budget(T) : 0;
+        const int cls = T >= 0 ? effective_class(T, merge_to) : 0;
         const int copy_bytes = wide_copy_bytes(CLS_WAVES[cls == NARROW_CLS ? 0 : cls]);
         const int copies = class_copies(cls, copies_mask);
         for (uint32_t kk = g; kk < Kp; kk += G) {
@@ -277,11 +278,12 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
     int32_t* tmeta = (int32_t*)(ws + L.tmeta_off);
     int32_t* ctrl = (int32_t*)(ws + L.ctrl_off);
+    const MinplusPlan plan = make_plan(L);
     hipLaunchKernelGGL(k1_reset_ctrl, dim3(1), dim3(64), 0, st, ctrl);
     hipLaunchKernelGGL(k1_validate, dim3((L.N + 255) / 256), dim3(256), 0, st, d_coef,
                        d_lambda, d_slo_us, d_r_fixed, tmeta, (int32_t*)(ws + L.order_off), ctrl,
                        (uint32_t)L.N, (uint32_t)L.S, p.r_max, (uint32_t)p.tick_us,
-                       p.slo_max_us, p.coef_shared);
+                       p.slo_max_us, p.coef_shared, plan.merge_to);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -295,7 +297,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                        (StepEntry*)(ws + L.step_off), (uint32_t*)(ws + L.tag_off),
                        (uint16_t*)(ws + L.bcum_off), bl, rows, (uint32_t)L.S, (uint32_t)L.K,
                        (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us, p.coef_shared, G,
-                       (uint32_t)L.nb, (uint32_t)L.nbs, wide_copies_mask());
+                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to);
     return hipGetLastError();
 }
 

@@ -259,28 +259,71 @@ __device__ __forceinline__ void publish_pair(char* p, int CSB, uint32_t v)
     *reinterpret_cast<volatile uint16_t*>(p + CSB) = (uint16_t)(v >> 16);
 }
 
+// Entries of one row held in registers on their way from HBM to the LDS
+// staging buffer (loaded before a model's sweeps, stored after them).
+constexpr int PREFETCH = 4;  // entries per thread
+
+struct RowPrefetch {
+    StepEntry e[PREFETCH];
+    int cnt;  // entries of the row to stage (at most CAND_BUF); 16 zero entries follow
+};
+
+__device__ __forceinline__ void prefetch_row(RowPrefetch& pf, const StepEntry* grow, int cnt)
+{
+    pf.cnt = cnt;
+#pragma unroll
+    for (int j = 0; j < PREFETCH; ++j) {
+        const int x = (int)threadIdx.x + j * (int)blockDim.x;
+        pf.e[j].shift = 0u;
+        pf.e[j].cost2 = 0u;
+        if (x < cnt) pf.e[j] = grow[x];
+    }
+}
+
+__device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntry* grow,
+                                           StepEntry* cbuf)
+{
+#pragma unroll
+    for (int j = 0; j < PREFETCH; ++j) {
+        const int x = (int)threadIdx.x + j * (int)blockDim.x;
+        if (x < pf.cnt + 16) cbuf[x] = pf.e[j];
+    }
+    // whatever the registers did not cover
+    for (int x = (int)threadIdx.x + PREFETCH * (int)blockDim.x; x < pf.cnt + 16;
+         x += (int)blockDim.x) {
+        StepEntry se;
+        se.shift = 0u;
+        se.cost2 = 0u;
+        if (x < pf.cnt) se = grow[x];
+        cbuf[x] = se;
+    }
+}
+
 // The positions of a row cost very different amounts of work (position p is
 // reached by bcum[p+1] entries), so they are not dealt out in advance: the
 // wavefronts of the workgroup take them one at a time from a counter in LDS,
-// most expensive first.  A finished position goes straight to the HBM row;
-// once every wavefront is done with the old row, the workgroup reads the new
-// one back (it is still in L2) and spreads it over the LDS copies.
+// most expensive first.  A finished position goes to the HBM row at once; once
+// every wavefront is done with the old row, the workgroup reads the new one
+// back (it is still in L2) and spreads it over the LDS copies.  (Keeping a
+// second set of copies to publish into directly costs more in occupancy than
+// the round trip through L2 does.)
 template <int COPIES>
 __global__ __launch_bounds__(1024) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
     int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int N, int S, int Kp, int nbs,
-    int row_stride, int cls)
+    int row_stride, int cls, int cand_buf)
 {
     using G = Geo<COPIES>;
     extern __shared__ uint32_t lds[];
     const int CSB = wide_copy_bytes(CLS_WAVES[cls]);  // bytes per copy: pad + the longest row
+    const int SETB = COPIES * CSB;                    // bytes of all copies
     char* const ldsb = reinterpret_cast<char*>(lds);
     // after the copies: a dword for the instance queue, one for the position
-    // counter, then the staged entries
-    volatile uint32_t* const slot = lds + COPIES * (CSB / 4);
-    int* const next_pos = reinterpret_cast<int*>(lds + COPIES * (CSB / 4) + 1);
-    StepEntry* const cbuf = reinterpret_cast<StepEntry*>(ldsb + COPIES * CSB + 16);
+    // counter, then the staging buffer for cand_buf (+16) candidate entries
+    volatile uint32_t* const slot = reinterpret_cast<volatile uint32_t*>(ldsb + SETB);
+    int* const next_pos = reinterpret_cast<int*>(ldsb + SETB + 4);
+    StepEntry* const cbuf = reinterpret_cast<StepEntry*>(ldsb + SETB + 16);
     const u32x2* const ent = reinterpret_cast<const u32x2*>(cbuf);
 
     const int tid = threadIdx.x;
@@ -303,7 +346,16 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                 lds[m * (CSB / 4) + x] = h0 | (h1 << 16);
             }
         }
-        // (the barrier after staging the first model's entries also covers this)
+        {
+            // entries of the first model
+            const size_t row = (size_t)i * S + (S - 1);
+            const int n_all = as_constant(bcum + row * nbs)[npos];
+            RowPrefetch pf;
+            prefetch_row(pf, step_tab + row * Kp, n_all < cand_buf ? n_all : cand_buf);
+            commit_row(pf, step_tab + row * Kp, cbuf);
+            if (tid == 0) *next_pos = npos - 1;
+        }
+        __syncthreads();
 
         for (int s = S - 1; s >= 0; --s) {
             const size_t row = (size_t)i * S + s;
@@ -312,17 +364,17 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
             uint16_t* const out = frow + row * row_stride;
             const int n_all = bc[npos];  // entries that reach the top position: all feasible ones
 
-            if (n_all <= CAND_BUF) {
-                // the whole row fits the staging buffer (the usual case)
-                for (int x = tid; x < n_all + 16; x += (int)blockDim.x) {
-                    StepEntry se;
-                    se.shift = 0u;
-                    se.cost2 = 0u;
-                    if (x < n_all) se = grow[x];
-                    cbuf[x] = se;  // 16 harmless entries behind the row feed the look-ahead
-                }
-                if (tid == 0) *next_pos = npos - 1;
-                __syncthreads();
+            // start fetching the next model's entries; they are stored after the sweeps
+            RowPrefetch pf;
+            const StepEntry* grow_next = grow;
+            if (s > 0) {
+                const int n_next = as_constant(bcum + (row - 1) * nbs)[npos];
+                grow_next = step_tab + (row - 1) * Kp;
+                prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
+            }
+
+            if (n_all <= cand_buf) {
+                // the whole row is in the staging buffer (the usual case)
                 for (;;) {
                     int p = 0;
                     if (lane == 0) p = atomicSub(next_pos, 1);
@@ -336,7 +388,8 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                 }
             } else {
                 // a long row goes through the buffer in parts; every wavefront keeps
-                // its positions (w, w + nw, ...) across the parts
+                // its positions (w, w + nw, ...) across the parts, with the partial
+                // minimum parked in the HBM row in between
                 const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
                 const int nw = (int)blockDim.x >> 6;
                 for (int p0 = w; p0 < npos; p0 += nw) {
@@ -345,22 +398,23 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                     for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
                     finish_position<COPIES>(acc, out, p0, lane, T);  // start from "none"
                 }
-                for (int seg = 0; seg < n_all; seg += CAND_BUF) {
-                    const int cnt = n_all - seg < CAND_BUF ? n_all - seg : CAND_BUF;
-                    __syncthreads();  // sweeps of the previous part are done, stores are visible
-                    for (int x = tid; x < cnt + 16; x += (int)blockDim.x) {
-                        StepEntry se;
-                        se.shift = 0u;
-                        se.cost2 = 0u;
-                        if (x < cnt) se = grow[seg + x];
-                        cbuf[x] = se;
+                for (int seg = 0; seg < n_all; seg += cand_buf) {
+                    const int cnt = n_all - seg < cand_buf ? n_all - seg : cand_buf;
+                    if (seg) {
+                        __syncthreads();  // sweeps of the previous part are done
+                        for (int x = tid; x < cnt + 16; x += (int)blockDim.x) {
+                            StepEntry se;
+                            se.shift = 0u;
+                            se.cost2 = 0u;
+                            if (x < cnt) se = grow[seg + x];
+                            cbuf[x] = se;
+                        }
+                        __syncthreads();
                     }
-                    __syncthreads();
                     for (int p0 = w; p0 < npos; p0 += nw) {
                         const int n_p = bc[p0 + 1];
                         const int ke = n_p - seg < 0 ? 0 : (n_p - seg < cnt ? n_p - seg : cnt);
                         if (ke <= 0) continue;
-                        // resume from the partial minimum this wavefront stored earlier
                         uint32_t acc[AD];
 #pragma unroll
                         for (int q = 0; q < G::NE; ++q) {
@@ -384,7 +438,6 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
             if (s == 0) break;  // nothing reads the LDS copies of the last row
 
             __syncthreads();  // every wavefront is done with the old row; the new one is stored
-            // bring the new row back and spread it over the copies
             for (int el = tid; el * (G::ELT / 2) <= T; el += (int)blockDim.x) {
                 char* const at = ldsb + PADB + G::ELT * el;
                 if constexpr (COPIES == 4) {
@@ -394,7 +447,10 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                     publish_pair(at, CSB, *reinterpret_cast<const uint32_t*>(out + 2 * el));
                 }
             }
-            // (the barrier after staging the next model's entries covers these writes)
+            // hand the next model its entries and its position counter
+            commit_row(pf, grow_next, cbuf);
+            if (tid == 0) *next_pos = npos - 1;
+            __syncthreads();
         }
         __syncthreads();  // last row's reads are done before the LDS is re-initialised
     }
@@ -498,46 +554,68 @@ int cu_count()
 constexpr size_t LDS_PER_CU = 160 * 1024;
 
 
+inline size_t wide_lds_bytes(int copies, int waves, int cand_buf)
+{
+    return (size_t)copies * wide_copy_bytes(waves) + 16 + (cand_buf + 16) * sizeof(StepEntry);
+}
+
+inline int wide_groups_per_cu(int copies, int waves, int cand_buf)
+{
+    int per_cu = (int)(LDS_PER_CU / wide_lds_bytes(copies, waves, cand_buf));
+    if (per_cu > 32 / waves) per_cu = 32 / waves;
+    return per_cu < 1 ? 1 : per_cu;
+}
+
 template <int COPIES>
 hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int cus)
 {
     const int nwc = CLS_WAVES[c];
-    const size_t lds_bytes =
-        (size_t)COPIES * wide_copy_bytes(nwc) + 16 + (CAND_BUF + 16) * sizeof(StepEntry);
+    const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
+    const size_t lds_bytes = wide_lds_bytes(COPIES, nwc, cand_buf);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_wide<COPIES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(LDS_PER_CU - 1024));
     if (e != hipSuccess) return e;
-    int per_cu = (int)(LDS_PER_CU / lds_bytes);
-    if (per_cu > 32 / nwc) per_cu = 32 / nwc;
-    if (per_cu < 1) per_cu = 1;
-    long long grid = (long long)cus * per_cu;
+    long long grid = (long long)cus * wide_groups_per_cu(COPIES, nwc, cand_buf);
     if (grid > L_.N) grid = L_.N;
     hipLaunchKernelGGL(k2_minplus_wide<COPIES>, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
                        (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
                        (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
                        (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off), L_.N, L_.S,
-                       L_.Kp, L_.nbs, L_.row_stride, c);
+                       L_.Kp, L_.nbs, L_.row_stride, c, cand_buf);
     return hipGetLastError();
 }
 
 }  // namespace
 
+MinplusPlan make_plan(const Layout& L_)
+{
+    MinplusPlan pl{};
+    pl.cus = cu_count();
+    pl.top = class_of_budget(L_.t_max);
+    pl.top_wide = pl.top == NARROW_CLS ? N_WIDE_CLS - 1 : pl.top;
+    pl.copies_mask = wide_copies_mask();
+    // few instances: one launch with the top class's geometry for all of them
+    const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
+    const long long resident =
+        (long long)pl.cus * wide_groups_per_cu(class_copies(pl.top_wide, pl.copies_mask),
+                                               CLS_WAVES[pl.top_wide], cand_buf);
+    pl.merge_to = L_.N <= 4 * resident ? pl.top_wide : 0;
+    return pl;
+}
+
 hipError_t launch_minplus(const themis_problem_t&, const Layout& L_, char* ws, hipStream_t st)
 {
-    const int cus = cu_count();
-    const int top = class_of_budget(L_.t_max);  // no instance can be in a higher class
-    const int top_wide = top == NARROW_CLS ? N_WIDE_CLS - 1 : top;
-    const int mask = wide_copies_mask();
+    const MinplusPlan pl = make_plan(L_);
     hipError_t e;
 
     // longest rows first: they take longest, so they should not start last
-    if (top == NARROW_CLS) {
+    if (pl.top == NARROW_CLS) {
         size_t lds_bytes = (size_t)(2 * NAR_BOFF + 4) * sizeof(uint32_t);
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_narrow),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        int grid = L_.N < cus ? L_.N : cus;
+        int grid = L_.N < pl.cus ? L_.N : pl.cus;
         hipLaunchKernelGGL(k2_minplus_narrow, dim3(grid), dim3(NAR_NW * 64), lds_bytes, st,
                            (const StepEntry*)(ws + L_.step_off),
                            (const uint16_t*)(ws + L_.bcum_off), (const int32_t*)(ws + L_.tmeta_off),
@@ -547,9 +625,9 @@ hipError_t launch_minplus(const themis_problem_t&, const Layout& L_, char* ws, h
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    for (int c = top_wide; c >= 0; --c) {
-        e = class_copies(c, mask) == 2 ? launch_wide_class<2>(L_, ws, st, c, cus)
-                                       : launch_wide_class<4>(L_, ws, st, c, cus);
+    for (int c = pl.top_wide; c >= pl.merge_to; --c) {
+        e = class_copies(c, pl.copies_mask) == 2 ? launch_wide_class<2>(L_, ws, st, c, pl.cus)
+                                                 : launch_wide_class<4>(L_, ws, st, c, pl.cus);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

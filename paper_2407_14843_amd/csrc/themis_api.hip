@@ -8,17 +8,16 @@ using namespace themis;
 
 namespace themis {
 
-// Classes 10..16 wavefronts (rows of more than 8192 cells) keep two row copies.
-// THEMIS_WIDE_COPIES_MASK overrides the choice for tuning runs.
+// Every wide class keeps two row copies by default: the smaller LDS footprint
+// buys more resident wavefronts, which pays more than the wider reads of the
+// four-copy layout.  THEMIS_WIDE_COPIES_MASK (bit c = class c keeps two)
+// overrides the choice for tuning runs.
 int wide_copies_mask()
 {
     static const int mask = [] {
         const char* e = std::getenv("THEMIS_WIDE_COPIES_MASK");
         if (e && *e) return (int)std::strtol(e, nullptr, 0) & ((1 << N_WIDE_CLS) - 1);
-        int m = 0;
-        for (int c = 0; c < N_WIDE_CLS; ++c)
-            if (CLS_WAVES[c] > 8) m |= 1 << c;
-        return m;
+        return (1 << N_WIDE_CLS) - 1;
     }();
     return mask;
 }

@@ -101,6 +101,25 @@ __host__ __device__ inline uint32_t narrow_shift(uint32_t lt)
                            : (uint32_t)NAR_CHUNK_DW - h);
 }
 
+// With few instances, one launch per class leaves the chip mostly idle and
+// pays a launch and a tail per class; then every wide class up to merge_to is
+// served by class merge_to's launch (its geometry fits all shorter rows).
+__host__ __device__ inline int effective_class(int T, int merge_to)
+{
+    const int c = class_of_budget(T);
+    return (c != NARROW_CLS && c < merge_to) ? merge_to : c;
+}
+
+struct Layout;
+struct MinplusPlan {
+    int cus;          // compute units of the current device
+    int top;          // highest class any instance can be in
+    int top_wide;     // highest wide class in use
+    int merge_to;     // see effective_class(); 0 = nothing merged
+    int copies_mask;  // see wide_copies_mask()
+};
+MinplusPlan make_plan(const Layout& L);
+
 // Workspace carve-up.  Every region starts on a 256-byte boundary.
 //   step   StepEntry [N*S][Kp] bucket-ordered; Kp = K rounded up to 8
 //   tag    u32 [N*S][Kp]       lt | k << 16 of the entry in the same slot
