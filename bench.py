@@ -26,6 +26,9 @@ N_CU, CLOCK_GHZ = 256, 2.4
 LDS_BYTES_PER_CLK_CU = 128          # ds_read path per compute unit
 LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
+# HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
+# profiles/); None until measured for the kernels as they stand.
+K2_HBM_TRAFFIC = {}
 
 
 def _events(n):
@@ -114,10 +117,11 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None):
     cand = w.n_inst * w.n_stage * w.n_cand * len(passes)
     k1_bytes = cand * 8 + w.n_inst * w.n_stage * 20 * len(passes)
     out["candidates_GBs"] = k1_bytes / (k_ms[0] * 1e-3) / 1e9 if k_ms[0] > 0 else None
-    # stage 2: 4 bytes read per relaxation + 4 bytes written per cell (int32-equivalent),
-    # of which this kernel physically moves 2 + 2*2 (16-bit cells, two copies written)
-    out["minplus_alg_bytes"] = relax * 4 + cells * 4
-    out["minplus_phys_bytes"] = relax * 2 + cells * 4
+    # stage 2, LDS bytes: 16-bit cells, so 2 bytes read per relaxation and 2 bytes
+    # written per cell into each of the two row copies; the generic figure for
+    # int32 cells (4 bytes per relaxation, 4 per cell) is kept beside it
+    out["minplus_lds_bytes"] = relax * 2 + cells * 4
+    out["minplus_int32_bytes"] = relax * 4 + cells * 4
     return out
 
 
@@ -207,7 +211,7 @@ def main():
 
     m = run_workload(themis, wl, a.workload, a.steps, a.warmup)
     k2_ms = m["kernel_ms"]["minplus"]
-    k2_gbs = m["minplus_alg_bytes"] / (k2_ms * 1e-3) / 1e9
+    k2_gbs = m["minplus_lds_bytes"] / (k2_ms * 1e-3) / 1e9
     line = {
         "metric": "joint-scaling DP solves/sec",
         "value": m["solves_per_s"],
@@ -228,11 +232,12 @@ def main():
         "feasible_fraction": m["feasible_fraction"],
         "kernel_ms": m["kernel_ms"],
         "roofline": {
-            "kernel": "k2_minplus", "bound": "lds", "achieved": k2_gbs, "peak": LDS_PEAK_GBS,
-            "unit": "GB/s", "frac": k2_gbs / LDS_PEAK_GBS, "traffic": None,
-            "bytes_per_launch": m["minplus_alg_bytes"],
-            "physical_bytes_per_launch": m["minplus_phys_bytes"],
-            "physical_frac": m["minplus_phys_bytes"] / (k2_ms * 1e-3) / 1e9 / LDS_PEAK_GBS,
+            "kernel": "k2_minplus_wide (all class launches of a step)", "bound": "lds",
+            "achieved": k2_gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s",
+            "frac": k2_gbs / LDS_PEAK_GBS, "traffic": K2_HBM_TRAFFIC.get(m["workload"]),
+            "bytes_per_launch": m["minplus_lds_bytes"],
+            "int32_equivalent_frac":
+                m["minplus_int32_bytes"] / (k2_ms * 1e-3) / 1e9 / LDS_PEAK_GBS,
             "valu_frac": (m["relaxations_executed"] / (k2_ms * 1e-3) / 1e9) / VALU_PEAK_GOPS,
         },
         "roofline_candidates": {
@@ -251,8 +256,10 @@ def main():
             others[o["workload"]] = {k: o[k] for k in (
                 "solves_per_s", "dp_cells_per_s", "relaxations_per_s", "ms_per_step",
                 "feasible_fraction", "kernel_ms", "candidates_GBs")}
-            others[o["workload"]]["minplus_lds_frac"] = (
-                o["minplus_alg_bytes"] / (o["kernel_ms"]["minplus"] * 1e-3) / 1e9 / LDS_PEAK_GBS)
+            k2s = o["kernel_ms"]["minplus"] * 1e-3
+            others[o["workload"]]["minplus_lds_frac"] = o["minplus_lds_bytes"] / k2s / 1e9 / LDS_PEAK_GBS
+            others[o["workload"]]["minplus_valu_frac"] = (
+                o["relaxations_executed"] / k2s / 1e9 / VALU_PEAK_GOPS)
         line["other_workloads"] = others
     if not a.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl, a.workload, 4096)
