@@ -13,73 +13,89 @@
 //   n     = ceil(lambda proc / (b 1e6))   joint,  or the given replicas
 //   queue = ceil((b-1) 1e6 n / lambda)
 //   lt    = ceil((proc + queue) / tick),  cost = n c
-// A candidate is dropped (lt = cost = -1) when n exceeds r_max, when the given
-// replicas cannot carry lambda, or when lt exceeds the instance's budget T.
+// A candidate is dropped when n exceeds r_max, when the given replicas cannot
+// carry lambda, or when lt exceeds the instance's budget T.
+#include <cstdlib>
+
 #include "themis_internal.h"
 
 namespace themis {
 namespace {
 
-// floor(n / d) for n < 2^53, 1 <= d < 2^32, quotient < 2^32.
-// A double-precision estimate (exact conversion, reciprocal refined by one
-// Newton step) is corrected by exact 64-bit integer arithmetic, so the result
-// does not depend on how the estimate rounds.  *rem receives n - q*d.
-__device__ __forceinline__ uint32_t floor_div_u64(uint64_t n, uint32_t d, uint64_t* rem)
+// All quantities of the model are integers below 2^53 (see the input rules in
+// themis.h), so they are carried in double precision, where sums, products and
+// fused multiply-adds of such integers are exact; gfx950 issues fp64 FMAs at the
+// full vector rate, while 64-bit integer multiplies and divides are several
+// times slower.
+
+// A reciprocal that is never above 1/d and at most 2^-44 (relative) below it:
+// hardware estimate, two Newton steps (enough to reach full precision from an
+// estimate good to only 2^-13), then a nudge downward.
+__device__ __forceinline__ double recip_below(double d)
 {
-    double dd = (double)d;
-    double r = __builtin_amdgcn_rcp(dd);
-    r = __builtin_fma(__builtin_fma(-dd, r, 1.0), r, r);
-    uint64_t q = (uint64_t)((double)n * r);
-    uint64_t prod = q * (uint64_t)d;
-    while (prod > n) { --q; prod -= d; }
-    while (n - prod >= d) { ++q; prod += d; }
-    *rem = n - prod;
-    return (uint32_t)q;
+    double r = __builtin_amdgcn_rcp(d);
+    r = __builtin_fma(__builtin_fma(-d, r, 1.0), r, r);
+    r = __builtin_fma(__builtin_fma(-d, r, 1.0), r, r);
+    return r * (1.0 - 0x1p-45);
 }
 
-__device__ __forceinline__ uint32_t ceil_div_u64(uint64_t n, uint32_t d)
+// ceil(n / d) for integers 0 <= n, 1 <= d, n + d < 2^53, quotient < 2^43, with
+// rd = recip_below(d).  ceil(n/d) = floor(m/d) for m = n + d - 1.  m * rd is
+// below m/d by less than one, so its floor is the true floor or one less; the
+// exact remainder m - q*d (one FMA) tells which.
+__device__ __forceinline__ double ceil_div_d(double n, double d, double rd)
 {
-    uint64_t rem;
-    uint32_t q = floor_div_u64(n, d, &rem);
-    return q + (rem != 0);
+    const double m = n + (d - 1.0);
+    const double q = __builtin_floor(m * rd);
+    const double r = __builtin_fma(-q, d, m);
+    return r >= d ? q + 1.0 : q;
 }
+
+// What every candidate of a row shares, prepared once per row.
+struct RowHdr {
+    double a, k, q, o;   // profile coefficients
+    double p;            // core cap
+    double lam, rlam;    // arrival rate and recip_below() of it
+    double slo, T;       // SLO in microseconds, budget in ticks (T < 0: invalid instance)
+    double n_given;      // replicas (vertical) or 0 (joint: derive)
+};
+
+// What every candidate with the same batch size shares.
+struct BatchHdr {
+    double b, b2;        // batch size and its square
+    double M, rM;        // b * 1e6 and recip_below() of it
+    double w;            // (b - 1) * 1e6
+};
 
 struct Cand {
     int32_t lt, cost;
 };
 
-// r_given <= 0: derive the replica count (joint); otherwise use it (vertical).
-__device__ __forceinline__ Cand eval_candidate(uint32_t a, uint32_t k, uint32_t q,
-                                               uint32_t p, uint32_t o, uint32_t lambda,
-                                               uint32_t slo_us, uint32_t T, uint32_t tick,
-                                               uint32_t c, uint32_t b, uint32_t r_max,
-                                               int32_t r_given)
+__device__ __forceinline__ Cand eval_candidate(const RowHdr& h, const BatchHdr& bh, double c,
+                                               double r_max, double tick, double rtick)
 {
     const Cand none{-1, -1};
-    // Anything whose latency exceeds slo_us also exceeds T ticks, so the tests
-    // against slo_us below only cut candidates that lt > T would cut anyway;
-    // they keep every later quotient inside 32 bits.
-    if (o > slo_us) return none;
-    uint64_t num = (uint64_t)a + (uint64_t)k * b + (uint64_t)q * b * b;
-    uint32_t d = c < p ? c : p;
-    if (num > (uint64_t)(slo_us - o) * d) return none;      // proc > slo_us
-    uint32_t proc = ceil_div_u64(num, d) + o;                // <= slo_us
-    uint64_t lp = (uint64_t)lambda * proc;                   // < 2^51
-    uint32_t M = b * 1000000u;                               // < 2^30
-    uint32_t n;
-    if (r_given <= 0) {
-        if (lp > (uint64_t)r_max * M) return none;           // needs > r_max replicas
-        n = ceil_div_u64(lp, M);
-        if (n < 1) n = 1;
+    const double d = c < h.p ? c : h.p;
+    const double num = __builtin_fma(h.q, bh.b2, __builtin_fma(h.k, bh.b, h.a));  // < 2^41
+    const double proc = ceil_div_d(num, d, recip_below(d)) + h.o;
+    // anything slower than the SLO also exceeds T ticks; cutting it here keeps
+    // every later product below 2^53
+    if (proc > h.slo) return none;
+    const double lp = h.lam * proc;  // < 2^51
+    double n;
+    if (h.n_given <= 0.0) {
+        if (lp > r_max * bh.M) return none;  // needs more than r_max replicas
+        n = ceil_div_d(lp, bh.M, bh.rM);
+        n = n < 1.0 ? 1.0 : n;
     } else {
-        n = (uint32_t)r_given;
-        if (lp > (uint64_t)n * M) return none;               // throughput too low
+        n = h.n_given;
+        if (lp > n * bh.M) return none;      // the given replicas cannot carry lambda
     }
-    uint64_t qn = (uint64_t)(b - 1) * 1000000u * n;          // < 2^45
-    if (qn > (uint64_t)(slo_us - proc) * lambda) return none; // proc + queue > slo_us
-    uint32_t lat = proc + ceil_div_u64(qn, lambda);          // <= slo_us < 2^31
-    uint32_t lt = (lat + tick - 1) / tick;
-    if (lt > T) return none;
+    const double qn = bh.w * n;              // < 2^45
+    if (qn > (h.slo - proc) * h.lam) return none;  // proc + queue > SLO
+    const double lat = proc + ceil_div_d(qn, h.lam, h.rlam);
+    const double lt = ceil_div_d(lat, tick, rtick);
+    if (lt > h.T) return none;
     return Cand{(int32_t)lt, (int32_t)(n * c)};
 }
 
@@ -142,20 +158,25 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 // rows are walked in steps of G).  Pass 1 evaluates every candidate, parks its
 // (lt, cost) in LDS and counts its bucket; after a prefix sum over the
 // buckets, pass 2 hands every entry a slot inside its bucket's range and
-// writes it to HBM in the two forms the later stages read.  The order inside a bucket is whatever
-// the LDS atomics yield; nothing downstream depends on it.
+// writes it to HBM in the two forms the later stages read.  The order inside a
+// bucket is whatever the LDS atomics yield; nothing downstream depends on it.
 __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     const int32_t* __restrict__ tmeta, StepEntry* __restrict__ step_tab,
     uint32_t* __restrict__ tag_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
-    uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, int coef_shared,
-    uint32_t G, uint32_t nb, uint32_t nbs, int copies_mask, int merge_to)
+    uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, double rtick,
+    int coef_shared, uint32_t G, uint32_t nb, uint32_t nbs, int copies_mask, int merge_to,
+    uint32_t inv_nbatch)
 {
-    extern __shared__ uint32_t smem[];
+    extern __shared__ double smem_d[];
     const uint32_t R = 256u / G;
-    // per local row: hist[MAX_BUCKETS + 1], cursor[MAX_BUCKETS + 1], then staging[Kp]
+    // doubles first (alignment): per-row headers, per-batch headers; then per
+    // local row hist[MAX_BUCKETS + 1], cursor[MAX_BUCKETS + 1], staging[Kp]
     constexpr uint32_t HB = MAX_BUCKETS + 1;
+    RowHdr* const hdr_all = reinterpret_cast<RowHdr*>(smem_d);
+    BatchHdr* const bhdr = reinterpret_cast<BatchHdr*>(hdr_all + R);
+    uint32_t* const smem = reinterpret_cast<uint32_t*>(bhdr + THEMIS_MAX_BATCH);
     uint32_t* const hist_all = smem;
     uint32_t* const cur_all = smem + R * HB;
     uint32_t* const stage_all = smem + 2 * R * HB;
@@ -168,22 +189,46 @@ __global__ __launch_bounds__(256) void k1_candidates(
     uint32_t* const stage = stage_all + rl * Kp;
 
     for (uint32_t x = threadIdx.x; x < 2 * R * HB; x += 256u) smem[x] = 0u;
+    if (threadIdx.x < (uint32_t)bl.n) {
+        const double b = (double)bl.b[threadIdx.x];
+        BatchHdr bh;
+        bh.b = b;
+        bh.b2 = b * b;
+        bh.M = b * 1.0e6;
+        bh.rM = recip_below(bh.M);
+        bh.w = (b - 1.0) * 1.0e6;
+        bhdr[threadIdx.x] = bh;
+    }
+    if (live && g == 0) {
+        const uint32_t i = row / S, s = row - i * S;
+        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
+        RowHdr h;
+        h.a = (double)cf[0];
+        h.k = (double)cf[1];
+        h.q = (double)cf[2];
+        h.p = (double)cf[3];
+        h.o = (double)cf[4];
+        h.lam = (double)lambda[i];
+        h.T = (double)tmeta[i];
+        h.rlam = h.T >= 0.0 ? recip_below(h.lam) : 0.0;
+        h.slo = (double)slo_us[i];
+        h.n_given = r_fixed ? (double)r_fixed[(size_t)i * S + s] : 0.0;
+        hdr_all[rl] = h;
+    }
     __syncthreads();
 
     int32_t T = -1;
     if (live) {
-        const uint32_t i = row / S, s = row - i * S;
-        T = tmeta[i];
-        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
-        const uint32_t a = cf[0], kc = cf[1], q = cf[2], pcap = cf[3], o = cf[4];
-        const uint32_t lam = lambda[i], slo = slo_us[i];
-        const int32_t rgiven = r_fixed ? r_fixed[(size_t)i * S + s] : 0;
+        const RowHdr h = hdr_all[rl];
+        T = (int32_t)h.T;
         for (uint32_t kk = g; kk < Kp; kk += G) {
             uint32_t w0 = TAG_NONE;  // lt | cost << 16
             if (T >= 0 && kk < K) {
-                const uint32_t c = kk / (uint32_t)bl.n + 1, j = kk % (uint32_t)bl.n;
-                const Cand cd = eval_candidate(a, kc, q, pcap, o, lam, slo, (uint32_t)T, tick, c,
-                                               bl.b[j], r_max, rgiven);
+                // kk / n_batch by a 2^32-scaled reciprocal (exact for kk < 2^13)
+                const uint32_t ci = bl.n == 1 ? kk : __umulhi(kk, inv_nbatch);
+                const uint32_t j = kk - ci * (uint32_t)bl.n;
+                const Cand cd = eval_candidate(h, bhdr[j], (double)(ci + 1), (double)r_max,
+                                               (double)tick, rtick);
                 if (cd.lt >= 0) w0 = (uint32_t)cd.lt | ((uint32_t)cd.cost << 16);
             }
             stage[kk] = w0;
@@ -192,13 +237,25 @@ __global__ __launch_bounds__(256) void k1_candidates(
         }
     }
     __syncthreads();
-    if (live) {
-        // exclusive prefix over the buckets; bucket nb (infeasible) comes last
-        for (uint32_t j = g; j <= nb; j += G) {
-            uint32_t c = 0;
-            for (uint32_t b = 0; b < j; ++b) c += hist[b];
-            cur[j] = c;
-            bcum[(size_t)row * nbs + j] = (uint16_t)c;
+    if (live && g < 64) {
+        // exclusive prefix over the buckets by the row's first wavefront (G is a
+        // multiple of 64, so these 64 threads are one wavefront); bucket nb
+        // (infeasible) comes last and starts where the feasible ones end
+        const uint32_t v = g < nb ? hist[g] : 0u;
+        uint32_t incl = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t t = __shfl_up(incl, d, 64);
+            if ((int)g >= d) incl += t;
+        }
+        const uint32_t excl = incl - v;
+        if (g <= nb) {
+            cur[g] = excl;
+            bcum[(size_t)row * nbs + g] = (uint16_t)excl;
+        }
+        if (g == 63 && nb == 64) {
+            cur[64] = incl;
+            bcum[(size_t)row * nbs + 64] = (uint16_t)incl;
         }
     }
     __syncthreads();
@@ -287,17 +344,23 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
+    // threads per row; THEMIS_K1_G overrides for tuning runs
     uint32_t G = 64;
-    while (G < 256u && G < (uint32_t)L.Kp) G <<= 1;
+    if (const char* e = std::getenv("THEMIS_K1_G")) {
+        G = (uint32_t)std::atoi(e);
+    }
     const uint32_t R = 256u / G;
     const uint32_t rows = (uint32_t)L.N * L.S;
-    const size_t lds = (size_t)(2 * R * (MAX_BUCKETS + 1) + R * L.Kp) * sizeof(uint32_t);
+    const size_t lds = R * sizeof(RowHdr) + THEMIS_MAX_BATCH * sizeof(BatchHdr) +
+                       (size_t)(2 * R * (MAX_BUCKETS + 1) + R * L.Kp) * sizeof(uint32_t);
     hipLaunchKernelGGL(k1_candidates, dim3((rows + R - 1) / R), dim3(256), lds, st, d_coef,
                        d_lambda, d_slo_us, d_r_fixed, (const int32_t*)tmeta,
                        (StepEntry*)(ws + L.step_off), (uint32_t*)(ws + L.tag_off),
                        (uint16_t*)(ws + L.bcum_off), bl, rows, (uint32_t)L.S, (uint32_t)L.K,
-                       (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us, p.coef_shared, G,
-                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to);
+                       (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us,
+                       (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, G,
+                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
+                       (uint32_t)((0x100000000ull + p.n_batch - 1) / p.n_batch));
     return hipGetLastError();
 }
 
