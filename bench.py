@@ -28,7 +28,7 @@ LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {}
+K2_HBM_TRAFFIC = {"w1-joint-4096x5": 117107021, "w3-joint-65536x8": 10943633238}
 
 
 def _events(n):
@@ -193,6 +193,9 @@ def main():
     ap.add_argument("--others", action="store_true",
                     help="also time the other numbered workloads (fewer steps)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="only run one 1 GiB device-to-device copy kernel (reference point for "
+                         "HBM byte counters)")
     ap.add_argument("--lds-probe", action="store_true",
                     help="only measure LDS read bandwidth (roofline denominator)")
     a = ap.parse_args()
@@ -207,6 +210,15 @@ def main():
     themis.lib()
     if a.lds_probe:
         lds_probe()
+        return
+    if a.copy_calib:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calib_bytes_read": src.numel() * 4,
+                          "copy_calib_bytes_written": dst.numel() * 4}), flush=True)
         return
 
     m = run_workload(themis, wl, a.workload, a.steps, a.warmup)
