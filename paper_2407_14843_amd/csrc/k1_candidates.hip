@@ -15,8 +15,6 @@
 //   lt    = ceil((proc + queue) / tick),  cost = n c
 // A candidate is dropped when n exceeds r_max, when the given replicas cannot
 // carry lambda, or when lt exceeds the instance's budget T.
-#include <cstdlib>
-
 #include "themis_internal.h"
 
 namespace themis {
@@ -51,12 +49,12 @@ __device__ __forceinline__ double ceil_div_d(double n, double d, double rd)
     return r >= d ? q + 1.0 : q;
 }
 
-// What every candidate of a row shares, prepared once per row.
+// What every candidate of a row shares.
 struct RowHdr {
     double a, k, q, o;   // profile coefficients
     double p;            // core cap
     double lam, rlam;    // arrival rate and recip_below() of it
-    double slo, T;       // SLO in microseconds, budget in ticks (T < 0: invalid instance)
+    double slo, T;       // SLO in microseconds, budget in ticks
     double n_given;      // replicas (vertical) or 0 (joint: derive)
 };
 
@@ -67,15 +65,16 @@ struct BatchHdr {
     double w;            // (b - 1) * 1e6
 };
 
-struct Cand {
-    int32_t lt, cost;
+// Latency in ticks and replica count of candidate (d = min(c,p), b), or lt < 0
+// when it is infeasible.  Both are the same for every c >= p.
+struct Eval {
+    int32_t lt, n;
 };
 
-__device__ __forceinline__ Cand eval_candidate(const RowHdr& h, const BatchHdr& bh, double c,
+__device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& bh, double d,
                                                double r_max, double tick, double rtick)
 {
-    const Cand none{-1, -1};
-    const double d = c < h.p ? c : h.p;
+    const Eval none{-1, 0};
     const double num = __builtin_fma(h.q, bh.b2, __builtin_fma(h.k, bh.b, h.a));  // < 2^41
     const double proc = ceil_div_d(num, d, recip_below(d)) + h.o;
     // anything slower than the SLO also exceeds T ticks; cutting it here keeps
@@ -96,7 +95,7 @@ __device__ __forceinline__ Cand eval_candidate(const RowHdr& h, const BatchHdr& 
     const double lat = proc + ceil_div_d(qn, h.lam, h.rlam);
     const double lt = ceil_div_d(lat, tick, rtick);
     if (lt > h.T) return none;
-    return Cand{(int32_t)lt, (int32_t)(n * c)};
+    return Eval{(int32_t)lt, (int32_t)n};
 }
 
 __device__ __forceinline__ bool in_range(int32_t v, int32_t lo, int32_t hi)
@@ -153,109 +152,110 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 
 // Candidate evaluation plus a counting sort of each row by bucket.
 //
-// A workgroup of 256 threads handles R = 256/G rows ((instance, model) pairs),
-// G threads per row, G = Kp rounded up to a power of two (at most 256; longer
-// rows are walked in steps of G).  Pass 1 evaluates every candidate, parks its
-// (lt, cost) in LDS and counts its bucket; after a prefix sum over the
-// buckets, pass 2 hands every entry a slot inside its bucket's range and
-// writes it to HBM in the two forms the later stages read.  The order inside a
-// bucket is whatever the LDS atomics yield; nothing downstream depends on it.
+// One thread per (row, batch size); a workgroup of 256 threads covers
+// RPW = 256 / n_batch rows ((instance, model) pairs).  The thread walks the
+// cores c = 1 .. c_max: the latency model only depends on min(c, p), so it is
+// evaluated for c <= p and reused (with cost n*c) beyond.  Pass 1 parks every
+// candidate's (lt, cost) in LDS and counts its bucket; a wavefront scan turns
+// the counts into bucket offsets; pass 2 hands every entry a slot inside its
+// bucket's range and writes it to HBM in the form the min-plus stage reads.
+// The order inside a bucket is whatever the LDS atomics yield; nothing
+// downstream depends on it.
+constexpr uint32_t STAGE_NONE = 0xFFFFu;  // lt field of an infeasible candidate in LDS
+
 __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     const int32_t* __restrict__ tmeta, StepEntry* __restrict__ step_tab,
-    uint32_t* __restrict__ tag_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
-    uint32_t S, uint32_t K, uint32_t Kp, uint32_t r_max, uint32_t tick, double rtick,
-    int coef_shared, uint32_t G, uint32_t nb, uint32_t nbs, int copies_mask, int merge_to,
-    uint32_t inv_nbatch)
+    uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows, uint32_t S, uint32_t K, uint32_t Kp,
+    uint32_t c_max, uint32_t r_max, uint32_t tick, double rtick, int coef_shared, uint32_t RPW,
+    uint32_t nb, uint32_t nbs, int copies_mask, int merge_to)
 {
-    extern __shared__ double smem_d[];
-    const uint32_t R = 256u / G;
-    // doubles first (alignment): per-row headers, per-batch headers; then per
-    // local row hist[MAX_BUCKETS + 1], cursor[MAX_BUCKETS + 1], staging[Kp]
-    constexpr uint32_t HB = MAX_BUCKETS + 1;
-    RowHdr* const hdr_all = reinterpret_cast<RowHdr*>(smem_d);
-    BatchHdr* const bhdr = reinterpret_cast<BatchHdr*>(hdr_all + R);
-    uint32_t* const smem = reinterpret_cast<uint32_t*>(bhdr + THEMIS_MAX_BATCH);
-    uint32_t* const hist_all = smem;
-    uint32_t* const cur_all = smem + R * HB;
-    uint32_t* const stage_all = smem + 2 * R * HB;
+    extern __shared__ uint32_t smem[];
+    // per local row: hist[nb + 1], cursor[nb + 1], staging[Kp]
+    const uint32_t HB = nb + 1;
+    const uint32_t row_words = 2 * HB + Kp;
+    const uint32_t nbat = (uint32_t)bl.n;
 
-    const uint32_t rl = threadIdx.x / G, g = threadIdx.x - rl * G;
-    const uint32_t row = blockIdx.x * R + rl;
-    const bool live = row < rows;
-    uint32_t* const hist = hist_all + rl * HB;
-    uint32_t* const cur = cur_all + rl * HB;
-    uint32_t* const stage = stage_all + rl * Kp;
+    const uint32_t rl = threadIdx.x / nbat, j = threadIdx.x - rl * nbat;
+    const uint32_t row = blockIdx.x * RPW + rl;
+    const bool live = rl < RPW && row < rows;
+    uint32_t* const hist = smem + rl * row_words;
+    uint32_t* const cur = hist + HB;
+    uint32_t* const stage = cur + HB;
 
-    for (uint32_t x = threadIdx.x; x < 2 * R * HB; x += 256u) smem[x] = 0u;
-    if (threadIdx.x < (uint32_t)bl.n) {
-        const double b = (double)bl.b[threadIdx.x];
-        BatchHdr bh;
-        bh.b = b;
-        bh.b2 = b * b;
-        bh.M = b * 1.0e6;
-        bh.rM = recip_below(bh.M);
-        bh.w = (b - 1.0) * 1.0e6;
-        bhdr[threadIdx.x] = bh;
-    }
-    if (live && g == 0) {
-        const uint32_t i = row / S, s = row - i * S;
-        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
-        RowHdr h;
-        h.a = (double)cf[0];
-        h.k = (double)cf[1];
-        h.q = (double)cf[2];
-        h.p = (double)cf[3];
-        h.o = (double)cf[4];
-        h.lam = (double)lambda[i];
-        h.T = (double)tmeta[i];
-        h.rlam = h.T >= 0.0 ? recip_below(h.lam) : 0.0;
-        h.slo = (double)slo_us[i];
-        h.n_given = r_fixed ? (double)r_fixed[(size_t)i * S + s] : 0.0;
-        hdr_all[rl] = h;
-    }
+    for (uint32_t x = threadIdx.x; x < RPW * row_words; x += 256u)
+        if (x % row_words < 2 * HB) smem[x] = 0u;
     __syncthreads();
 
     int32_t T = -1;
     if (live) {
-        const RowHdr h = hdr_all[rl];
-        T = (int32_t)h.T;
-        for (uint32_t kk = g; kk < Kp; kk += G) {
-            uint32_t w0 = TAG_NONE;  // lt | cost << 16
-            if (T >= 0 && kk < K) {
-                // kk / n_batch by a 2^32-scaled reciprocal (exact for kk < 2^13)
-                const uint32_t ci = bl.n == 1 ? kk : __umulhi(kk, inv_nbatch);
-                const uint32_t j = kk - ci * (uint32_t)bl.n;
-                const Cand cd = eval_candidate(h, bhdr[j], (double)(ci + 1), (double)r_max,
-                                               (double)tick, rtick);
-                if (cd.lt >= 0) w0 = (uint32_t)cd.lt | ((uint32_t)cd.cost << 16);
+        const uint32_t i = row / S, s = row - i * S;
+        T = tmeta[i];
+        if (T >= 0) {
+            const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
+            RowHdr h;
+            h.a = (double)cf[0];
+            h.k = (double)cf[1];
+            h.q = (double)cf[2];
+            h.p = (double)cf[3];
+            h.o = (double)cf[4];
+            h.lam = (double)lambda[i];
+            h.rlam = recip_below(h.lam);
+            h.slo = (double)slo_us[i];
+            h.T = (double)T;
+            h.n_given = r_fixed ? (double)r_fixed[(size_t)i * S + s] : 0.0;
+            BatchHdr bh;
+            bh.b = (double)bl.b[j];
+            bh.b2 = bh.b * bh.b;
+            bh.M = bh.b * 1.0e6;
+            bh.rM = recip_below(bh.M);
+            bh.w = (bh.b - 1.0) * 1.0e6;
+            const uint32_t pcap = (uint32_t)cf[3];
+            Eval ev{-1, 0};
+            for (uint32_t c = 1; c <= c_max; ++c) {
+                if (c <= pcap)
+                    ev = eval_candidate(h, bh, (double)c, (double)r_max, (double)tick, rtick);
+                const uint32_t w0 = ev.lt < 0 ? STAGE_NONE
+                                              : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
+                stage[(c - 1) * nbat + j] = w0;
+                atomicAdd(&hist[ev.lt < 0 ? nb : (uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
             }
-            stage[kk] = w0;
-            const uint32_t b = w0 == TAG_NONE ? nb : (w0 & 0xFFFFu) >> BUCKET_SHIFT;
-            atomicAdd(&hist[b], 1u);
+        } else {
+            for (uint32_t c = 1; c <= c_max; ++c) stage[(c - 1) * nbat + j] = STAGE_NONE;
+            if (j == 0) hist[nb] = K;
+        }
+        // entries that pad the row to a multiple of eight
+        if (j == 0) {
+            for (uint32_t kk = K; kk < Kp; ++kk) stage[kk] = STAGE_NONE;
+            atomicAdd(&hist[nb], Kp - K);
         }
     }
     __syncthreads();
-    if (live && g < 64) {
-        // exclusive prefix over the buckets by the row's first wavefront (G is a
-        // multiple of 64, so these 64 threads are one wavefront); bucket nb
-        // (infeasible) comes last and starts where the feasible ones end
-        const uint32_t v = g < nb ? hist[g] : 0u;
-        uint32_t incl = v;
+    {
+        // exclusive prefix over the buckets, one row at a time per wavefront;
+        // bucket nb (infeasible) comes last and starts where the feasible ones end
+        const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+        for (uint32_t r = wv; r < RPW; r += 4) {
+            const uint32_t grow = blockIdx.x * RPW + r;
+            if (grow >= rows) break;
+            uint32_t* const hh = smem + r * row_words;
+            const uint32_t v = lane < nb ? hh[lane] : 0u;
+            uint32_t incl = v;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t t = __shfl_up(incl, d, 64);
-            if ((int)g >= d) incl += t;
-        }
-        const uint32_t excl = incl - v;
-        if (g <= nb) {
-            cur[g] = excl;
-            bcum[(size_t)row * nbs + g] = (uint16_t)excl;
-        }
-        if (g == 63 && nb == 64) {
-            cur[64] = incl;
-            bcum[(size_t)row * nbs + 64] = (uint16_t)incl;
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t t = __shfl_up(incl, d, 64);
+                if ((int)lane >= d) incl += t;
+            }
+            const uint32_t excl = incl - v;
+            if (lane <= nb) {
+                hh[HB + lane] = excl;
+                bcum[(size_t)grow * nbs + lane] = (uint16_t)excl;
+            }
+            if (lane == 63 && nb == 64) {
+                hh[HB + 64] = incl;
+                bcum[(size_t)grow * nbs + 64] = (uint16_t)incl;
+            }
         }
     }
     __syncthreads();
@@ -264,18 +264,21 @@ __global__ __launch_bounds__(256) void k1_candidates(
         const int cls = T >= 0 ? effective_class(T, merge_to) : 0;
         const int copy_bytes = wide_copy_bytes(CLS_WAVES[cls == NARROW_CLS ? 0 : cls]);
         const int copies = class_copies(cls, copies_mask);
-        for (uint32_t kk = g; kk < Kp; kk += G) {
+        StepEntry* const out = step_tab + (size_t)row * Kp;
+        auto place = [&](uint32_t kk) {
             const uint32_t w0 = stage[kk];
-            const bool none = w0 == TAG_NONE;
             const uint32_t lt = w0 & 0xFFFFu;
-            const uint32_t b = none ? nb : lt >> BUCKET_SHIFT;
-            const uint32_t slot = atomicAdd(&cur[b], 1u);
+            const bool none = lt == STAGE_NONE;
+            const uint32_t slot = atomicAdd(&cur[none ? nb : lt >> BUCKET_SHIFT], 1u);
             StepEntry se;
-            se.shift = none ? 0u : (cls == NARROW_CLS ? narrow_shift(lt) : wide_shift(lt, copies, copy_bytes));
-            se.cost2 = none ? 0u : (w0 >> 16) * 0x10001u;
-            step_tab[(size_t)row * Kp + slot] = se;
-            tag_tab[(size_t)row * Kp + slot] = lt | (kk << 16);
-        }
+            se.shift = none ? 0u
+                            : (cls == NARROW_CLS ? narrow_shift(lt) : wide_shift(lt, copies, copy_bytes));
+            se.ck = (none ? 0u : w0 >> 16) | (kk << 16);
+            out[slot] = se;
+        };
+        for (uint32_t c = 1; c <= c_max; ++c) place((c - 1) * nbat + j);
+        if (j == 0)
+            for (uint32_t kk = K; kk < Kp; ++kk) place(kk);  // the padding entries
     }
 }
 
@@ -283,35 +286,45 @@ __global__ void k_zero64(unsigned long long* p) { *p = 0ull; }
 
 // Undo the bucket order: separate lt / cost arrays [N][S][K], index k.
 __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ step_tab,
-                                                const uint32_t* __restrict__ tag_tab,
+                                                const uint16_t* __restrict__ bcum,
+                                                const int32_t* __restrict__ tmeta,
                                                 int32_t* __restrict__ lt,
                                                 int32_t* __restrict__ cost, uint32_t rows,
-                                                uint32_t K, uint32_t Kp)
+                                                uint32_t S, uint32_t K, uint32_t Kp, uint32_t nb,
+                                                uint32_t nbs, int copies_mask, int merge_to)
 {
     uint32_t g = blockIdx.x * 256u + threadIdx.x;
     if (g >= rows * Kp) return;
-    uint32_t row = g / Kp;
-    uint32_t tag = tag_tab[g], k = tag >> 16;
+    const uint32_t row = g / Kp, e = g - row * Kp;
+    const StepEntry se = step_tab[g];
+    const uint32_t k = se.ck >> 16;
     if (k >= K) return;  // padding entry
-    const bool none = (tag & 0xFFFFu) == TAG_NONE;
-    lt[(size_t)row * K + k] = none ? -1 : (int32_t)(tag & 0xFFFFu);
-    cost[(size_t)row * K + k] = none ? -1 : (int32_t)(step_tab[g].cost2 & 0xFFFFu);
+    const int32_t T = tmeta[row / S];
+    const bool none = T < 0 || e >= bcum[(size_t)row * nbs + nb];
+    lt[(size_t)row * K + k] = none ? -1 : (int32_t)lt_of_entry(se.shift, T, merge_to, copies_mask);
+    cost[(size_t)row * K + k] = none ? -1 : (int32_t)(se.ck & 0xFFFFu);
 }
 
 // Sum over valid instances, models and feasible candidates of (T + 1 - lt).
-__global__ __launch_bounds__(256) void k_count_relax(const uint32_t* __restrict__ tag_tab,
+__global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict__ step_tab,
+                                                     const uint16_t* __restrict__ bcum,
                                                      const int32_t* __restrict__ tmeta,
                                                      unsigned long long* __restrict__ out,
-                                                     uint32_t N, uint32_t SK)
+                                                     uint32_t N, uint32_t S, uint32_t Kp,
+                                                     uint32_t nb, uint32_t nbs, int copies_mask,
+                                                     int merge_to)
 {
     __shared__ unsigned long long part[256];
     unsigned long long acc = 0;
     for (uint32_t i = blockIdx.x; i < N; i += gridDim.x) {
-        int32_t T = tmeta[i];
+        const int32_t T = tmeta[i];
         if (T < 0) continue;
-        for (uint32_t e = threadIdx.x; e < SK; e += 256) {
-            uint32_t lt = tag_tab[(size_t)i * SK + e] & 0xFFFFu;
-            if (lt != TAG_NONE) acc += (unsigned long long)(T + 1 - (int32_t)lt);
+        for (uint32_t s = 0; s < S; ++s) {
+            const size_t row = (size_t)i * S + s;
+            const uint32_t n = bcum[row * nbs + nb];
+            for (uint32_t e = threadIdx.x; e < n; e += 256)
+                acc += (unsigned long long)(T + 1) -
+                       lt_of_entry(step_tab[row * Kp + e].shift, T, merge_to, copies_mask);
         }
     }
     part[threadIdx.x] = acc;
@@ -344,47 +357,52 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    // threads per row; THEMIS_K1_G overrides for tuning runs
-    uint32_t G = 64;
-    if (const char* e = std::getenv("THEMIS_K1_G")) {
-        G = (uint32_t)std::atoi(e);
-    }
-    const uint32_t R = 256u / G;
+    // rows per workgroup: as many as 256 threads cover, within 52 KB of LDS
+    const uint32_t row_bytes = (uint32_t)(2 * (L.nb + 1) + L.Kp) * sizeof(uint32_t);
+    uint32_t RPW = 256u / (uint32_t)p.n_batch;
+    while (RPW > 1 && RPW * row_bytes > 52u * 1024u) --RPW;
     const uint32_t rows = (uint32_t)L.N * L.S;
-    const size_t lds = R * sizeof(RowHdr) + THEMIS_MAX_BATCH * sizeof(BatchHdr) +
-                       (size_t)(2 * R * (MAX_BUCKETS + 1) + R * L.Kp) * sizeof(uint32_t);
-    hipLaunchKernelGGL(k1_candidates, dim3((rows + R - 1) / R), dim3(256), lds, st, d_coef,
+    const size_t lds = (size_t)RPW * row_bytes;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k1_candidates),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k1_candidates, dim3((rows + RPW - 1) / RPW), dim3(256), lds, st, d_coef,
                        d_lambda, d_slo_us, d_r_fixed, (const int32_t*)tmeta,
-                       (StepEntry*)(ws + L.step_off), (uint32_t*)(ws + L.tag_off),
-                       (uint16_t*)(ws + L.bcum_off), bl, rows, (uint32_t)L.S, (uint32_t)L.K,
-                       (uint32_t)L.Kp, (uint32_t)p.r_max, (uint32_t)p.tick_us,
-                       (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, G,
-                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
-                       (uint32_t)((0x100000000ull + p.n_batch - 1) / p.n_batch));
+                       (StepEntry*)(ws + L.step_off), (uint16_t*)(ws + L.bcum_off), bl, rows,
+                       (uint32_t)L.S, (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.c_max,
+                       (uint32_t)p.r_max, (uint32_t)p.tick_us,
+                       (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
+                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to);
     return hipGetLastError();
 }
 
 hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_lt,
                                     int32_t* d_cost, hipStream_t st)
 {
+    const MinplusPlan plan = make_plan(L);
     uint32_t rows = (uint32_t)L.N * L.S;
     uint32_t blocks = (rows * (uint32_t)L.Kp + 255u) / 256u;
     hipLaunchKernelGGL(k_export, dim3(blocks), dim3(256), 0, st,
-                       (const StepEntry*)(ws + L.step_off), (const uint32_t*)(ws + L.tag_off), d_lt,
-                       d_cost, rows, (uint32_t)L.K, (uint32_t)L.Kp);
+                       (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
+                       (const int32_t*)(ws + L.tmeta_off), d_lt, d_cost, rows, (uint32_t)L.S,
+                       (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs,
+                       plan.copies_mask, plan.merge_to);
     return hipGetLastError();
 }
 
 hipError_t launch_count_relaxations(const Layout& L, const char* ws,
                                     unsigned long long* d_count, hipStream_t st)
 {
+    const MinplusPlan plan = make_plan(L);
     hipLaunchKernelGGL(k_zero64, dim3(1), dim3(1), 0, st, d_count);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     uint32_t blocks = (uint32_t)(L.N < 4096 ? L.N : 4096);
     hipLaunchKernelGGL(k_count_relax, dim3(blocks), dim3(256), 0, st,
-                       (const uint32_t*)(ws + L.tag_off), (const int32_t*)(ws + L.tmeta_off),
-                       d_count, (uint32_t)L.N, (uint32_t)(L.S * L.Kp));
+                       (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
+                       (const int32_t*)(ws + L.tmeta_off), d_count, (uint32_t)L.N, (uint32_t)L.S,
+                       (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask,
+                       plan.merge_to);
     return hipGetLastError();
 }
 

@@ -263,6 +263,14 @@ __device__ __forceinline__ void publish_pair(char* p, int CSB, uint32_t v)
 // staging buffer (loaded before a model's sweeps, stored after them).
 constexpr int PREFETCH = 4;  // entries per thread
 
+// An entry as the sweep wants it in LDS: the cost replicated into both halves
+// of the second word (the operand of the packed add), the index dropped.
+__device__ __forceinline__ StepEntry staged(StepEntry se)
+{
+    se.ck = (se.ck & 0xFFFFu) * 0x10001u;
+    return se;
+}
+
 struct RowPrefetch {
     StepEntry e[PREFETCH];
     int cnt;  // entries of the row to stage (at most CAND_BUF); 16 zero entries follow
@@ -275,7 +283,7 @@ __device__ __forceinline__ void prefetch_row(RowPrefetch& pf, const StepEntry* g
     for (int j = 0; j < PREFETCH; ++j) {
         const int x = (int)threadIdx.x + j * (int)blockDim.x;
         pf.e[j].shift = 0u;
-        pf.e[j].cost2 = 0u;
+        pf.e[j].ck = 0u;
         if (x < cnt) pf.e[j] = grow[x];
     }
 }
@@ -286,16 +294,16 @@ __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntr
 #pragma unroll
     for (int j = 0; j < PREFETCH; ++j) {
         const int x = (int)threadIdx.x + j * (int)blockDim.x;
-        if (x < pf.cnt + 16) cbuf[x] = pf.e[j];
+        if (x < pf.cnt + 16) cbuf[x] = staged(pf.e[j]);
     }
     // whatever the registers did not cover
     for (int x = (int)threadIdx.x + PREFETCH * (int)blockDim.x; x < pf.cnt + 16;
          x += (int)blockDim.x) {
         StepEntry se;
         se.shift = 0u;
-        se.cost2 = 0u;
+        se.ck = 0u;
         if (x < pf.cnt) se = grow[x];
-        cbuf[x] = se;
+        cbuf[x] = staged(se);
     }
 }
 
@@ -405,9 +413,9 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                         for (int x = tid; x < cnt + 16; x += (int)blockDim.x) {
                             StepEntry se;
                             se.shift = 0u;
-                            se.cost2 = 0u;
+                            se.ck = 0u;
                             if (x < cnt) se = grow[seg + x];
-                            cbuf[x] = se;
+                            cbuf[x] = staged(se);
                         }
                         __syncthreads();
                     }
@@ -506,7 +514,7 @@ __global__ __launch_bounds__(NAR_NW * 64) void k2_minplus_narrow(
                 const AS_CONST StepEntry* ep = as_constant(step_tab + row * Kp);
                 const int n = prefix_count(as_constant(bcum + row * nbs), last_cell > T ? T : last_cell);
                 for (int k = 0; k < n; ++k) {
-                    const uint32_t cost2 = ep[k].cost2;
+                    const uint32_t cost2 = (ep[k].ck & 0xFFFFu) * 0x10001u;
                     // shift = byte offset of the aligned source of dword 0 (copy A or B)
                     const uint32_t* src = lds + ((ep[k].shift >> 2) + j0 + lane);
 #pragma unroll

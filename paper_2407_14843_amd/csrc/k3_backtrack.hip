@@ -19,11 +19,10 @@ namespace themis {
 namespace {
 
 __global__ __launch_bounds__(256) void k3_backtrack(
-    const StepEntry* __restrict__ step_tab, const uint32_t* __restrict__ tag_tab,
-    const uint16_t* __restrict__ bcum, const int32_t* __restrict__ tmeta,
+    const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum, const int32_t* __restrict__ tmeta,
     const uint16_t* __restrict__ frow, int32_t* __restrict__ status,
     int32_t* __restrict__ cost_out, int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg,
-    BatchList bl, int N, int S, int Kp, int nbs, int row_stride)
+    BatchList bl, int N, int S, int Kp, int nbs, int row_stride, int copies_mask, int merge_to)
 {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -73,7 +72,6 @@ __global__ __launch_bounds__(256) void k3_backtrack(
         const uint16_t* next = row0 + (size_t)(s + 1) * row_stride;  // only read if s+1 < S
         const size_t row = (size_t)i * S + s;
         const StepEntry* sp = step_tab + row * Kp;
-        const uint32_t* tp = tag_tab + row * Kp;
         // only entries whose bucket does not exceed t's can fit
         const int n = bcum[row * nbs + (t >> BUCKET_SHIFT) + 1];
         // smallest index k among the entries that attain the target; lt and cost
@@ -82,14 +80,14 @@ __global__ __launch_bounds__(256) void k3_backtrack(
         for (int e0 = 0; e0 < n; e0 += 64) {
             const int e = e0 + lane;
             if (e < n) {
-                const uint32_t tag = tp[e];
-                const int lt = (int)(tag & 0xFFFFu);  // every entry below n is feasible
+                const StepEntry se = sp[e];  // every entry below n is feasible
+                const int lt = (int)lt_of_entry(se.shift, T, merge_to, copies_mask);
                 if (lt <= t) {
-                    const uint32_t co = sp[e].cost2 & 0xFFFFu;
+                    const uint32_t co = se.ck & 0xFFFFu;
                     const uint32_t rest = (s + 1 < S) ? (uint32_t)next[t - lt] : 0u;
                     if (rest < F_INF && co + rest == target) {
                         const unsigned long long cand =
-                            ((unsigned long long)(tag >> 16) << 32) | (co << 16) | (uint32_t)lt;
+                            ((unsigned long long)(se.ck >> 16) << 32) | (co << 16) | (uint32_t)lt;
                         key = cand < key ? cand : key;
                     }
                 }
@@ -136,11 +134,12 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
     BatchList bl{};
     bl.n = p.n_batch;
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
+    const MinplusPlan plan = make_plan(L);
     hipLaunchKernelGGL(k3_backtrack, dim3((L.N + 3) / 4), dim3(256), 0, st,
-                       (const StepEntry*)(ws + L.step_off), (const uint32_t*)(ws + L.tag_off),
-                       (const uint16_t*)(ws + L.bcum_off), (const int32_t*)(ws + L.tmeta_off),
-                       (const uint16_t*)(ws + L.frow_off), d_status, d_cost, d_ticks, d_cfg, bl,
-                       L.N, L.S, L.Kp, L.nbs, L.row_stride);
+                       (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
+                       (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
+                       d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.Kp, L.nbs, L.row_stride,
+                       plan.copies_mask, plan.merge_to);
     return hipGetLastError();
 }
 

@@ -16,20 +16,20 @@ namespace themis {
 constexpr uint32_t F_INF = 0x8000u;
 constexpr uint32_t F_INF2 = 0x80008000u;
 
-// Stage 1 leaves two tables, both ordered within a row by latency bucket
-// lt >> BUCKET_SHIFT (infeasible candidates last), so that the candidates that
-// can reach a given stretch of the budget grid form a prefix of the row:
-//   StepEntry  what the min-plus loop needs with no further scalar arithmetic:
-//              the byte offset that turns "my place in row copy 0" into "the
-//              aligned place lt cells below, in the copy whose shift fits"
-//              (it depends on the LDS layout of the instance's work class),
-//              and the cost replicated into both halves of a dword;
-//   tag        lt | k << 16 for reconstruction (lt = TAG_NONE if infeasible).
+// Stage 1 leaves one table of 8-byte entries, ordered within a row by latency
+// bucket lt >> BUCKET_SHIFT (infeasible candidates last), so that the
+// candidates that can reach a given stretch of the budget grid form a prefix
+// of the row.  An entry holds
+//   shift  the byte offset that turns "my place in row copy 0" into "the
+//          aligned place lt cells below, in the copy whose shift fits"; it
+//          depends on the LDS layout of the instance's work class and is
+//          invertible (lt_of_shift), so lt itself is not stored;
+//   ck     cost | k << 16: replicas * cores (<= 32767) and the candidate index.
+// Entries at or beyond bcum[nb] are infeasible candidates (shift 0, cost 0).
 struct __attribute__((aligned(8))) StepEntry {
-    uint32_t shift;  // see wide_shift() / narrow_shift()
-    uint32_t cost2;  // cost * 0x10001; 0 for an infeasible candidate
+    uint32_t shift;
+    uint32_t ck;
 };
-constexpr uint32_t TAG_NONE = 0xFFFFu;
 constexpr int BUCKET_SHIFT = 9;                 // 512 cells per bucket
 constexpr int BUCKET_CELLS = 1 << BUCKET_SHIFT;
 constexpr int MAX_BUCKETS = (THEMIS_MAX_TICKS >> BUCKET_SHIFT) + 1;   // 64
@@ -101,6 +101,25 @@ __host__ __device__ inline uint32_t narrow_shift(uint32_t lt)
                            : (uint32_t)NAR_CHUNK_DW - h);
 }
 
+// Inverses.  Wide: the term 8h (4h) is less than one copy, so the sign of the
+// offset taken modulo the copy size tells the copy.  Narrow: even shifts lie at
+// or below the pad, odd ones above it.
+__host__ __device__ inline uint32_t wide_lt_of_shift(uint32_t shift, int copies, int copy_bytes)
+{
+    const int32_t sh = (int32_t)shift;
+    // sh = m * copy_bytes - e * h with 0 <= e * h < copy_bytes
+    const int32_t m = sh <= 0 ? 0 : (sh + copy_bytes - 1) / copy_bytes;
+    const uint32_t back = (uint32_t)(m * copy_bytes - sh);
+    return copies == 4 ? 4u * (back >> 3) - (uint32_t)m : 2u * (back >> 2) - (uint32_t)m;
+}
+
+__host__ __device__ inline uint32_t narrow_lt_of_shift(uint32_t shift)
+{
+    const int32_t x = (int32_t)shift / 4;
+    return x <= NAR_CHUNK_DW ? 2u * (uint32_t)(NAR_CHUNK_DW - x)
+                             : 2u * (uint32_t)(NAR_COPY_DW + NAR_CHUNK_DW - 1 - x) + 1u;
+}
+
 // With few instances, one launch per class leaves the chip mostly idle and
 // pays a launch and a tail per class; then every wide class up to merge_to is
 // served by class merge_to's launch (its geometry fits all shorter rows).
@@ -122,14 +141,13 @@ MinplusPlan make_plan(const Layout& L);
 
 // Workspace carve-up.  Every region starts on a 256-byte boundary.
 //   step   StepEntry [N*S][Kp] bucket-ordered; Kp = K rounded up to 8
-//   tag    u32 [N*S][Kp]       lt | k << 16 of the entry in the same slot
 //   bcum   u16 [N*S][nbs]      bcum[j] = entries of the row with bucket < j, j = 0..nb
 //   frow   u16 [N][S][row_stride] f[s][t] of the min-plus recurrence
 //   tmeta  int32 [N]           budget T of the instance, -1 = invalid instance
 //   order  int32 [N_CLS][N]    instance ids grouped by work class
 //   ctrl   int32 [2][N_CLS]    per class: number of instances, queue cursor
 struct Layout {
-    size_t step_off, tag_off, bcum_off, frow_off, tmeta_off, order_off, ctrl_off, total;
+    size_t step_off, bcum_off, frow_off, tmeta_off, order_off, ctrl_off, total;
     int32_t N, S, K, Kp, t_max, row_stride, nb, nbs;
 };
 
@@ -150,9 +168,7 @@ inline Layout make_layout(const themis_problem_t& p)
     L.row_stride = (int32_t)((L.t_max + 4 + 127) / 128 * 128);
     size_t rows = (size_t)L.N * L.S;
     size_t at = 0;
-    // one spare batch after the last row: the min-plus loop fetches one batch ahead
-    L.step_off = at;  at = align256(at + (rows * L.Kp + 8) * sizeof(StepEntry));
-    L.tag_off = at;   at = align256(at + rows * L.Kp * sizeof(uint32_t));
+    L.step_off = at;  at = align256(at + rows * L.Kp * sizeof(StepEntry));
     L.bcum_off = at;  at = align256(at + rows * L.nbs * sizeof(uint16_t));
     L.frow_off = at;  at = align256(at + rows * L.row_stride * sizeof(uint16_t));
     L.tmeta_off = at; at = align256(at + (size_t)L.N * sizeof(int32_t));
@@ -174,6 +190,16 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                              char* ws, hipStream_t st);
 hipError_t launch_minplus(const themis_problem_t& p, const Layout& L, char* ws,
                           hipStream_t st);
+// lt of an entry of an instance with budget T (see StepEntry)
+__host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, int merge_to,
+                                                int copies_mask)
+{
+    const int cls = effective_class(T, merge_to);
+    if (cls == NARROW_CLS) return narrow_lt_of_shift(shift);
+    return wide_lt_of_shift(shift, class_copies(cls, copies_mask),
+                            wide_copy_bytes(CLS_WAVES[cls]));
+}
+
 hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L,
                             int32_t* d_status, int32_t* d_cost, int32_t* d_ticks,
                             int32_t* d_cfg, char* ws, hipStream_t st);
