@@ -74,33 +74,32 @@ struct Eval {
 __device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& bh, double d,
                                                double r_max, double tick, double rtick)
 {
-    const Eval none{-1, 0};
+    // Straight-line: every test only clears `ok`, so the lanes of a wavefront
+    // stay together.  A candidate that fails an early test may push later
+    // intermediates past 2^53; they are then inexact but never used.
     const double num = __builtin_fma(h.q, bh.b2, __builtin_fma(h.k, bh.b, h.a));  // < 2^41
     const double proc = ceil_div_d(num, d, recip_below(d)) + h.o;
     // anything slower than the SLO also exceeds T ticks; cutting it here keeps
-    // every later product below 2^53
-    if (proc > h.slo) return none;
+    // every later product of a surviving candidate below 2^53
+    bool ok = proc <= h.slo;
     const double lp = h.lam * proc;  // < 2^51
-    double n;
-    if (h.n_given <= 0.0) {
-        if (lp > r_max * bh.M) return none;  // needs more than r_max replicas
-        n = ceil_div_d(lp, bh.M, bh.rM);
-        n = n < 1.0 ? 1.0 : n;
-    } else {
-        n = h.n_given;
-        if (lp > n * bh.M) return none;      // the given replicas cannot carry lambda
-    }
-    const double qn = bh.w * n;              // < 2^45
-    if (qn > (h.slo - proc) * h.lam) return none;  // proc + queue > SLO
+    const bool derive = h.n_given <= 0.0;
+    double n = ceil_div_d(lp, bh.M, bh.rM);  // least n with lambda <= n * b / proc
+    n = n < 1.0 ? 1.0 : n;
+    n = derive ? n : h.n_given;
+    // joint: no more than r_max replicas; vertical: the given ones must carry lambda
+    ok = ok && (derive ? lp <= r_max * bh.M : lp <= n * bh.M);
+    const double qn = bh.w * n;  // < 2^45
+    ok = ok && qn <= (h.slo - proc) * h.lam;  // proc + queue <= SLO
     const double lat = proc + ceil_div_d(qn, h.lam, h.rlam);
     const double lt = ceil_div_d(lat, tick, rtick);
-    if (lt > h.T) return none;
-    return Eval{(int32_t)lt, (int32_t)n};
+    ok = ok && lt <= h.T;
+    return Eval{ok ? (int32_t)lt : -1, ok ? (int32_t)n : 0};
 }
 
-__device__ __forceinline__ bool in_range(int32_t v, int32_t lo, int32_t hi)
+__device__ __forceinline__ int in_range(int32_t v, int32_t lo, int32_t hi)
 {
-    return v >= lo && v <= hi;
+    return (int)(v >= lo) & (int)(v <= hi);
 }
 
 // Input check and work classification, one thread per instance:
@@ -119,13 +118,14 @@ __global__ __launch_bounds__(256) void k1_validate(
     if (i < N) {
         int32_t lam = lambda[i], slo = slo_us[i];
         const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5);
-        bool ok = in_range(lam, 1, THEMIS_VALUE_MAX) && in_range(slo, 0, slo_max);
+        // no short-circuiting: the loads of all models are independent
+        int ok = in_range(lam, 1, THEMIS_VALUE_MAX) & in_range(slo, 0, slo_max);
         for (uint32_t z = 0; z < S; ++z) {
             const int32_t* cz = cf + z * 5;
-            ok = ok && in_range(cz[0], 0, THEMIS_VALUE_MAX) &&
-                 in_range(cz[1], 0, THEMIS_VALUE_MAX) && in_range(cz[2], 0, THEMIS_VALUE_MAX) &&
-                 cz[3] >= 1 && in_range(cz[4], 1, THEMIS_VALUE_MAX);
-            if (r_fixed) ok = ok && in_range(r_fixed[(size_t)i * S + z], 1, r_max);
+            const int32_t a = cz[0], k = cz[1], q = cz[2], pc = cz[3], o = cz[4];
+            ok &= in_range(a, 0, THEMIS_VALUE_MAX) & in_range(k, 0, THEMIS_VALUE_MAX) &
+                  in_range(q, 0, THEMIS_VALUE_MAX) & (int)(pc >= 1) & in_range(o, 1, THEMIS_VALUE_MAX);
+            if (r_fixed) ok &= in_range(r_fixed[(size_t)i * S + z], 1, r_max);
         }
         int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
         tmeta[i] = T;
@@ -262,17 +262,26 @@ __global__ __launch_bounds__(256) void k1_candidates(
     if (live) {
         // the LDS geometry the min-plus stage will use for this instance
         const int cls = T >= 0 ? effective_class(T, merge_to) : 0;
-        const int copy_bytes = wide_copy_bytes(CLS_WAVES[cls == NARROW_CLS ? 0 : cls]);
-        const int copies = class_copies(cls, copies_mask);
+        // wide_shift() / narrow_shift() in one branch-free form:
+        //   shift = base + ((-lt) & cm) * step - (((lt + add) >> sh) << (sh + 1))
+        uint32_t cm, sh, add, step, base;
+        if (cls == NARROW_CLS) {
+            cm = 1, sh = 1, add = 0, step = 4u * (NAR_COPY_DW - 1), base = 4u * NAR_CHUNK_DW;
+        } else if (class_copies(cls, copies_mask) == 4) {
+            cm = 3, sh = 2, add = 3, step = (uint32_t)wide_copy_bytes(CLS_WAVES[cls]), base = 0;
+        } else {
+            cm = 1, sh = 1, add = 1, step = (uint32_t)wide_copy_bytes(CLS_WAVES[cls]), base = 0;
+        }
         StepEntry* const out = step_tab + (size_t)row * Kp;
         auto place = [&](uint32_t kk) {
             const uint32_t w0 = stage[kk];
             const uint32_t lt = w0 & 0xFFFFu;
             const bool none = lt == STAGE_NONE;
             const uint32_t slot = atomicAdd(&cur[none ? nb : lt >> BUCKET_SHIFT], 1u);
+            const uint32_t shift =
+                base + __umul24((0u - lt) & cm, step) - (((lt + add) >> sh) << (sh + 1));
             StepEntry se;
-            se.shift = none ? 0u
-                            : (cls == NARROW_CLS ? narrow_shift(lt) : wide_shift(lt, copies, copy_bytes));
+            se.shift = none ? 0u : shift;
             se.ck = (none ? 0u : w0 >> 16) | (kk << 16);
             out[slot] = se;
         };

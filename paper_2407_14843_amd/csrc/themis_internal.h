@@ -108,7 +108,7 @@ __host__ __device__ inline uint32_t wide_lt_of_shift(uint32_t shift, int copies,
 {
     const int32_t sh = (int32_t)shift;
     // sh = m * copy_bytes - e * h with 0 <= e * h < copy_bytes
-    const int32_t m = sh <= 0 ? 0 : (sh + copy_bytes - 1) / copy_bytes;
+    const int32_t m = (sh > 0) + (sh > copy_bytes) + (sh > 2 * copy_bytes);  // ceil(sh / copy_bytes)
     const uint32_t back = (uint32_t)(m * copy_bytes - sh);
     return copies == 4 ? 4u * (back >> 3) - (uint32_t)m : 2u * (back >> 2) - (uint32_t)m;
 }
