@@ -149,7 +149,7 @@ struct Geo {
 //
 // The loop is software-pipelined by hand: the row reads of entry k+1 are issued
 // before the arithmetic of entry k, into the other half of a double buffer, and
-// the entries themselves are fetched two ahead, so a wavefront always has reads
+// the entries themselves are fetched three ahead, so a wavefront always has reads
 // in flight while it works.  The scheduling barriers keep the compiler from
 // undoing that order.  In the last steps the entries at or beyond ke are
 // parked on the F_INF pad, where they change nothing.
@@ -176,17 +176,19 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
     };
 
     // ring of four entries: while entry k is being relaxed, the row reads of k+1
-    // are in flight and entry k+2 is being fetched
+    // are in flight and entry k+3 is being fetched (the slot of entry k-1, whose
+    // cost was copied out when its reads were issued)
     u32x2 e[4];
     e[0] = ent[kb];
     e[1] = ent[kb + 1];
+    e[2] = ent[kb + 2];
     issue(e[0], true, 0);
     int k0 = kb;
-    // groups of four whose entries and the two after them all lie inside [kb, ke)
-    for (; k0 + 6 <= ke; k0 += 4) {
+    // groups of four whose entries and the one after them all lie inside [kb, ke)
+    for (; k0 + 5 <= ke; k0 += 4) {
 #pragma unroll
         for (int z = 0; z < 4; ++z) {
-            e[(z + 2) & 3] = ent[k0 + z + 2];
+            e[(z + 3) & 3] = ent[k0 + z + 3];
             issue(e[(z + 1) & 3], true, (z + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
             consume(z & 1);
@@ -198,7 +200,7 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
     for (; k0 < ke; k0 += 4) {
 #pragma unroll
         for (int z = 0; z < 4; ++z) {
-            e[(z + 2) & 3] = ent[k0 + z + 2];
+            e[(z + 3) & 3] = ent[k0 + z + 3];
             issue(e[(z + 1) & 3], k0 + z + 1 < ke, (z + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);
             consume(z & 1);
