@@ -45,6 +45,16 @@ def _load():
         _lib.themis_oracle_solve.restype = ctypes.c_int
         _lib.themis_oracle_solve.argtypes = [i32, i32, i32, p, i32, i32, i32, i32,
                                              p, p, p, p, i32, i32, p, p, p, p]
+        _lib.themis_oracle_solve_ex.restype = ctypes.c_int
+        _lib.themis_oracle_solve_ex.argtypes = [i32, i32, i32, p, i32, i32, i32, i32,
+                                                p, p, p, p, p, i32, i32, p, p, p, p]
+        _lib.themis_oracle_vertical_fallback.restype = ctypes.c_int
+        _lib.themis_oracle_vertical_fallback.argtypes = [i32, i32, i32, p, i32, i32, i32, i32,
+                                                         p, p, p, p, i32, i32,
+                                                         p, p, p, p, p, p, p, p, p]
+        _lib.themis_bruteforce_ex.restype = ctypes.c_int
+        _lib.themis_bruteforce_ex.argtypes = [i32, i32, i32, p, i32, i32, p, i32, i32, p, p,
+                                              p, p, p, p]
         _lib.themis_bruteforce.restype = ctypes.c_int
         _lib.themis_bruteforce.argtypes = [i32, i32, i32, p, i32, i32, p, i32, i32, p,
                                            p, p, p, p]
@@ -81,14 +91,16 @@ def candidates(w):
     return lt, cost, r
 
 
-def solve(w, threads: int = 1):
+def solve(w, threads: int = 1, c_fixed=None):
     """Solve every instance; returns (status[N], cost[N], ticks[N], cfg[N][S][3]).
 
     `threads` > 1 only shards the instance range over a thread pool; each
-    shard runs the same single-threaded C routine.
+    shard runs the same single-threaded C routine.  `c_fixed` (int [N][S])
+    pins each model's cores.
     """
     lib = _load()
     bs, coef, lam, slo, rf = _common(w)
+    cfx = _i32(c_fixed)
     n, s = w.n_inst, w.n_stage
     status = np.empty(n, np.int32)
     cost = np.empty(n, np.int32)
@@ -96,11 +108,11 @@ def solve(w, threads: int = 1):
     cfg = np.empty((n, s, 3), np.int32)
 
     def run(lo, hi):
-        rc = lib.themis_oracle_solve(s, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us,
-                                     w.slo_max_us, int(w.coef_shared), _ptr(coef),
-                                     _ptr(lam), _ptr(slo), _ptr(rf), lo, hi,
-                                     _ptr(status[lo:]), _ptr(cost[lo:]),
-                                     _ptr(ticks[lo:]), _ptr(cfg[lo:]))
+        rc = lib.themis_oracle_solve_ex(s, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us,
+                                        w.slo_max_us, int(w.coef_shared), _ptr(coef),
+                                        _ptr(lam), _ptr(slo), _ptr(rf), _ptr(cfx), lo, hi,
+                                        _ptr(status[lo:]), _ptr(cost[lo:]),
+                                        _ptr(ticks[lo:]), _ptr(cfg[lo:]))
         if rc != 0:
             raise RuntimeError(f"themis_oracle_solve failed: {rc}")
 
@@ -116,8 +128,48 @@ def solve(w, threads: int = 1):
     return status, cost, ticks, cfg
 
 
-def bruteforce(w, i: int = 0):
-    """Exhaustive enumeration for instance i: (status, cost, ticks, cfg[S][3], visited)."""
+def vertical_fallback(w, threads: int = 1):
+    """Algorithm 1 with its fallback for every instance of a vertical workload.
+
+    Returns a dict of int32 arrays: status, cost, ticks, cfg (vertical part at
+    lambda_v), lambda_v, status_h, cost_h, ticks_h, cfg_h (new instances for the
+    remaining lambda - lambda_v, cores pinned to the vertical part's).
+    """
+    lib = _load()
+    bs, coef, lam, slo, rf = _common(w)
+    if rf is None:
+        raise ValueError("vertical_fallback needs r_fixed")
+    n, s = w.n_inst, w.n_stage
+    out = {k: np.empty(n, np.int32) for k in
+           ("status", "cost", "ticks", "lambda_v", "status_h", "cost_h", "ticks_h")}
+    out["cfg"] = np.empty((n, s, 3), np.int32)
+    out["cfg_h"] = np.empty((n, s, 3), np.int32)
+
+    def run(lo, hi):
+        rc = lib.themis_oracle_vertical_fallback(
+            s, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us, w.slo_max_us,
+            int(w.coef_shared), _ptr(coef), _ptr(lam), _ptr(slo), _ptr(rf), lo, hi,
+            _ptr(out["status"][lo:]), _ptr(out["cost"][lo:]), _ptr(out["ticks"][lo:]),
+            _ptr(out["cfg"][lo:]), _ptr(out["lambda_v"][lo:]), _ptr(out["status_h"][lo:]),
+            _ptr(out["cost_h"][lo:]), _ptr(out["ticks_h"][lo:]), _ptr(out["cfg_h"][lo:]))
+        if rc != 0:
+            raise RuntimeError(f"themis_oracle_vertical_fallback failed: {rc}")
+
+    threads = max(1, min(threads, n))
+    if threads == 1:
+        run(0, n)
+    else:
+        step = max(1, n // (threads * 16))
+        spans = [(lo, min(n, lo + step)) for lo in range(0, n, step)]
+        with ThreadPoolExecutor(threads) as pool:
+            list(pool.map(lambda ab: run(*ab), spans))
+    return out
+
+
+def bruteforce(w, i: int = 0, c_fixed=None):
+    """Exhaustive enumeration for instance i: (status, cost, ticks, cfg[S][3], visited).
+
+    `c_fixed` (int [S]) pins the cores of each model."""
     lib = _load()
     bs, coef, lam, slo, rf = _common(w)
     cf = coef if w.coef_shared else coef[i]
@@ -127,8 +179,9 @@ def bruteforce(w, i: int = 0):
     ticks = ctypes.c_int32(0)
     visited = ctypes.c_int64(0)
     cfg = np.zeros((w.n_stage, 3), np.int32)
-    rc = lib.themis_bruteforce(w.n_stage, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us,
-                               _ptr(cf), int(lam[i]), int(slo[i]), _ptr(rfi),
+    cfx = _i32(c_fixed)
+    rc = lib.themis_bruteforce_ex(w.n_stage, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us,
+                               _ptr(cf), int(lam[i]), int(slo[i]), _ptr(rfi), _ptr(cfx),
                                ctypes.byref(cost), ctypes.byref(ticks), _ptr(cfg),
                                ctypes.byref(visited))
     if rc < 0:

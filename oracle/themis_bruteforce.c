@@ -36,6 +36,7 @@ typedef struct {
     const int32_t *batch_sizes;
     const int32_t *coef;    /* [S][5] */
     const int32_t *r_fixed; /* [S] or NULL */
+    const int32_t *c_fixed; /* [S] or NULL */
     long long lambda, tick, T;
     int cur[BF_MAX_STAGE][3];
     int best[BF_MAX_STAGE][3];
@@ -60,7 +61,7 @@ static int key_less(const bf_state *st, long long cost, long long ticks)
 
 static void walk(bf_state *st, int s, long long cost, long long ticks)
 {
-    int c, j, n, n_lo, n_hi;
+    int c, j, n, n_lo, n_hi, c_lo, c_hi;
     if (s == st->S) {
         st->visited++;
         if (ticks <= st->T && key_less(st, cost, ticks)) {
@@ -73,7 +74,9 @@ static void walk(bf_state *st, int s, long long cost, long long ticks)
     }
     n_lo = st->r_fixed ? st->r_fixed[s] : 1;
     n_hi = st->r_fixed ? st->r_fixed[s] : st->r_max;
-    for (c = 1; c <= st->c_max; ++c)
+    c_lo = st->c_fixed ? st->c_fixed[s] : 1;
+    c_hi = st->c_fixed ? st->c_fixed[s] : st->c_max;
+    for (c = c_lo; c <= c_hi; ++c)
         for (j = 0; j < st->n_batch; ++j)
             for (n = n_lo; n <= n_hi; ++n) {
                 const int32_t *cf = st->coef + 5 * s;
@@ -94,14 +97,15 @@ static void walk(bf_state *st, int s, long long cost, long long ticks)
 
 /*
  * One instance.  Returns 0 solved, 1 nothing feasible, <0 bad call.
- * coef is [S][5] = (a,k,q,p,o); r_fixed NULL enumerates 1..r_max.
+ * coef is [S][5] = (a,k,q,p,o); r_fixed NULL enumerates 1..r_max; c_fixed
+ * NULL enumerates 1..c_max, else pins each model's cores.
  * Outputs: cost, ticks, cfg[S][3] = (c,b,n); *n_visited = leaves walked.
  */
-int themis_bruteforce(int32_t n_stage, int32_t c_max, int32_t n_batch,
-                      const int32_t *batch_sizes, int32_t r_max, int32_t tick_us,
-                      const int32_t *coef, int32_t lambda, int32_t slo_us,
-                      const int32_t *r_fixed,
-                      int32_t *cost, int32_t *ticks, int32_t *cfg, int64_t *n_visited)
+int themis_bruteforce_ex(int32_t n_stage, int32_t c_max, int32_t n_batch,
+                         const int32_t *batch_sizes, int32_t r_max, int32_t tick_us,
+                         const int32_t *coef, int32_t lambda, int32_t slo_us,
+                         const int32_t *r_fixed, const int32_t *c_fixed,
+                         int32_t *cost, int32_t *ticks, int32_t *cfg, int64_t *n_visited)
 {
     bf_state st;
     int s, j;
@@ -115,6 +119,7 @@ int themis_bruteforce(int32_t n_stage, int32_t c_max, int32_t n_batch,
     st.batch_sizes = batch_sizes;
     st.coef = coef;
     st.r_fixed = r_fixed;
+    st.c_fixed = c_fixed;
     st.lambda = lambda;
     st.tick = tick_us;
     st.T = slo_us / tick_us;
@@ -130,4 +135,15 @@ int themis_bruteforce(int32_t n_stage, int32_t c_max, int32_t n_batch,
     for (s = 0; s < n_stage; ++s)
         for (j = 0; j < 3; ++j) cfg[3 * s + j] = st.best[s][j];
     return 0;
+}
+
+int themis_bruteforce(int32_t n_stage, int32_t c_max, int32_t n_batch,
+                      const int32_t *batch_sizes, int32_t r_max, int32_t tick_us,
+                      const int32_t *coef, int32_t lambda, int32_t slo_us,
+                      const int32_t *r_fixed,
+                      int32_t *cost, int32_t *ticks, int32_t *cfg, int64_t *n_visited)
+{
+    return themis_bruteforce_ex(n_stage, c_max, n_batch, batch_sizes, r_max, tick_us, coef,
+                                lambda, slo_us, r_fixed, (const int32_t *)0, cost, ticks, cfg,
+                                n_visited);
 }

@@ -166,12 +166,158 @@ int themis_oracle_candidates(int32_t n_stage, int32_t c_max, int32_t n_batch,
     return 0;
 }
 
+/* Scratch that solve_one() grows as needed and the caller frees. */
+typedef struct {
+    orc_cand *cand;
+    size_t cand_cap;
+    int64_t *g;
+    size_t g_cap;
+} orc_scratch;
+
+static void scratch_free(orc_scratch *w)
+{
+    free(w->cand);
+    free(w->g);
+    w->cand = NULL;
+    w->g = NULL;
+    w->cand_cap = w->g_cap = 0;
+}
+
+/*
+ * One instance at arrival rate `lambda`.  rf != NULL: replicas given per model
+ * (vertical).  cfix != NULL: cores given per model (only candidates with
+ * c == cfix[s] are considered; used for the horizontal remainder of
+ * Algorithm 1's fallback).  Writes status (0 solved, 1 none, 2 invalid),
+ * cost, ticks, cfg[S][3].  Returns <0 on an internal error.
+ */
+static int solve_one(int S, int c_max, int n_batch, const int32_t *batch_sizes, int r_max,
+                     int tick_us, int slo_max_us, const int32_t *cf, int64_t lambda,
+                     int64_t slo, const int32_t *rf, const int32_t *cfix, orc_scratch *w,
+                     int32_t *status, int32_t *cost, int32_t *ticks, int32_t *o_cfg)
+{
+    int K = c_max * n_batch;
+    int s, k;
+    int64_t T, t, best_cost, best_t;
+    size_t row;
+    orc_cand *cand;
+    int64_t *g;
+
+    *status = 1;
+    *cost = -1;
+    *ticks = -1;
+    memset(o_cfg, 0, sizeof(int32_t) * S * 3);
+    if (!instance_valid(lambda, slo, slo_max_us, cf, S, rf, r_max)) {
+        *status = 2;
+        return 0;
+    }
+    T = slo / tick_us;
+    row = (size_t)T + 1;
+    if ((size_t)S * K > w->cand_cap) {
+        free(w->cand);
+        w->cand_cap = (size_t)S * K;
+        w->cand = (orc_cand *)malloc(sizeof(orc_cand) * w->cand_cap);
+        if (!w->cand) return -1;
+    }
+    if ((size_t)(S + 1) * row > w->g_cap) {
+        free(w->g);
+        w->g_cap = (size_t)(S + 1) * row;
+        w->g = (int64_t *)malloc(sizeof(int64_t) * w->g_cap);
+        if (!w->g) return -1;
+    }
+    cand = w->cand;
+    g = w->g;
+
+    /* the candidates of every model, in (c ascending, b ascending) order */
+    for (s = 0; s < S; ++s)
+        for (k = 0; k < K; ++k) {
+            int c = k / n_batch + 1;
+            orc_cand cd = eval_candidate(cf + 5 * s, lambda, T, tick_us, c,
+                                         batch_sizes[k % n_batch], r_max, rf ? rf[s] : 0);
+            if (cfix && c != cfix[s]) cd.feasible = 0;
+            cand[(size_t)s * K + k] = cd;
+        }
+
+    /* no models left: only the empty split (zero latency) is reachable */
+    for (t = 0; t <= T; ++t) g[(size_t)S * row + t] = ORC_INF;
+    g[(size_t)S * row + 0] = 0;
+
+    /* add models one at a time; split budget t between model s and the rest */
+    for (s = S - 1; s >= 0; --s)
+        for (t = 0; t <= T; ++t) {
+            int64_t m = ORC_INF;
+            for (k = 0; k < K; ++k) {
+                const orc_cand *cd = &cand[(size_t)s * K + k];
+                int64_t rest;
+                if (!cd->feasible || cd->lt > t) continue;
+                rest = g[(size_t)(s + 1) * row + (t - cd->lt)];
+                if (rest >= ORC_INF) continue;
+                if (cd->cost + rest < m) m = cd->cost + rest;
+            }
+            g[(size_t)s * row + t] = m;
+        }
+
+    /* answer scan: budgets upward, strictly smaller total replaces */
+    best_cost = ORC_INF;
+    best_t = -1;
+    for (t = 0; t <= T; ++t)
+        if (g[t] < best_cost) { best_cost = g[t]; best_t = t; }
+    if (best_t < 0) return 0;
+
+    /* rebuild forward; first candidate in (c,b) order that attains g */
+    t = best_t;
+    for (s = 0; s < S; ++s) {
+        int found = 0;
+        for (k = 0; k < K && !found; ++k) {
+            const orc_cand *cd = &cand[(size_t)s * K + k];
+            int64_t rest;
+            if (!cd->feasible || cd->lt > t) continue;
+            rest = g[(size_t)(s + 1) * row + (t - cd->lt)];
+            if (rest >= ORC_INF) continue;
+            if (cd->cost + rest == g[(size_t)s * row + t]) {
+                o_cfg[3 * s + 0] = k / n_batch + 1;
+                o_cfg[3 * s + 1] = batch_sizes[k % n_batch];
+                o_cfg[3 * s + 2] = (int32_t)cd->r;
+                t -= cd->lt;
+                found = 1;
+            }
+        }
+        if (!found) return -2;
+    }
+    if (t != 0) return -3;
+    *status = 0;
+    *cost = (int32_t)best_cost;
+    *ticks = (int32_t)best_t;
+    return 0;
+}
+
 /*
  * Solve instances [i0, i1).  Outputs are indexed from i0:
  *   status 0 solved, 1 no configuration meets the SLO, 2 invalid input;
  *   cost = total cores, ticks = total latency on the grid (both -1 unless
  *   solved); cfg[.][s] = (c, b, n) per model (zeros unless solved).
+ * c_fixed (may be NULL): int32 [N][S], cores pinned per model.
  */
+int themis_oracle_solve_ex(int32_t n_stage, int32_t c_max, int32_t n_batch,
+                           const int32_t *batch_sizes, int32_t r_max,
+                           int32_t tick_us, int32_t slo_max_us, int32_t coef_shared,
+                           const int32_t *coef, const int32_t *lambda,
+                           const int32_t *slo_us, const int32_t *r_fixed,
+                           const int32_t *c_fixed, int32_t i0, int32_t i1,
+                           int32_t *status, int32_t *cost, int32_t *ticks, int32_t *cfg)
+{
+    int S = n_stage, i, rc = 0;
+    orc_scratch w = {0};
+    for (i = i0; i < i1 && rc == 0; ++i) {
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
+                       lambda[i], slo_us[i], r_fixed ? r_fixed + (size_t)i * S : NULL,
+                       c_fixed ? c_fixed + (size_t)i * S : NULL, &w, status + (i - i0),
+                       cost + (i - i0), ticks + (i - i0), cfg + (size_t)(i - i0) * S * 3);
+    }
+    scratch_free(&w);
+    return rc;
+}
+
 int themis_oracle_solve(int32_t n_stage, int32_t c_max, int32_t n_batch,
                         const int32_t *batch_sizes, int32_t r_max,
                         int32_t tick_us, int32_t slo_max_us, int32_t coef_shared,
@@ -180,97 +326,106 @@ int themis_oracle_solve(int32_t n_stage, int32_t c_max, int32_t n_batch,
                         int32_t i0, int32_t i1,
                         int32_t *status, int32_t *cost, int32_t *ticks, int32_t *cfg)
 {
-    int S = n_stage, K = c_max * n_batch;
-    int i, s, k;
-    orc_cand *cand = (orc_cand *)malloc(sizeof(orc_cand) * (size_t)S * K);
-    int64_t *g = NULL;
-    size_t g_cap = 0;
-    if (!cand) return -1;
+    return themis_oracle_solve_ex(n_stage, c_max, n_batch, batch_sizes, r_max, tick_us,
+                                  slo_max_us, coef_shared, coef, lambda, slo_us, r_fixed, NULL,
+                                  i0, i1, status, cost, ticks, cfg);
+}
 
-    for (i = i0; i < i1; ++i) {
+/*
+ * Algorithm 1 with its fallback (Section 4.4): solve the vertical problem at
+ * lambda; if there is no solution, binary-search the largest arrival rate the
+ * given replicas can absorb, keep the vertical configuration at that rate, and
+ * serve the remaining lambda - lambda_v by NEW instances found with the
+ * horizontal dynamic program (Algorithm 2: choose instance count and batch)
+ * "with the same CPU", i.e. with each model's cores pinned to the vertical
+ * configuration's.
+ *
+ * Readings where the listing is garbled: the midpoint is (left+right)/2, and a
+ * FEASIBLE midpoint raises `left` (the printed midpoint formula and branches
+ * would not search).  left starts at 1 and right at lambda, the loop runs while
+ * right - left > 1, and the configuration returned is the one at `left`; if
+ * even that is infeasible the instance has no solution (lambda_v = 0).
+ * Feasibility is not monotone in lambda (a higher rate fills batches faster),
+ * so the search is a heuristic; this checker follows its steps literally.
+ *
+ * Outputs per instance, indexed from i0:
+ *   status/cost/ticks/cfg   the vertical part (at lambda_v); status 1 if none
+ *   lambda_v                rate absorbed by the given replicas (lambda if the
+ *                           vertical solve succeeded outright, 0 if none)
+ *   status_h/cost_h/ticks_h/cfg_h  the new instances for lambda - lambda_v:
+ *                           status_h 0 with cost 0, ticks 0 and zero cfg when
+ *                           nothing remains; 1 when the remainder cannot be
+ *                           served within the SLO and r_max; 2 when there is
+ *                           no vertical part to pin the cores to.
+ */
+int themis_oracle_vertical_fallback(int32_t n_stage, int32_t c_max, int32_t n_batch,
+                                    const int32_t *batch_sizes, int32_t r_max,
+                                    int32_t tick_us, int32_t slo_max_us, int32_t coef_shared,
+                                    const int32_t *coef, const int32_t *lambda,
+                                    const int32_t *slo_us, const int32_t *r_fixed,
+                                    int32_t i0, int32_t i1,
+                                    int32_t *status, int32_t *cost, int32_t *ticks, int32_t *cfg,
+                                    int32_t *lambda_v,
+                                    int32_t *status_h, int32_t *cost_h, int32_t *ticks_h,
+                                    int32_t *cfg_h)
+{
+    int S = n_stage, i, s, rc = 0;
+    orc_scratch w = {0};
+    int32_t *cfix = (int32_t *)malloc(sizeof(int32_t) * (size_t)S);
+    if (!cfix) return -1;
+    for (i = i0; i < i1 && rc == 0; ++i) {
         const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
-        const int32_t *rf = r_fixed ? r_fixed + (size_t)i * S : NULL;
-        int32_t *o_cfg = cfg + (size_t)(i - i0) * S * 3;
-        int64_t T, t, best_cost, best_t;
-        size_t row;
+        const int32_t *rf = r_fixed + (size_t)i * S;
+        int32_t *st = status + (i - i0), *co = cost + (i - i0), *tk = ticks + (i - i0);
+        int32_t *cg = cfg + (size_t)(i - i0) * S * 3;
+        int32_t *sth = status_h + (i - i0), *coh = cost_h + (i - i0), *tkh = ticks_h + (i - i0);
+        int32_t *cgh = cfg_h + (size_t)(i - i0) * S * 3;
+        int64_t left, right;
 
-        status[i - i0] = 1;
-        cost[i - i0] = -1;
-        ticks[i - i0] = -1;
-        memset(o_cfg, 0, sizeof(int32_t) * S * 3);
-        if (!instance_valid(lambda[i], slo_us[i], slo_max_us, cf, S, rf, r_max)) {
-            status[i - i0] = 2;
+        lambda_v[i - i0] = 0;
+        *sth = 2;
+        *coh = -1;
+        *tkh = -1;
+        memset(cgh, 0, sizeof(int32_t) * S * 3);
+
+        rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
+                       lambda[i], slo_us[i], rf, NULL, &w, st, co, tk, cg);
+        if (rc) break;
+        if (*st == 2) continue;                 /* invalid input */
+        if (*st == 0) {                         /* vertical scaling alone suffices */
+            lambda_v[i - i0] = lambda[i];
+            *sth = 0;
+            *coh = 0;
+            *tkh = 0;
             continue;
         }
-        T = slo_us[i] / tick_us;
-        row = (size_t)T + 1;
-
-        /* the candidates of every model, in (c ascending, b ascending) order */
-        for (s = 0; s < S; ++s)
-            for (k = 0; k < K; ++k)
-                cand[(size_t)s * K + k] =
-                    eval_candidate(cf + 5 * s, lambda[i], T, tick_us,
-                                   k / n_batch + 1, batch_sizes[k % n_batch],
-                                   r_max, rf ? rf[s] : 0);
-
-        if ((size_t)(S + 1) * row > g_cap) {
-            free(g);
-            g_cap = (size_t)(S + 1) * row;
-            g = (int64_t *)malloc(sizeof(int64_t) * g_cap);
-            if (!g) { free(cand); return -1; }
+        /* binary search on the workload */
+        left = 1;
+        right = lambda[i];
+        while (right - left > 1 && rc == 0) {
+            int64_t mid = (left + right) / 2;
+            rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
+                           mid, slo_us[i], rf, NULL, &w, st, co, tk, cg);
+            if (*st == 0) left = mid; else right = mid;
         }
-        /* no models left: only the empty split (zero latency) is reachable */
-        for (t = 0; t <= T; ++t) g[(size_t)S * row + t] = ORC_INF;
-        g[(size_t)S * row + 0] = 0;
-
-        /* add models one at a time; split budget t between model s and the rest */
-        for (s = S - 1; s >= 0; --s)
-            for (t = 0; t <= T; ++t) {
-                int64_t m = ORC_INF;
-                for (k = 0; k < K; ++k) {
-                    const orc_cand *cd = &cand[(size_t)s * K + k];
-                    int64_t rest;
-                    if (!cd->feasible || cd->lt > t) continue;
-                    rest = g[(size_t)(s + 1) * row + (t - cd->lt)];
-                    if (rest >= ORC_INF) continue;
-                    if (cd->cost + rest < m) m = cd->cost + rest;
-                }
-                g[(size_t)s * row + t] = m;
-            }
-
-        /* answer scan: budgets upward, strictly smaller total replaces */
-        best_cost = ORC_INF;
-        best_t = -1;
-        for (t = 0; t <= T; ++t)
-            if (g[t] < best_cost) { best_cost = g[t]; best_t = t; }
-        if (best_t < 0) continue;
-
-        /* rebuild forward; first candidate in (c,b) order that attains g */
-        t = best_t;
-        for (s = 0; s < S; ++s) {
-            int found = 0;
-            for (k = 0; k < K && !found; ++k) {
-                const orc_cand *cd = &cand[(size_t)s * K + k];
-                int64_t rest;
-                if (!cd->feasible || cd->lt > t) continue;
-                rest = g[(size_t)(s + 1) * row + (t - cd->lt)];
-                if (rest >= ORC_INF) continue;
-                if (cd->cost + rest == g[(size_t)s * row + t]) {
-                    o_cfg[3 * s + 0] = k / n_batch + 1;
-                    o_cfg[3 * s + 1] = batch_sizes[k % n_batch];
-                    o_cfg[3 * s + 2] = (int32_t)cd->r;
-                    t -= cd->lt;
-                    found = 1;
-                }
-            }
-            if (!found) { free(cand); free(g); return -2; }
+        if (rc) break;
+        rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
+                       left, slo_us[i], rf, NULL, &w, st, co, tk, cg);
+        if (rc) break;
+        if (*st != 0) continue;                 /* not even one request per second */
+        lambda_v[i - i0] = (int32_t)left;
+        if (left == lambda[i]) {                /* only when lambda == 1 */
+            *sth = 0;
+            *coh = 0;
+            *tkh = 0;
+            continue;
         }
-        if (t != 0) { free(cand); free(g); return -3; }
-        status[i - i0] = 0;
-        cost[i - i0] = (int32_t)best_cost;
-        ticks[i - i0] = (int32_t)best_t;
+        /* new instances for the rest, cores as in the vertical configuration */
+        for (s = 0; s < S; ++s) cfix[s] = cg[3 * s + 0];
+        rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
+                       lambda[i] - left, slo_us[i], NULL, cfix, &w, sth, coh, tkh, cgh);
     }
-    free(cand);
-    free(g);
-    return 0;
+    free(cfix);
+    scratch_free(&w);
+    return rc;
 }
