@@ -147,6 +147,71 @@ int themis_solve_vertical(const themis_problem_t *p, const int32_t *d_coef,
                           void *stream);
 
 /*
+ * Horizontal-only solve (Algorithm 2): the cores of every model are given and
+ * the instance count n and the batch size b are chosen, n derived from the
+ * throughput constraint as in the joint solve; cost is n*c per model.
+ *   d_cores   int32 [N][S], every entry in 1..c_max (anything else makes the
+ *             instance THEMIS_INVALID), or NULL for the one-core instances of
+ *             Algorithm 2.
+ * Other arguments, outputs and workspace as for themis_solve_joint; the cfg
+ * rows repeat the given cores.
+ */
+int themis_solve_horizontal(const themis_problem_t *p, const int32_t *d_coef,
+                            const int32_t *d_lambda, const int32_t *d_slo_us,
+                            const int32_t *d_cores,
+                            int32_t *d_status, int32_t *d_cost, int32_t *d_ticks,
+                            int32_t *d_cfg, void *d_workspace, size_t workspace_bytes,
+                            void *stream);
+
+/*
+ * Bytes of device workspace themis_solve_vertical_fallback needs (0 if `p` is
+ * not acceptable): themis_workspace_bytes(p) plus the search state, a few words
+ * per instance and model.  256-byte aligned, contents need not be initialised.
+ */
+size_t themis_fallback_workspace_bytes(const themis_problem_t *p);
+
+/*
+ * Vertical solve with the fallback of Algorithm 1 (Section 4.4, the step taken
+ * when the main loop finds no configuration): where the given replicas cannot
+ * serve lambda within the SLO, a binary search on the arrival rate finds a rate
+ * lambda_v they can absorb (left = 1, right = lambda, a feasible midpoint
+ * (left+right)/2 raises left, until right - left <= 1; lambda_v = left), the
+ * vertical configuration is solved at lambda_v, and the remaining
+ * lambda - lambda_v is given to NEW instances chosen by the horizontal solve
+ * with each model's cores pinned to those of the vertical configuration.
+ * Feasibility is not monotone in the rate (a higher rate fills batches
+ * sooner), so like the paper's search this is a heuristic for "the largest
+ * rate"; its steps are fixed and the result is deterministic.
+ *
+ *   d_r_fixed   int32 [N][S]  running replicas, 1..r_max
+ *   lambda_max  host value: no instance's rate exceeds it (1..THEMIS_VALUE_MAX,
+ *               0 = THEMIS_VALUE_MAX).  It fixes the number of passes,
+ *               2 + ceil(log2(lambda_max - 1)); an instance with a larger rate
+ *               is reported THEMIS_INVALID.
+ * Outputs, all int32 on the device:
+ *   d_status/d_cost/d_ticks [N], d_cfg [N][S][3]   the vertical part at
+ *               lambda_v; THEMIS_INFEASIBLE when not even rate 1 fits
+ *   d_lambda_v [N]  rate the running replicas keep (lambda if the plain solve
+ *               succeeds, 0 when there is no vertical part or the instance is
+ *               invalid)
+ *   d_status_h/d_cost_h/d_ticks_h [N], d_cfg_h [N][S][3]   the new instances:
+ *               THEMIS_SOLVED with cost 0, ticks 0 and zero rows when nothing
+ *               remains; THEMIS_INFEASIBLE when the remainder cannot be served
+ *               within the SLO and r_max; THEMIS_INVALID when there is no
+ *               vertical part to take the cores from.
+ * d_workspace holds themis_fallback_workspace_bytes(p) bytes.  All passes run
+ * on `stream`; nothing is allocated and the host does not wait.
+ */
+int themis_solve_vertical_fallback(const themis_problem_t *p, const int32_t *d_coef,
+                                   const int32_t *d_lambda, const int32_t *d_slo_us,
+                                   const int32_t *d_r_fixed, int32_t lambda_max,
+                                   int32_t *d_status, int32_t *d_cost, int32_t *d_ticks,
+                                   int32_t *d_cfg, int32_t *d_lambda_v,
+                                   int32_t *d_status_h, int32_t *d_cost_h,
+                                   int32_t *d_ticks_h, int32_t *d_cfg_h,
+                                   void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Stage 1 alone: evaluate every candidate of every model of every instance
  * (the "calculate l, q, h" step of Algorithms 1 and 2, done once instead of
  * once per budget cell) into the workspace.  d_r_fixed NULL = joint.

@@ -109,9 +109,9 @@ __device__ __forceinline__ int in_range(int32_t v, int32_t lo, int32_t hi)
 __global__ __launch_bounds__(256) void k1_validate(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
-    int32_t* __restrict__ tmeta, int32_t* __restrict__ order, int32_t* __restrict__ ctrl,
-    uint32_t N, uint32_t S, int32_t r_max, uint32_t tick, int32_t slo_max, int coef_shared,
-    int merge_to)
+    const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta,
+    int32_t* __restrict__ order, int32_t* __restrict__ ctrl, uint32_t N, uint32_t S,
+    int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, int merge_to)
 {
     uint32_t i = blockIdx.x * 256u + threadIdx.x;
     int cls = -1;
@@ -126,6 +126,7 @@ __global__ __launch_bounds__(256) void k1_validate(
             ok &= in_range(a, 0, THEMIS_VALUE_MAX) & in_range(k, 0, THEMIS_VALUE_MAX) &
                   in_range(q, 0, THEMIS_VALUE_MAX) & (int)(pc >= 1) & in_range(o, 1, THEMIS_VALUE_MAX);
             if (r_fixed) ok &= in_range(r_fixed[(size_t)i * S + z], 1, r_max);
+            if (c_fixed) ok &= in_range(c_fixed[(size_t)i * S + z], 1, c_max);
         }
         int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
         tmeta[i] = T;
@@ -161,15 +162,20 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 // bucket's range and writes it to HBM in the form the min-plus stage reads.
 // The order inside a bucket is whatever the LDS atomics yield; nothing
 // downstream depends on it.
+//
+// c_fixed (may be null; then c_all, 0 = free): cores given per row; the model is
+// evaluated for those cores only and every other candidate of the row is marked infeasible.
+// sparse: rows of instances that failed the input check are left untouched.
 constexpr uint32_t STAGE_NONE = 0xFFFFu;  // lt field of an infeasible candidate in LDS
 
 __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
-    const int32_t* __restrict__ tmeta, StepEntry* __restrict__ step_tab,
-    uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows, uint32_t S, uint32_t K, uint32_t Kp,
-    uint32_t c_max, uint32_t r_max, uint32_t tick, double rtick, int coef_shared, uint32_t RPW,
-    uint32_t nb, uint32_t nbs, int copies_mask, int merge_to)
+    const int32_t* __restrict__ c_fixed, const int32_t* __restrict__ tmeta,
+    StepEntry* __restrict__ step_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
+    uint32_t S, uint32_t K, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick,
+    double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs, int copies_mask,
+    int merge_to, int sparse, uint32_t c_all)
 {
     extern __shared__ uint32_t smem[];
     // per local row: hist[nb + 1], cursor[nb + 1], staging[Kp]
@@ -179,19 +185,23 @@ __global__ __launch_bounds__(256) void k1_candidates(
 
     const uint32_t rl = threadIdx.x / nbat, j = threadIdx.x - rl * nbat;
     const uint32_t row = blockIdx.x * RPW + rl;
-    const bool live = rl < RPW && row < rows;
+    bool live = rl < RPW && row < rows;
     uint32_t* const hist = smem + rl * row_words;
     uint32_t* const cur = hist + HB;
     uint32_t* const stage = cur + HB;
+
+    const int32_t T = live ? tmeta[row / S] : -1;
+    if (sparse) {
+        if (!__syncthreads_or(T >= 0)) return;  // nothing to do for any row of this workgroup
+        live = live && T >= 0;
+    }
 
     for (uint32_t x = threadIdx.x; x < RPW * row_words; x += 256u)
         if (x % row_words < 2 * HB) smem[x] = 0u;
     __syncthreads();
 
-    int32_t T = -1;
     if (live) {
         const uint32_t i = row / S, s = row - i * S;
-        T = tmeta[i];
         if (T >= 0) {
             const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
             RowHdr h;
@@ -212,14 +222,20 @@ __global__ __launch_bounds__(256) void k1_candidates(
             bh.rM = recip_below(bh.M);
             bh.w = (bh.b - 1.0) * 1.0e6;
             const uint32_t pcap = (uint32_t)cf[3];
+            const uint32_t only = c_fixed ? (uint32_t)c_fixed[row] : c_all;
             Eval ev{-1, 0};
+            if (only) {
+                const uint32_t d = only < pcap ? only : pcap;
+                ev = eval_candidate(h, bh, (double)d, (double)r_max, (double)tick, rtick);
+            }
             for (uint32_t c = 1; c <= c_max; ++c) {
-                if (c <= pcap)
+                if (!only && c <= pcap)
                     ev = eval_candidate(h, bh, (double)c, (double)r_max, (double)tick, rtick);
-                const uint32_t w0 = ev.lt < 0 ? STAGE_NONE
-                                              : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
+                const bool none = ev.lt < 0 || (only && c != only);
+                const uint32_t w0 = none ? STAGE_NONE
+                                         : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
                 stage[(c - 1) * nbat + j] = w0;
-                atomicAdd(&hist[ev.lt < 0 ? nb : (uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
+                atomicAdd(&hist[none ? nb : (uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
             }
         } else {
             for (uint32_t c = 1; c <= c_max; ++c) stage[(c - 1) * nbat + j] = STAGE_NONE;
@@ -239,6 +255,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
         for (uint32_t r = wv; r < RPW; r += 4) {
             const uint32_t grow = blockIdx.x * RPW + r;
             if (grow >= rows) break;
+            if (sparse && tmeta[grow / S] < 0) continue;
             uint32_t* const hh = smem + r * row_words;
             const uint32_t v = lane < nb ? hh[lane] : 0u;
             uint32_t incl = v;
@@ -350,7 +367,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
 hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                              const int32_t* d_coef, const int32_t* d_lambda,
                              const int32_t* d_slo_us, const int32_t* d_r_fixed,
-                             char* ws, hipStream_t st)
+                             char* ws, hipStream_t st, const PassOpts& opts)
 {
     BatchList bl{};
     bl.n = p.n_batch;
@@ -360,9 +377,9 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     const MinplusPlan plan = make_plan(L);
     hipLaunchKernelGGL(k1_reset_ctrl, dim3(1), dim3(64), 0, st, ctrl);
     hipLaunchKernelGGL(k1_validate, dim3((L.N + 255) / 256), dim3(256), 0, st, d_coef,
-                       d_lambda, d_slo_us, d_r_fixed, tmeta, (int32_t*)(ws + L.order_off), ctrl,
-                       (uint32_t)L.N, (uint32_t)L.S, p.r_max, (uint32_t)p.tick_us,
-                       p.slo_max_us, p.coef_shared, plan.merge_to);
+                       d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, tmeta,
+                       (int32_t*)(ws + L.order_off), ctrl, (uint32_t)L.N, (uint32_t)L.S, p.r_max,
+                       p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, plan.merge_to);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -376,12 +393,13 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                             hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k1_candidates, dim3((rows + RPW - 1) / RPW), dim3(256), lds, st, d_coef,
-                       d_lambda, d_slo_us, d_r_fixed, (const int32_t*)tmeta,
+                       d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, (const int32_t*)tmeta,
                        (StepEntry*)(ws + L.step_off), (uint16_t*)(ws + L.bcum_off), bl, rows,
                        (uint32_t)L.S, (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.c_max,
                        (uint32_t)p.r_max, (uint32_t)p.tick_us,
                        (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
-                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to);
+                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
+                       opts.sparse, (uint32_t)opts.c_all);
     return hipGetLastError();
 }
 

@@ -22,7 +22,8 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum, const int32_t* __restrict__ tmeta,
     const uint16_t* __restrict__ frow, int32_t* __restrict__ status,
     int32_t* __restrict__ cost_out, int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg,
-    BatchList bl, int N, int S, int Kp, int nbs, int row_stride, int copies_mask, int merge_to)
+    BatchList bl, int N, int S, int Kp, int nbs, int row_stride, int copies_mask, int merge_to,
+    int sparse)
 {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -31,6 +32,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     int32_t* my_cfg = cfg + (size_t)i * S * 3;
 
     const int T = tmeta[i];
+    if (sparse && T < 0) return;  // switched off in this pass: outputs stay as they are
     const uint16_t* row0 = frow + (size_t)i * S * row_stride;
     uint32_t best = F_INF;
     if (T >= 0) best = row0[T];
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
 
 hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t* d_status,
                             int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg, char* ws,
-                            hipStream_t st)
+                            hipStream_t st, const PassOpts& opts)
 {
     BatchList bl{};
     bl.n = p.n_batch;
@@ -139,7 +141,7 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
                        d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.Kp, L.nbs, L.row_stride,
-                       plan.copies_mask, plan.merge_to);
+                       plan.copies_mask, plan.merge_to, opts.sparse);
     return hipGetLastError();
 }
 

@@ -64,24 +64,32 @@ int check_ws(const themis_problem_t* p, const void* ws, size_t bytes, Layout* L)
     return THEMIS_OK;
 }
 
+// one pass of the three stages
+int pass(const themis_problem_t& p, const Layout& L, const int32_t* d_coef,
+         const int32_t* d_lambda, const int32_t* d_slo_us, const int32_t* d_r_fixed,
+         int32_t* d_status, int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg, char* w,
+         hipStream_t st, const PassOpts& opts)
+{
+    if (launch_candidates(p, L, d_coef, d_lambda, d_slo_us, d_r_fixed, w, st, opts) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    if (launch_minplus(p, L, w, st) != hipSuccess) return THEMIS_ERR_LAUNCH;
+    if (launch_backtrack(p, L, d_status, d_cost, d_ticks, d_cfg, w, st, opts) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    return THEMIS_OK;
+}
+
 int solve(const themis_problem_t* p, const int32_t* d_coef, const int32_t* d_lambda,
           const int32_t* d_slo_us, const int32_t* d_r_fixed, int32_t* d_status,
           int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg, void* ws, size_t bytes,
-          void* stream)
+          void* stream, const PassOpts& opts = PassOpts())
 {
     if (!d_coef || !d_lambda || !d_slo_us || !d_status || !d_cost || !d_ticks || !d_cfg)
         return THEMIS_ERR_NULL;
     Layout L;
     int rc = check_ws(p, ws, bytes, &L);
     if (rc != THEMIS_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    char* w = static_cast<char*>(ws);
-    if (launch_candidates(*p, L, d_coef, d_lambda, d_slo_us, d_r_fixed, w, st) != hipSuccess)
-        return THEMIS_ERR_LAUNCH;
-    if (launch_minplus(*p, L, w, st) != hipSuccess) return THEMIS_ERR_LAUNCH;
-    if (launch_backtrack(*p, L, d_status, d_cost, d_ticks, d_cfg, w, st) != hipSuccess)
-        return THEMIS_ERR_LAUNCH;
-    return THEMIS_OK;
+    return pass(*p, L, d_coef, d_lambda, d_slo_us, d_r_fixed, d_status, d_cost, d_ticks, d_cfg,
+                static_cast<char*>(ws), static_cast<hipStream_t>(stream), opts);
 }
 
 }  // namespace
@@ -116,6 +124,75 @@ int themis_solve_vertical(const themis_problem_t* p, const int32_t* d_coef,
     if (!d_r_fixed) return THEMIS_ERR_NULL;
     return solve(p, d_coef, d_lambda, d_slo_us, d_r_fixed, d_status, d_cost, d_ticks, d_cfg,
                  d_workspace, workspace_bytes, stream);
+}
+
+int themis_solve_horizontal(const themis_problem_t* p, const int32_t* d_coef,
+                            const int32_t* d_lambda, const int32_t* d_slo_us,
+                            const int32_t* d_cores, int32_t* d_status, int32_t* d_cost,
+                            int32_t* d_ticks, int32_t* d_cfg, void* d_workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    PassOpts opts;
+    opts.c_fixed = d_cores;
+    opts.c_all = d_cores ? 0 : 1;
+    return solve(p, d_coef, d_lambda, d_slo_us, nullptr, d_status, d_cost, d_ticks, d_cfg,
+                 d_workspace, workspace_bytes, stream, opts);
+}
+
+size_t themis_fallback_workspace_bytes(const themis_problem_t* p)
+{
+    if (check(p) != THEMIS_OK) return 0;
+    return make_fallback_layout(make_layout(*p)).total;
+}
+
+int themis_solve_vertical_fallback(const themis_problem_t* p, const int32_t* d_coef,
+                                   const int32_t* d_lambda, const int32_t* d_slo_us,
+                                   const int32_t* d_r_fixed, int32_t lambda_max,
+                                   int32_t* d_status, int32_t* d_cost, int32_t* d_ticks,
+                                   int32_t* d_cfg, int32_t* d_lambda_v, int32_t* d_status_h,
+                                   int32_t* d_cost_h, int32_t* d_ticks_h, int32_t* d_cfg_h,
+                                   void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!d_coef || !d_lambda || !d_slo_us || !d_r_fixed || !d_status || !d_cost || !d_ticks ||
+        !d_cfg || !d_lambda_v || !d_status_h || !d_cost_h || !d_ticks_h || !d_cfg_h)
+        return THEMIS_ERR_NULL;
+    if (lambda_max < 0 || lambda_max > THEMIS_VALUE_MAX) return THEMIS_ERR_RANGE;
+    if (lambda_max == 0) lambda_max = THEMIS_VALUE_MAX;
+    int rc = check(p);
+    if (rc != THEMIS_OK) return rc;
+    const Layout L = make_layout(*p);
+    const FallbackLayout F = make_fallback_layout(L);
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0 ||
+        workspace_bytes < F.total)
+        return THEMIS_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* w = static_cast<char*>(d_workspace);
+    const FallbackOut out{d_status, d_cost,     d_ticks, d_cfg,    d_lambda_v,
+                          d_status_h, d_cost_h, d_ticks_h, d_cfg_h};
+    const int32_t* lam_cur = (const int32_t*)(w + F.lam_cur_off);
+
+    // the plain vertical solve, reported for every instance
+    rc = pass(*p, L, d_coef, d_lambda, d_slo_us, d_r_fixed, d_status, d_cost, d_ticks, d_cfg, w,
+              st, PassOpts());
+    if (rc != THEMIS_OK) return rc;
+    if (launch_fallback_step(L, F, 1, d_lambda, lambda_max, out, w, st) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    // the search: each pass only touches the instances that are still looking
+    PassOpts only_active;
+    only_active.sparse = 1;
+    for (int r = fallback_rounds(lambda_max); r > 0; --r) {
+        rc = pass(*p, L, d_coef, lam_cur, d_slo_us, d_r_fixed, d_status, d_cost, d_ticks, d_cfg,
+                  w, st, only_active);
+        if (rc != THEMIS_OK) return rc;
+        if (launch_fallback_step(L, F, 0, d_lambda, lambda_max, out, w, st) != hipSuccess)
+            return THEMIS_ERR_LAUNCH;
+    }
+    // new instances for what the running replicas could not absorb
+    PassOpts rest;
+    rest.sparse = 1;
+    rest.c_fixed = (const int32_t*)(w + F.cores_off);
+    return pass(*p, L, d_coef, (const int32_t*)(w + F.lam_rem_off), d_slo_us, nullptr,
+                d_status_h, d_cost_h, d_ticks_h, d_cfg_h, w, st, rest);
 }
 
 int themis_stage_candidates(const themis_problem_t* p, const int32_t* d_coef,

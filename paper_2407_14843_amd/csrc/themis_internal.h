@@ -183,11 +183,25 @@ struct BatchList {
     int32_t b[THEMIS_MAX_BATCH];
 };
 
+// Options of one pass over the three stages.
+//   c_fixed  int32 [N][S] or null: only candidates with exactly these cores
+//            compete (an entry outside 1..c_max makes the instance invalid)
+//   c_all    the same cores for every model of every instance (host value)
+//   sparse   nonzero: instances that fail the input check are skipped outright
+//            (no table rows, no outputs written) instead of being reported;
+//            used by multi-pass solves that switch instances off by handing
+//            them an arrival rate of zero
+struct PassOpts {
+    const int32_t* c_fixed = nullptr;
+    int c_all = 0;  // nonzero and c_fixed null: these cores for every model
+    int sparse = 0;
+};
+
 // kernel launchers (one per stage), defined next to their kernels
 hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                              const int32_t* d_coef, const int32_t* d_lambda,
                              const int32_t* d_slo_us, const int32_t* d_r_fixed,
-                             char* ws, hipStream_t st);
+                             char* ws, hipStream_t st, const PassOpts& opts = PassOpts());
 hipError_t launch_minplus(const themis_problem_t& p, const Layout& L, char* ws,
                           hipStream_t st);
 // lt of an entry of an instance with budget T (see StepEntry)
@@ -202,7 +216,52 @@ __host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, int merge
 
 hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L,
                             int32_t* d_status, int32_t* d_cost, int32_t* d_ticks,
-                            int32_t* d_cfg, char* ws, hipStream_t st);
+                            int32_t* d_cfg, char* ws, hipStream_t st,
+                            const PassOpts& opts = PassOpts());
+
+// Search state of the vertical solve with fallback, appended to the workspace
+// after Layout::total (every region 256-byte aligned):
+//   lam_cur int32 [N]  arrival rate of the next pass, 0 = instance switched off
+//   left, right int32 [N]  ends of the binary search
+//   state   int32 [N]  see k4_fallback.hip
+//   lam_rem int32 [N]  rate left for new instances, 0 = none
+//   cores   int32 [N][S] cores of the vertical configuration
+struct FallbackLayout {
+    size_t lam_cur_off, left_off, right_off, state_off, lam_rem_off, cores_off, total;
+};
+
+inline FallbackLayout make_fallback_layout(const Layout& L)
+{
+    FallbackLayout F{};
+    size_t at = L.total;
+    const size_t n4 = (size_t)L.N * sizeof(int32_t);
+    F.lam_cur_off = at; at = align256(at + n4);
+    F.left_off = at;    at = align256(at + n4);
+    F.right_off = at;   at = align256(at + n4);
+    F.state_off = at;   at = align256(at + n4);
+    F.lam_rem_off = at; at = align256(at + n4);
+    F.cores_off = at;   at = align256(at + n4 * L.S);
+    F.total = at;
+    return F;
+}
+
+// Passes after the first that the search needs when no rate exceeds lambda_max:
+// one per halving of the interval (1, lambda_max), plus the solve at its lower end.
+inline int fallback_rounds(int32_t lambda_max)
+{
+    int rounds = 1;
+    for (int64_t w = (int64_t)lambda_max - 1; w > 1; w = (w + 1) / 2) ++rounds;
+    return rounds;
+}
+
+struct FallbackOut {
+    int32_t *status, *cost, *ticks, *cfg;          // vertical part
+    int32_t* lambda_v;
+    int32_t *status_h, *cost_h, *ticks_h, *cfg_h;  // new instances
+};
+hipError_t launch_fallback_step(const Layout& L, const FallbackLayout& F, int first,
+                                const int32_t* d_lambda, int32_t lambda_max,
+                                const FallbackOut& out, char* ws, hipStream_t st);
 hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_lt,
                                     int32_t* d_cost, hipStream_t st);
 hipError_t launch_count_relaxations(const Layout& L, const char* ws,

@@ -23,7 +23,9 @@ ERR_NULL, ERR_SHAPE, ERR_BATCH, ERR_RANGE, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -
 
 EXPORTS = [
     "themis_version", "themis_check_problem", "themis_workspace_bytes",
-    "themis_solve_joint", "themis_solve_vertical", "themis_stage_candidates",
+    "themis_solve_joint", "themis_solve_vertical", "themis_solve_horizontal",
+    "themis_fallback_workspace_bytes", "themis_solve_vertical_fallback",
+    "themis_stage_candidates",
     "themis_stage_minplus", "themis_stage_backtrack", "themis_export_candidates",
     "themis_count_relaxations", "themis_probe_lds_read", "themis_probe_valu",
 ]
@@ -62,6 +64,13 @@ def lib():
         L.themis_solve_joint.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.themis_solve_vertical.restype = ctypes.c_int
         L.themis_solve_vertical.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.themis_solve_horizontal.restype = ctypes.c_int
+        L.themis_solve_horizontal.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.themis_fallback_workspace_bytes.restype = sz
+        L.themis_fallback_workspace_bytes.argtypes = [P]
+        L.themis_solve_vertical_fallback.restype = ctypes.c_int
+        L.themis_solve_vertical_fallback.argtypes = (
+            [P, vp, vp, vp, vp, ctypes.c_int32] + [vp] * 9 + [vp, sz, vp])
         L.themis_stage_candidates.restype = ctypes.c_int
         L.themis_stage_candidates.argtypes = [P, vp, vp, vp, vp, vp, sz, vp]
         L.themis_stage_minplus.restype = ctypes.c_int
@@ -152,6 +161,28 @@ def themis_solve_vertical(p, coef, lam, slo_us, r_fixed, status, cost, ticks, cf
         _stream(stream)))
 
 
+def themis_solve_horizontal(p, coef, lam, slo_us, cores, status, cost, ticks, cfg, workspace,
+                            stream=None):
+    _chk("themis_solve_horizontal", lib().themis_solve_horizontal(
+        ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(cores), _dp(status),
+        _dp(cost), _dp(ticks), _dp(cfg), _dp(workspace, torch.uint8), workspace.numel(),
+        _stream(stream)))
+
+
+def fallback_workspace_bytes(p: ThemisProblem) -> int:
+    return int(lib().themis_fallback_workspace_bytes(ctypes.byref(p)))
+
+
+def themis_solve_vertical_fallback(p, coef, lam, slo_us, r_fixed, lambda_max, status, cost,
+                                   ticks, cfg, lambda_v, status_h, cost_h, ticks_h, cfg_h,
+                                   workspace, stream=None):
+    _chk("themis_solve_vertical_fallback", lib().themis_solve_vertical_fallback(
+        ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(r_fixed), int(lambda_max),
+        _dp(status), _dp(cost), _dp(ticks), _dp(cfg), _dp(lambda_v), _dp(status_h),
+        _dp(cost_h), _dp(ticks_h), _dp(cfg_h), _dp(workspace, torch.uint8),
+        workspace.numel(), _stream(stream)))
+
+
 def themis_stage_candidates(p, coef, lam, slo_us, r_fixed, workspace, stream=None):
     _chk("themis_stage_candidates", lib().themis_stage_candidates(
         ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(r_fixed),
@@ -221,6 +252,32 @@ class DeviceBatch:
             themis_solve_vertical(self.p, self.coef, self.lam, self.slo_us, self.r_fixed,
                                   self.status, self.cost, self.ticks, self.cfg,
                                   self.workspace, stream)
+
+    def solve_horizontal(self, cores=None, stream=None):
+        """Enqueue the horizontal-only solve (cores: numpy int [N][S] or None = one core)."""
+        self.cores = None if cores is None else torch.from_numpy(
+            cores.astype("int32")).to(self.device).contiguous()
+        themis_solve_horizontal(self.p, self.coef, self.lam, self.slo_us, self.cores,
+                                self.status, self.cost, self.ticks, self.cfg, self.workspace,
+                                stream)
+
+    def solve_vertical_fallback(self, lambda_max=0, stream=None):
+        """Enqueue the vertical solve with fallback; results via fallback_results()."""
+        if getattr(self, "fb", None) is None:
+            n = fallback_workspace_bytes(self.p)
+            self.fb_workspace = torch.empty(n, dtype=torch.uint8, device=self.device)
+            self.lambda_v = torch.empty(self.p.n_inst, dtype=torch.int32, device=self.device)
+            self.fb = alloc_outputs(self.p, self.device)
+        themis_solve_vertical_fallback(self.p, self.coef, self.lam, self.slo_us, self.r_fixed,
+                                       lambda_max, self.status, self.cost, self.ticks, self.cfg,
+                                       self.lambda_v, *self.fb, self.fb_workspace, stream)
+
+    def fallback_results(self):
+        torch.cuda.synchronize()
+        names = ("status", "cost", "ticks", "cfg", "lambda_v", "status_h", "cost_h", "ticks_h",
+                 "cfg_h")
+        bufs = (self.status, self.cost, self.ticks, self.cfg, self.lambda_v) + tuple(self.fb)
+        return {k: b.cpu().numpy() for k, b in zip(names, bufs)}
 
     def results(self):
         torch.cuda.synchronize()
