@@ -212,6 +212,33 @@ int themis_solve_vertical_fallback(const themis_problem_t *p, const int32_t *d_c
                                    void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Bytes of device workspace themis_check_stability needs (0 if `p` is not
+ * acceptable): themis_workspace_bytes(p) plus one set of results.
+ */
+size_t themis_stability_workspace_bytes(const themis_problem_t *p);
+
+/*
+ * Workload-stability test (Section 5.1.3, "When"): the horizontal solve of
+ * Algorithm 2 at the current rate and at the predicted rate; the workload is
+ * stable when both succeed with the same (c, b, n) for every model, which is
+ * the paper's cue to move from vertical to horizontal scaling.  The predicted
+ * rate is an input (the paper's predictor is not part of this library).
+ *   d_lambda_now, d_lambda_pred  int32 [N]
+ *   d_cores    as for themis_solve_horizontal (NULL = one core)
+ *   d_stable   int32 [N]  1 stable, 0 not (also when either solve fails or the
+ *              instance is invalid)
+ *   d_status/d_cost/d_ticks/d_cfg  the solve at the current rate, as for
+ *              themis_solve_joint
+ * d_workspace holds themis_stability_workspace_bytes(p) bytes.
+ */
+int themis_check_stability(const themis_problem_t *p, const int32_t *d_coef,
+                           const int32_t *d_lambda_now, const int32_t *d_lambda_pred,
+                           const int32_t *d_slo_us, const int32_t *d_cores,
+                           int32_t *d_stable, int32_t *d_status, int32_t *d_cost,
+                           int32_t *d_ticks, int32_t *d_cfg, void *d_workspace,
+                           size_t workspace_bytes, void *stream);
+
+/*
  * Stage 1 alone: evaluate every candidate of every model of every instance
  * (the "calculate l, q, h" step of Algorithms 1 and 2, done once instead of
  * once per budget cell) into the workspace.  d_r_fixed NULL = joint.

@@ -52,6 +52,9 @@ def _load():
         _lib.themis_oracle_vertical_fallback.argtypes = [i32, i32, i32, p, i32, i32, i32, i32,
                                                          p, p, p, p, i32, i32,
                                                          p, p, p, p, p, p, p, p, p]
+        _lib.themis_oracle_stability.restype = ctypes.c_int
+        _lib.themis_oracle_stability.argtypes = [i32, i32, i32, p, i32, i32, i32, i32,
+                                                 p, p, p, p, p, i32, i32, p, p, p, p, p]
         _lib.themis_bruteforce_ex.restype = ctypes.c_int
         _lib.themis_bruteforce_ex.argtypes = [i32, i32, i32, p, i32, i32, p, i32, i32, p, p,
                                               p, p, p, p]
@@ -164,6 +167,26 @@ def vertical_fallback(w, threads: int = 1):
         with ThreadPoolExecutor(threads) as pool:
             list(pool.map(lambda ab: run(*ab), spans))
     return out
+
+
+def stability(w, lam_pred, cores=None):
+    """Section 5.1.3's stability test for every instance of a joint workload.
+
+    Returns (stable[N], status[N], cost[N], ticks[N], cfg[N][S][3]); the last
+    four are the horizontal solve at the current rate w.lam."""
+    lib = _load()
+    bs, coef, lam, slo, _ = _common(w)
+    n, s = w.n_inst, w.n_stage
+    lp, cx = _i32(lam_pred), _i32(cores)
+    stable, status, cost, ticks = (np.empty(n, np.int32) for _ in range(4))
+    cfg = np.empty((n, s, 3), np.int32)
+    rc = lib.themis_oracle_stability(s, w.c_max, len(bs), _ptr(bs), w.r_max, w.tick_us,
+                                     w.slo_max_us, int(w.coef_shared), _ptr(coef), _ptr(lam),
+                                     _ptr(lp), _ptr(slo), _ptr(cx), 0, n, _ptr(stable),
+                                     _ptr(status), _ptr(cost), _ptr(ticks), _ptr(cfg))
+    if rc != 0:
+        raise RuntimeError(f"themis_oracle_stability failed: {rc}")
+    return stable, status, cost, ticks, cfg
 
 
 def bruteforce(w, i: int = 0, c_fixed=None):

@@ -185,8 +185,8 @@ static void scratch_free(orc_scratch *w)
 
 /*
  * One instance at arrival rate `lambda`.  rf != NULL: replicas given per model
- * (vertical).  cfix != NULL: cores given per model (only candidates with
- * c == cfix[s] are considered; used for the horizontal remainder of
+ * (vertical).  cfix != NULL: cores given per model, each in 1..c_max or the
+ * instance is invalid (only candidates with c == cfix[s] are considered; used for the horizontal remainder of
  * Algorithm 1's fallback).  Writes status (0 solved, 1 none, 2 invalid),
  * cost, ticks, cfg[S][3].  Returns <0 on an internal error.
  */
@@ -210,6 +210,12 @@ static int solve_one(int S, int c_max, int n_batch, const int32_t *batch_sizes, 
         *status = 2;
         return 0;
     }
+    if (cfix)                          /* given cores must be allocatable */
+        for (s = 0; s < S; ++s)
+            if (cfix[s] < 1 || cfix[s] > c_max) {
+                *status = 2;
+                return 0;
+            }
     T = slo / tick_us;
     row = (size_t)T + 1;
     if ((size_t)S * K > w->cand_cap) {
@@ -426,6 +432,54 @@ int themis_oracle_vertical_fallback(int32_t n_stage, int32_t c_max, int32_t n_ba
                        lambda[i] - left, slo_us[i], NULL, cfix, &w, sth, coh, tkh, cgh);
     }
     free(cfix);
+    scratch_free(&w);
+    return rc;
+}
+
+/*
+ * The workload-stability test of Section 5.1.3 ("When"): run the horizontal
+ * dynamic program (Algorithm 2) at the current rate and at the predicted
+ * rate and call the workload stable when both yield the same configuration
+ * (same instance count and batch size for every model).  cores (may be NULL =
+ * the one-core instances of Algorithm 2): int32 [N][S].
+ *
+ * Outputs indexed from i0: stable = 1 only when both solves succeed and agree;
+ * status/cost/ticks/cfg are those of the current rate.
+ */
+int themis_oracle_stability(int32_t n_stage, int32_t c_max, int32_t n_batch,
+                            const int32_t *batch_sizes, int32_t r_max,
+                            int32_t tick_us, int32_t slo_max_us, int32_t coef_shared,
+                            const int32_t *coef, const int32_t *lambda_now,
+                            const int32_t *lambda_pred, const int32_t *slo_us,
+                            const int32_t *cores, int32_t i0, int32_t i1,
+                            int32_t *stable, int32_t *status, int32_t *cost, int32_t *ticks,
+                            int32_t *cfg)
+{
+    int S = n_stage, i, s, rc = 0;
+    orc_scratch w = {0};
+    int32_t *one = (int32_t *)malloc(sizeof(int32_t) * (size_t)S);
+    int32_t *cfg_p = (int32_t *)malloc(sizeof(int32_t) * (size_t)S * 3);
+    if (!one || !cfg_p) { free(one); free(cfg_p); return -1; }
+    for (s = 0; s < S; ++s) one[s] = 1;
+    for (i = i0; i < i1 && rc == 0; ++i) {
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        const int32_t *cx = cores ? cores + (size_t)i * S : one;
+        int32_t *cg = cfg + (size_t)(i - i0) * S * 3;
+        int32_t st_p, cost_p, ticks_p;
+        stable[i - i0] = 0;
+        rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
+                       lambda_now[i], slo_us[i], NULL, cx, &w, status + (i - i0),
+                       cost + (i - i0), ticks + (i - i0), cg);
+        if (rc) break;
+        rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
+                       lambda_pred[i], slo_us[i], NULL, cx, &w, &st_p, &cost_p, &ticks_p, cfg_p);
+        if (rc) break;
+        if (status[i - i0] == 0 && st_p == 0 &&
+            memcmp(cg, cfg_p, sizeof(int32_t) * S * 3) == 0)
+            stable[i - i0] = 1;
+    }
+    free(one);
+    free(cfg_p);
     scratch_free(&w);
     return rc;
 }

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(HERE, "libthemis_hip.so")
 SOURCES = ["themis_api.hip", "k1_candidates.hip", "k2_minplus.hip", "k3_backtrack.hip",
-           "k4_fallback.hip", "lds_probe.hip"]
+           "k4_fallback.hip", "k5_stability.hip", "lds_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

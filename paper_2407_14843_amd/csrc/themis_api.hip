@@ -195,6 +195,46 @@ int themis_solve_vertical_fallback(const themis_problem_t* p, const int32_t* d_c
                 d_status_h, d_cost_h, d_ticks_h, d_cfg_h, w, st, rest);
 }
 
+size_t themis_stability_workspace_bytes(const themis_problem_t* p)
+{
+    if (check(p) != THEMIS_OK) return 0;
+    return make_stability_layout(make_layout(*p)).total;
+}
+
+int themis_check_stability(const themis_problem_t* p, const int32_t* d_coef,
+                           const int32_t* d_lambda_now, const int32_t* d_lambda_pred,
+                           const int32_t* d_slo_us, const int32_t* d_cores, int32_t* d_stable,
+                           int32_t* d_status, int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg,
+                           void* d_workspace, size_t workspace_bytes, void* stream)
+{
+    if (!d_coef || !d_lambda_now || !d_lambda_pred || !d_slo_us || !d_stable || !d_status ||
+        !d_cost || !d_ticks || !d_cfg)
+        return THEMIS_ERR_NULL;
+    int rc = check(p);
+    if (rc != THEMIS_OK) return rc;
+    const Layout L = make_layout(*p);
+    const StabilityLayout B = make_stability_layout(L);
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0 ||
+        workspace_bytes < B.total)
+        return THEMIS_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* w = static_cast<char*>(d_workspace);
+    PassOpts opts;
+    opts.c_fixed = d_cores;
+    opts.c_all = d_cores ? 0 : 1;
+    int32_t* status_p = (int32_t*)(w + B.status_off);
+    int32_t* cfg_p = (int32_t*)(w + B.cfg_off);
+    rc = pass(*p, L, d_coef, d_lambda_pred, d_slo_us, nullptr, status_p,
+              (int32_t*)(w + B.cost_off), (int32_t*)(w + B.ticks_off), cfg_p, w, st, opts);
+    if (rc != THEMIS_OK) return rc;
+    rc = pass(*p, L, d_coef, d_lambda_now, d_slo_us, nullptr, d_status, d_cost, d_ticks, d_cfg, w,
+              st, opts);
+    if (rc != THEMIS_OK) return rc;
+    return launch_same_config(L, d_status, d_cfg, status_p, cfg_p, d_stable, st) == hipSuccess
+               ? THEMIS_OK
+               : THEMIS_ERR_LAUNCH;
+}
+
 int themis_stage_candidates(const themis_problem_t* p, const int32_t* d_coef,
                             const int32_t* d_lambda, const int32_t* d_slo_us,
                             const int32_t* d_r_fixed, void* d_workspace,

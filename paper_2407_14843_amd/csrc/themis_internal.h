@@ -262,6 +262,30 @@ struct FallbackOut {
 hipError_t launch_fallback_step(const Layout& L, const FallbackLayout& F, int first,
                                 const int32_t* d_lambda, int32_t lambda_max,
                                 const FallbackOut& out, char* ws, hipStream_t st);
+// Results of the solve at the predicted rate, appended to the workspace after
+// Layout::total for the stability test: status, cost, ticks int32 [N] each and
+// cfg int32 [N][S][3].
+struct StabilityLayout {
+    size_t status_off, cost_off, ticks_off, cfg_off, total;
+};
+
+inline StabilityLayout make_stability_layout(const Layout& L)
+{
+    StabilityLayout B{};
+    size_t at = L.total;
+    const size_t n4 = (size_t)L.N * sizeof(int32_t);
+    B.status_off = at; at = align256(at + n4);
+    B.cost_off = at;   at = align256(at + n4);
+    B.ticks_off = at;  at = align256(at + n4);
+    B.cfg_off = at;    at = align256(at + n4 * L.S * 3);
+    B.total = at;
+    return B;
+}
+
+hipError_t launch_same_config(const Layout& L, const int32_t* status_now, const int32_t* cfg_now,
+                              const int32_t* status_pred, const int32_t* cfg_pred,
+                              int32_t* stable, hipStream_t st);
+
 hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_lt,
                                     int32_t* d_cost, hipStream_t st);
 hipError_t launch_count_relaxations(const Layout& L, const char* ws,

@@ -25,6 +25,7 @@ EXPORTS = [
     "themis_version", "themis_check_problem", "themis_workspace_bytes",
     "themis_solve_joint", "themis_solve_vertical", "themis_solve_horizontal",
     "themis_fallback_workspace_bytes", "themis_solve_vertical_fallback",
+    "themis_stability_workspace_bytes", "themis_check_stability",
     "themis_stage_candidates",
     "themis_stage_minplus", "themis_stage_backtrack", "themis_export_candidates",
     "themis_count_relaxations", "themis_probe_lds_read", "themis_probe_valu",
@@ -71,6 +72,10 @@ def lib():
         L.themis_solve_vertical_fallback.restype = ctypes.c_int
         L.themis_solve_vertical_fallback.argtypes = (
             [P, vp, vp, vp, vp, ctypes.c_int32] + [vp] * 9 + [vp, sz, vp])
+        L.themis_stability_workspace_bytes.restype = sz
+        L.themis_stability_workspace_bytes.argtypes = [P]
+        L.themis_check_stability.restype = ctypes.c_int
+        L.themis_check_stability.argtypes = [P] + [vp] * 10 + [vp, sz, vp]
         L.themis_stage_candidates.restype = ctypes.c_int
         L.themis_stage_candidates.argtypes = [P, vp, vp, vp, vp, vp, sz, vp]
         L.themis_stage_minplus.restype = ctypes.c_int
@@ -183,6 +188,18 @@ def themis_solve_vertical_fallback(p, coef, lam, slo_us, r_fixed, lambda_max, st
         workspace.numel(), _stream(stream)))
 
 
+def stability_workspace_bytes(p: ThemisProblem) -> int:
+    return int(lib().themis_stability_workspace_bytes(ctypes.byref(p)))
+
+
+def themis_check_stability(p, coef, lam_now, lam_pred, slo_us, cores, stable, status, cost,
+                           ticks, cfg, workspace, stream=None):
+    _chk("themis_check_stability", lib().themis_check_stability(
+        ctypes.byref(p), _dp(coef), _dp(lam_now), _dp(lam_pred), _dp(slo_us), _dp(cores),
+        _dp(stable), _dp(status), _dp(cost), _dp(ticks), _dp(cfg),
+        _dp(workspace, torch.uint8), workspace.numel(), _stream(stream)))
+
+
 def themis_stage_candidates(p, coef, lam, slo_us, r_fixed, workspace, stream=None):
     _chk("themis_stage_candidates", lib().themis_stage_candidates(
         ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(r_fixed),
@@ -260,6 +277,20 @@ class DeviceBatch:
         themis_solve_horizontal(self.p, self.coef, self.lam, self.slo_us, self.cores,
                                 self.status, self.cost, self.ticks, self.cfg, self.workspace,
                                 stream)
+
+    def check_stability(self, lam_pred, cores=None, stream=None):
+        """Enqueue the stability test; returns the device tensor of flags."""
+        to = lambda a: None if a is None else torch.from_numpy(
+            a.astype("int32")).to(self.device).contiguous()
+        self.lam_pred, self.cores = to(lam_pred), to(cores)
+        ws = torch.empty(stability_workspace_bytes(self.p), dtype=torch.uint8,
+                         device=self.device)
+        self.stable = torch.empty(self.p.n_inst, dtype=torch.int32, device=self.device)
+        themis_check_stability(self.p, self.coef, self.lam, self.lam_pred, self.slo_us,
+                               self.cores, self.stable, self.status, self.cost, self.ticks,
+                               self.cfg, ws, stream)
+        self.stability_workspace = ws
+        return self.stable
 
     def solve_vertical_fallback(self, lambda_max=0, stream=None):
         """Enqueue the vertical solve with fallback; results via fallback_results()."""

@@ -124,3 +124,15 @@ def test_fallback_argument_checks_on_host(T):
     assert f(ctypes.byref(p), *args, 0, *outs, ctypes.c_void_p(264), 1 << 30, None) == \
         T.ERR_WORKSPACE
     assert f(ctypes.byref(p), *args, 0, *outs, None, 1 << 30, None) == T.ERR_WORKSPACE
+
+
+def test_stability_workspace_and_argument_checks(T):
+    import ctypes
+    p = T.make_problem(100, 3, 8, [1, 2], 8, 1000, 300_000)
+    assert T.stability_workspace_bytes(p) >= T.workspace_bytes(p) + (3 + 9) * 100 * 4
+    f = T.lib().themis_check_stability
+    one = ctypes.c_void_p(256)
+    assert f(ctypes.byref(p), one, one, None, one, None, *([one] * 5), one, 1 << 30, None) == \
+        T.ERR_NULL
+    assert f(ctypes.byref(p), one, one, one, one, None, *([one] * 5), one, 256, None) == \
+        T.ERR_WORKSPACE

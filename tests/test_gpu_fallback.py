@@ -183,3 +183,22 @@ def test_fallback_twice_on_one_workspace(T, oracle):
     for got, w in ((got1, w1), (got2, w2)):
         want = oracle.vertical_fallback(w, threads=8)
         same([got[k] for k in FB_KEYS], [want[k] for k in FB_KEYS], FB_KEYS)
+
+
+# ------------------------------------------------------------ stability test
+@pytest.mark.parametrize("idx,n,given", [(1, 200, False), (0, 64, True), (3, 50, False)])
+def test_stability_matches_checker(T, oracle, idx, n, given):
+    w = as_joint(wl.workload(idx, n))
+    rng = np.random.default_rng(30 + idx)
+    w.slo_us = (w.slo_us // 3).astype(np.int32)
+    pred = np.clip(w.lam.astype(np.int64) + rng.integers(-20, 40, w.n_inst), 1, 1 << 20)
+    pred = pred.astype(np.int32)
+    pred[1] = 0                                   # invalid prediction: not stable
+    cores = rng.integers(1, 3, size=(w.n_inst, w.n_stage)).astype(np.int32) if given else None
+    want = oracle.stability(w, pred, cores)
+    print(f"[case] stability workload {idx} N={n} given={given}", flush=True)
+    b = T.DeviceBatch(w)
+    stable = b.check_stability(pred, cores)
+    got = (stable.cpu().numpy(),) + b.results()
+    same(got, want, ("stable",) + FB_KEYS[:4])
+    assert want[0].any() and not want[0].all() and want[0][1] == 0

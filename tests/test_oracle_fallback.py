@@ -133,3 +133,60 @@ def test_fallback_invalid_inputs(oracle):
     for i in (1, 3):
         assert out["status"][i] == 2 and out["status_h"][i] == 2 and out["lambda_v"][i] == 0
         assert not out["cfg"][i].any() and not out["cfg_h"][i].any()
+
+
+# ---------------------------------------------------------------- stability test
+def _joint(coef_rows, lam, slo_us, c_max, batch_sizes, r_max, tick):
+    coef = np.asarray(coef_rows, np.int32)[None, :, :]
+    return wl.Workload("t", wl.JOINT, 1, coef.shape[1], c_max, list(batch_sizes), r_max, tick,
+                       max(slo_us, 1), False, coef, np.array([lam], np.int32),
+                       np.array([slo_us], np.int32))
+
+
+def test_hand_derived_stability(oracle):
+    """Catches: comparing instance counts only (batch ignored), calling two
+    failed solves 'the same', solving with free cores instead of one core."""
+    g = json.load(open(GOLDEN))
+    for cs in g["stability"]["cases"]:
+        w = _joint([g["coef"]], cs["now"], cs["slo_us"], g["c_max"], g["batch_sizes"],
+                   g["r_max"], g["tick_us"])
+        stable, st, cost, ticks, cfg = oracle.stability(w, np.array([cs["pred"]], np.int32))
+        assert int(stable[0]) == cs["stable"], cs
+        assert cfg[0].tolist() == cs["cfg_now"]
+
+
+def test_stability_by_enumeration(oracle):
+    """stable <=> the exhaustive optimum with the cores pinned exists at both
+    rates and is the same triple for every model."""
+    rng = np.random.default_rng(8)
+    n_stable = n_unstable = 0
+    for rep in range(40):
+        w = wl.tiny_random(rng, wl.JOINT, 12, 3)
+        # predicted rate close to the current one, so that both outcomes occur
+        pred = np.clip(w.lam.astype(np.int64) + rng.integers(-30, 60, w.n_inst), 1, 1 << 20)
+        cores = None if rep % 2 else rng.integers(1, w.c_max + 1,
+                                                  size=(w.n_inst, w.n_stage)).astype(np.int32)
+        stable, st, cost, ticks, cfg = oracle.stability(w, pred.astype(np.int32), cores)
+        for i in range(w.n_inst):
+            cx = np.ones(w.n_stage, np.int32) if cores is None else cores[i]
+            a = oracle.bruteforce(w, i, c_fixed=cx)
+            wp = w.take(np.array([i]))
+            wp.lam = np.array([pred[i]], np.int32)
+            b = oracle.bruteforce(wp, 0, c_fixed=cx)
+            want = int(a[0] == 0 and b[0] == 0 and a[3].tolist() == b[3].tolist())
+            assert int(stable[i]) == want
+            assert (int(st[i]), int(cost[i]), int(ticks[i])) == a[:3]
+            assert cfg[i].tolist() == a[3].tolist()
+            n_stable += want
+            n_unstable += 1 - want
+    assert n_stable > 30 and n_unstable > 30, (n_stable, n_unstable)
+
+
+def test_given_cores_out_of_range_are_invalid(oracle):
+    rng = np.random.default_rng(2)
+    w = wl.tiny_random(rng, wl.JOINT, 5, 2)
+    cores = np.ones((w.n_inst, w.n_stage), np.int32)
+    cores[1, 0] = 0
+    cores[3, -1] = w.c_max + 1
+    st = oracle.solve(w, c_fixed=cores)[0]
+    assert st[1] == 2 and st[3] == 2 and (st[[0, 2, 4]] != 2).all()
