@@ -73,6 +73,11 @@ def _i32(a):
 
 
 def _common(w):
+    # model options are process-wide in the C files: set them for this call
+    qm, pf = int(getattr(w, "queue_model", 0)), int(getattr(w, "profile_form", 0))
+    if _load().themis_oracle_set_model(qm, pf) or _load().themis_bruteforce_set_model(qm, pf):
+        raise ValueError(f"unknown model options {qm}, {pf}")
+    assert w.coef.shape[-1] == (6 if pf else 5)
     bs = np.asarray(w.batch_sizes, dtype=np.int32)
     return bs, _i32(w.coef), _i32(w.lam), _i32(w.slo_us), _i32(w.r_fixed)
 

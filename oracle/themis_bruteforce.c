@@ -19,6 +19,9 @@
  *
  * with proc_s = ceil((a + k b + q b^2)/min(c,p)) + o,
  * queue_s = ceil((b-1) * 1e6 * n / lambda), lt_s = ceil((proc_s+queue_s)/tick).
+ * themis_bruteforce_set_model() switches to the paper's printed forms: the
+ * queue of Eq. 4, ceil((b-1)*1e6/lambda), or of Eq. 3, the larger of that and
+ * proc - floor((n b + 1)*1e6/lambda); and Eq. 1's term d*b added to proc.
  * Exponential in the number of models: only for tiny pipelines.
  *
  * It deliberately duplicates the few lines of latency arithmetic instead of
@@ -34,7 +37,8 @@
 typedef struct {
     int S, c_max, n_batch, r_max;
     const int32_t *batch_sizes;
-    const int32_t *coef;    /* [S][5] */
+    const int32_t *coef;    /* [S][5], or [S][6] with the sixth coefficient d */
+    int queue_model, profile_form;
     const int32_t *r_fixed; /* [S] or NULL */
     const int32_t *c_fixed; /* [S] or NULL */
     long long lambda, tick, T;
@@ -79,14 +83,22 @@ static void walk(bf_state *st, int s, long long cost, long long ticks)
     for (c = c_lo; c <= c_hi; ++c)
         for (j = 0; j < st->n_batch; ++j)
             for (n = n_lo; n <= n_hi; ++n) {
-                const int32_t *cf = st->coef + 5 * s;
+                const int32_t *cf = st->coef + (st->profile_form ? 6 : 5) * s;
                 long long b = st->batch_sizes[j];
                 long long cores = c < cf[3] ? c : cf[3];
                 long long proc = up_div((long long)cf[0] + (long long)cf[1] * b +
                                         (long long)cf[2] * b * b, cores) + cf[4];
                 long long queue, lt;
+                if (st->profile_form) proc += (long long)cf[5] * b;   /* Eq. 1's delta*b */
                 if (st->lambda * proc > (long long)n * b * 1000000LL) continue;
-                queue = up_div((b - 1) * 1000000LL * n, st->lambda);
+                if (st->queue_model == 0) {
+                    queue = up_div((b - 1) * 1000000LL * n, st->lambda);
+                } else {
+                    /* Eq. 4; for model 2 the larger of it and Eq. 3's busy term */
+                    long long busy = proc - ((long long)n * b + 1) * 1000000LL / st->lambda;
+                    queue = up_div((b - 1) * 1000000LL, st->lambda);
+                    if (st->queue_model == 2 && busy > queue) queue = busy;
+                }
                 lt = up_div(proc + queue, st->tick);
                 st->cur[s][0] = c;
                 st->cur[s][1] = (int)b;
@@ -101,6 +113,17 @@ static void walk(bf_state *st, int s, long long cost, long long ticks)
  * NULL enumerates 1..c_max, else pins each model's cores.
  * Outputs: cost, ticks, cfg[S][3] = (c,b,n); *n_visited = leaves walked.
  */
+static int bf_queue_model = 0, bf_profile_form = 0;
+
+/* Model options as in themis_oracle.c's header; process-wide. */
+int themis_bruteforce_set_model(int32_t queue_model, int32_t profile_form)
+{
+    if (queue_model < 0 || queue_model > 2 || profile_form < 0 || profile_form > 1) return -1;
+    bf_queue_model = queue_model;
+    bf_profile_form = profile_form;
+    return 0;
+}
+
 int themis_bruteforce_ex(int32_t n_stage, int32_t c_max, int32_t n_batch,
                          const int32_t *batch_sizes, int32_t r_max, int32_t tick_us,
                          const int32_t *coef, int32_t lambda, int32_t slo_us,
@@ -120,6 +143,8 @@ int themis_bruteforce_ex(int32_t n_stage, int32_t c_max, int32_t n_batch,
     st.coef = coef;
     st.r_fixed = r_fixed;
     st.c_fixed = c_fixed;
+    st.queue_model = bf_queue_model;
+    st.profile_form = bf_profile_form;
     st.lambda = lambda;
     st.tick = tick_us;
     st.T = slo_us / tick_us;

@@ -60,6 +60,33 @@
 
 #define ORC_INF ((int64_t)1 << 60)
 
+/*
+ * Model options, process-wide (set them before calling, never while another
+ * thread is inside this file).
+ *   queue model   0  batch-fill wait per replica, ceil((b-1)*1e6*n/lambda)
+ *                    (the default reading described above)
+ *                 1  Eq. 4 as printed: one queue per model,
+ *                    ceil((b-1)*1e6/lambda), independent of n
+ *                 2  Eq. 3: max( (b-1)/lambda , l(b,c) - (n*b+1)/lambda ),
+ *                    first term as in 1, second rounded up as
+ *                    proc - floor((n*b+1)*1e6/lambda)
+ *   profile form  0  five coefficients (a,k,q,p,o)
+ *                 1  six (a,k,q,p,o,d): Eq. 1's term delta*b, which does not
+ *                    shrink with the cores, is added: proc += d*b
+ */
+static int g_queue_model = 0;
+static int g_profile_form = 0;
+
+int themis_oracle_set_model(int32_t queue_model, int32_t profile_form)
+{
+    if (queue_model < 0 || queue_model > 2 || profile_form < 0 || profile_form > 1) return -1;
+    g_queue_model = queue_model;
+    g_profile_form = profile_form;
+    return 0;
+}
+
+static int coef_stride(void) { return g_profile_form ? 6 : 5; }
+
 static int64_t ceildiv64(int64_t x, int64_t d) { return (x + d - 1) / d; }
 
 /* One candidate (c, b) of one model: Section 4.4, the "calculate l, q, h" step. */
@@ -77,8 +104,9 @@ static orc_cand eval_candidate(const int32_t *cf, int64_t lambda, int64_t T,
 {
     orc_cand out;
     int64_t a = cf[0], k = cf[1], q = cf[2], p = cf[3], o = cf[4];
+    int64_t d = g_profile_form ? cf[5] : 0;
     int64_t div = c < p ? c : p;
-    int64_t proc = ceildiv64(a + k * b + q * b * b, div) + o;
+    int64_t proc = ceildiv64(a + k * b + q * b * b, div) + d * b + o;
     int64_t r;
     memset(&out, 0, sizeof out);
     if (r_given <= 0) {
@@ -91,8 +119,18 @@ static orc_cand eval_candidate(const int32_t *cf, int64_t lambda, int64_t T,
         if (lambda * proc > r * b * 1000000) return out;
     }
     {
-        int64_t queue = ceildiv64((b - 1) * 1000000 * r, lambda);
-        int64_t lat = proc + queue;
+        int64_t queue, lat;
+        if (g_queue_model == 0) {
+            queue = ceildiv64((b - 1) * 1000000 * r, lambda);
+        } else {
+            queue = ceildiv64((b - 1) * 1000000, lambda);
+            if (g_queue_model == 2) {
+                /* all n instances busy: wait for one to finish */
+                int64_t busy = proc - ((r * b + 1) * 1000000) / lambda;
+                if (busy > queue) queue = busy;
+            }
+        }
+        lat = proc + queue;
         int64_t lt = ceildiv64(lat, tick);
         if (lt > T) return out;
         out.feasible = 1;
@@ -106,7 +144,7 @@ static orc_cand eval_candidate(const int32_t *cf, int64_t lambda, int64_t T,
 
 /*
  * Input ranges an instance must respect (an interface rule, not the paper's):
- * 1 <= lambda <= 2^20, 0 <= SLO <= slo_max, 0 <= a,k,q <= 2^20,
+ * 1 <= lambda <= 2^20, 0 <= SLO <= slo_max, 0 <= a,k,q,d <= 2^20,
  * 1 <= o <= 2^20, p >= 1, and 1 <= given instances <= r_max.  They keep every
  * product below 2^63 for batch sizes up to 1024 and make every stage latency
  * at least one microsecond.
@@ -117,13 +155,14 @@ static int instance_valid(int64_t lambda, int64_t slo, int64_t slo_max,
                           const int32_t *cf, int S,
                           const int32_t *rfix, int64_t r_max)
 {
-    int s, j;
+    int s, j, cs = coef_stride();
     if (lambda < 1 || lambda > ORC_VAL_MAX || slo < 0 || slo > slo_max) return 0;
     for (s = 0; s < S; ++s) {
         for (j = 0; j < 3; ++j)
-            if (cf[5 * s + j] < 0 || cf[5 * s + j] > ORC_VAL_MAX) return 0;
-        if (cf[5 * s + 3] < 1) return 0;
-        if (cf[5 * s + 4] < 1 || cf[5 * s + 4] > ORC_VAL_MAX) return 0;
+            if (cf[cs * s + j] < 0 || cf[cs * s + j] > ORC_VAL_MAX) return 0;
+        if (cf[cs * s + 3] < 1) return 0;
+        if (cf[cs * s + 4] < 1 || cf[cs * s + 4] > ORC_VAL_MAX) return 0;
+        if (cs == 6 && (cf[cs * s + 5] < 0 || cf[cs * s + 5] > ORC_VAL_MAX)) return 0;
         if (rfix && (rfix[s] < 1 || rfix[s] > r_max)) return 0;
     }
     return 1;
@@ -145,7 +184,7 @@ int themis_oracle_candidates(int32_t n_stage, int32_t c_max, int32_t n_batch,
     int S = n_stage, K = c_max * n_batch;
     int i, s, c, j;
     for (i = i0; i < i1; ++i) {
-        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * coef_stride();
         const int32_t *rf = r_fixed ? r_fixed + (size_t)i * S : NULL;
         int ok = instance_valid(lambda[i], slo_us[i], slo_max_us, cf, S, rf, r_max);
         int64_t T = ok ? slo_us[i] / tick_us : 0;
@@ -156,7 +195,7 @@ int themis_oracle_candidates(int32_t n_stage, int32_t c_max, int32_t n_batch,
                     orc_cand cd;
                     memset(&cd, 0, sizeof cd);
                     if (ok)
-                        cd = eval_candidate(cf + 5 * s, lambda[i], T, tick_us, c,
+                        cd = eval_candidate(cf + coef_stride() * s, lambda[i], T, tick_us, c,
                                             batch_sizes[j], r_max, rf ? rf[s] : 0);
                     lt_out[at] = cd.feasible ? (int32_t)cd.lt : -1;
                     cost_out[at] = cd.feasible ? (int32_t)cd.cost : -1;
@@ -237,7 +276,7 @@ static int solve_one(int S, int c_max, int n_batch, const int32_t *batch_sizes, 
     for (s = 0; s < S; ++s)
         for (k = 0; k < K; ++k) {
             int c = k / n_batch + 1;
-            orc_cand cd = eval_candidate(cf + 5 * s, lambda, T, tick_us, c,
+            orc_cand cd = eval_candidate(cf + coef_stride() * s, lambda, T, tick_us, c,
                                          batch_sizes[k % n_batch], r_max, rf ? rf[s] : 0);
             if (cfix && c != cfix[s]) cd.feasible = 0;
             cand[(size_t)s * K + k] = cd;
@@ -314,7 +353,7 @@ int themis_oracle_solve_ex(int32_t n_stage, int32_t c_max, int32_t n_batch,
     int S = n_stage, i, rc = 0;
     orc_scratch w = {0};
     for (i = i0; i < i1 && rc == 0; ++i) {
-        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * coef_stride();
         rc = solve_one(S, c_max, n_batch, batch_sizes, r_max, tick_us, slo_max_us, cf,
                        lambda[i], slo_us[i], r_fixed ? r_fixed + (size_t)i * S : NULL,
                        c_fixed ? c_fixed + (size_t)i * S : NULL, &w, status + (i - i0),
@@ -380,7 +419,7 @@ int themis_oracle_vertical_fallback(int32_t n_stage, int32_t c_max, int32_t n_ba
     int32_t *cfix = (int32_t *)malloc(sizeof(int32_t) * (size_t)S);
     if (!cfix) return -1;
     for (i = i0; i < i1 && rc == 0; ++i) {
-        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * coef_stride();
         const int32_t *rf = r_fixed + (size_t)i * S;
         int32_t *st = status + (i - i0), *co = cost + (i - i0), *tk = ticks + (i - i0);
         int32_t *cg = cfg + (size_t)(i - i0) * S * 3;
@@ -462,7 +501,7 @@ int themis_oracle_stability(int32_t n_stage, int32_t c_max, int32_t n_batch,
     if (!one || !cfg_p) { free(one); free(cfg_p); return -1; }
     for (s = 0; s < S; ++s) one[s] = 1;
     for (i = i0; i < i1 && rc == 0; ++i) {
-        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * 5;
+        const int32_t *cf = coef_shared ? coef : coef + (size_t)i * S * coef_stride();
         const int32_t *cx = cores ? cores + (size_t)i * S : one;
         int32_t *cg = cfg + (size_t)(i - i0) * S * 3;
         int32_t st_p, cost_p, ticks_p;

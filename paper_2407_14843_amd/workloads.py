@@ -51,6 +51,8 @@ class Workload:
     lam: np.ndarray              # int32 [N]
     slo_us: np.ndarray           # int32 [N]
     r_fixed: Optional[np.ndarray] = None   # int32 [N][S], vertical only
+    queue_model: int = 0         # 0 batch fill per replica, 1 Eq. 4, 2 Eq. 3
+    profile_form: int = 0        # 0: coefficients (a,k,q,p,o); 1: (a,k,q,p,o,d), Eq. 1's delta
     seed: int = 0
     note: str = ""
     extra: dict = field(default_factory=dict)
@@ -82,6 +84,19 @@ class Workload:
         assert r_fixed.shape == (self.n_inst, self.n_stage)
         return replace(self, variant=VERTICAL, r_fixed=r_fixed,
                        r_max=self.r_max if r_max is None else r_max)
+
+
+    def with_model(self, queue_model: int = 0, d: Optional[np.ndarray] = None) -> "Workload":
+        """The same instances under another queue model and, when `d` is given
+        (int array shaped like coef without its last axis), with that sixth
+        profile coefficient appended."""
+        coef, form = self.coef, self.profile_form
+        if d is not None:
+            assert form == 0 and d.shape == coef.shape[:-1]
+            coef = np.ascontiguousarray(
+                np.concatenate([coef, np.asarray(d, np.int32)[..., None]], axis=-1))
+            form = 1
+        return replace(self, coef=coef, queue_model=queue_model, profile_form=form)
 
 
 def _pow2_upto(bmax: int) -> List[int]:
