@@ -26,6 +26,15 @@
  *     lt    = ceil((proc+queue) / tick_us)   grid ticks
  *     cost  = n*c
  * and the budget of an instance is T = floor(slo_us / tick_us) ticks.
+ * The queue above is Eq. 4's batch-fill wait seen by one replica (each of the
+ * n replicas receives lambda/n).  themis_problem_t.queue_model selects the
+ * paper's printed forms instead:
+ *     THEMIS_QUEUE_SHARED      queue = ceil((b-1)*1e6 / lambda)          Eq. 4
+ *     THEMIS_QUEUE_WORST_CASE  queue = max of that and
+ *                              proc - floor((n*b+1)*1e6 / lambda)        Eq. 3
+ * and profile_form = THEMIS_PROFILE_EQ1 adds Eq. 1's term delta*b, which does
+ * not shrink with the cores: six coefficients (a,k,q,p,o,d) per model and
+ *     proc  = ceil((a + k*b + q*b*b) / min(c,p)) + d*b + o.
  * A candidate is the pair (c,b); its index is k = (c-1)*n_batch + j for
  * b = batch_sizes[j], so index order is (c ascending, b ascending).
  *
@@ -71,6 +80,14 @@ extern "C" {
 #define THEMIS_ERR_WORKSPACE (-5) /* workspace missing, misaligned or too small */
 #define THEMIS_ERR_LAUNCH (-6)    /* the HIP runtime refused a launch           */
 
+/* themis_problem_t.queue_model */
+#define THEMIS_QUEUE_PER_REPLICA 0
+#define THEMIS_QUEUE_SHARED 1
+#define THEMIS_QUEUE_WORST_CASE 2
+/* themis_problem_t.profile_form */
+#define THEMIS_PROFILE_5 0   /* coefficients (a,k,q,p,o)                        */
+#define THEMIS_PROFILE_EQ1 1 /* coefficients (a,k,q,p,o,d)                      */
+
 /* per-instance status written to d_status */
 #define THEMIS_SOLVED 0
 #define THEMIS_INFEASIBLE 1 /* no assignment meets both constraints            */
@@ -82,9 +99,9 @@ extern "C" {
  *
  * An instance is THEMIS_INVALID when lambda is outside 1..THEMIS_VALUE_MAX,
  * slo_us is outside 0..slo_max_us, any of a,k,q is outside
- * 0..THEMIS_VALUE_MAX, o is outside 1..THEMIS_VALUE_MAX (so every stage takes
- * at least one tick), p < 1, or (vertical) a given replica count is outside
- * 1..r_max.
+ * 0..THEMIS_VALUE_MAX (d too, where present), o is outside
+ * 1..THEMIS_VALUE_MAX (so every stage takes at least one tick), p < 1, or
+ * (vertical) a given replica count is outside 1..r_max.
  */
 typedef struct themis_problem {
     int32_t n_inst;     /* N >= 1 instances                                    */
@@ -95,8 +112,12 @@ typedef struct themis_problem {
     int32_t r_max;      /* replicas range over 1..r_max (vertical: bound on r_fixed) */
     int32_t tick_us;    /* grid resolution, >= 1                               */
     int32_t slo_max_us; /* caller's bound on every slo_us entry, >= 0          */
-    int32_t coef_shared;/* 1: d_coef is [S][5]; 0: [N][S][5]; order a,k,q,p,o  */
-    int32_t reserved[4];/* must be zero                                        */
+    int32_t coef_shared;/* 1: d_coef is [S][5]; 0: [N][S][5]; order a,k,q,p,o
+                           ([S][6] / [N][S][6], order a,k,q,p,o,d, under
+                           THEMIS_PROFILE_EQ1)                                  */
+    int32_t queue_model;/* THEMIS_QUEUE_*                                      */
+    int32_t profile_form;/* THEMIS_PROFILE_*                                   */
+    int32_t reserved[2];/* must be zero                                        */
 } themis_problem_t;
 
 /* Library version, major*100 + minor. */
@@ -119,7 +140,8 @@ size_t themis_workspace_bytes(const themis_problem_t *p);
 
 /*
  * Joint horizontal+vertical solve (Eq. 6 with n_s derived per candidate).
- *   d_coef    int32, [S][5] or [N][S][5] per coef_shared
+ *   d_coef    int32, [S][5] or [N][S][5] per coef_shared (six per model
+ *             under THEMIS_PROFILE_EQ1)
  *   d_lambda  int32 [N]   requests per second
  *   d_slo_us  int32 [N]
  *   d_status  int32 [N]   THEMIS_SOLVED / INFEASIBLE / INVALID

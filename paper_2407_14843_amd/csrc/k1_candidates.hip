@@ -13,6 +13,9 @@
 //   n     = ceil(lambda proc / (b 1e6))   joint,  or the given replicas
 //   queue = ceil((b-1) 1e6 n / lambda)
 //   lt    = ceil((proc + queue) / tick),  cost = n c
+// Options: the queue of Eq. 4 as printed, ceil((b-1) 1e6 / lambda), or of
+// Eq. 3, the larger of that and proc - floor((n b + 1) 1e6 / lambda); and a
+// sixth coefficient d for Eq. 1's term delta*b: proc += d b.
 // A candidate is dropped when n exceeds r_max, when the given replicas cannot
 // carry lambda, or when lt exceeds the instance's budget T.
 #include "themis_internal.h"
@@ -52,6 +55,7 @@ __device__ __forceinline__ double ceil_div_d(double n, double d, double rd)
 // What every candidate of a row shares.
 struct RowHdr {
     double a, k, q, o;   // profile coefficients
+    double d;            // Eq. 1's delta (0 when the profile has five coefficients)
     double p;            // core cap
     double lam, rlam;    // arrival rate and recip_below() of it
     double slo, T;       // SLO in microseconds, budget in ticks
@@ -71,6 +75,7 @@ struct Eval {
     int32_t lt, n;
 };
 
+template <int QUEUE>
 __device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& bh, double d,
                                                double r_max, double tick, double rtick)
 {
@@ -78,7 +83,7 @@ __device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& 
     // stay together.  A candidate that fails an early test may push later
     // intermediates past 2^53; they are then inexact but never used.
     const double num = __builtin_fma(h.q, bh.b2, __builtin_fma(h.k, bh.b, h.a));  // < 2^41
-    const double proc = ceil_div_d(num, d, recip_below(d)) + h.o;
+    const double proc = ceil_div_d(num, d, recip_below(d)) + __builtin_fma(h.d, bh.b, h.o);
     // anything slower than the SLO also exceeds T ticks; cutting it here keeps
     // every later product of a surviving candidate below 2^53
     bool ok = proc <= h.slo;
@@ -89,9 +94,19 @@ __device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& 
     n = derive ? n : h.n_given;
     // joint: no more than r_max replicas; vertical: the given ones must carry lambda
     ok = ok && (derive ? lp <= r_max * bh.M : lp <= n * bh.M);
-    const double qn = bh.w * n;  // < 2^45
+    // batch-fill wait: per replica (each sees lambda / n) or Eq. 4's shared queue
+    const double qn = QUEUE == THEMIS_QUEUE_PER_REPLICA ? bh.w * n : bh.w;  // < 2^45
     ok = ok && qn <= (h.slo - proc) * h.lam;  // proc + queue <= SLO
-    const double lat = proc + ceil_div_d(qn, h.lam, h.rlam);
+    double queue = ceil_div_d(qn, h.lam, h.rlam);
+    if (QUEUE == THEMIS_QUEUE_WORST_CASE) {
+        // Eq. 3: all n instances busy.  floor(x / lambda) = ceil((x + 1) / lambda) - 1;
+        // x = (n b + 1) 1e6 < 2^46
+        const double x = __builtin_fma(n, bh.M, 1.0e6);
+        const double busy = proc - (ceil_div_d(x + 1.0, h.lam, h.rlam) - 1.0);
+        queue = busy > queue ? busy : queue;
+        ok = ok && proc + queue <= h.slo;
+    }
+    const double lat = proc + queue;
     const double lt = ceil_div_d(lat, tick, rtick);
     ok = ok && lt <= h.T;
     return Eval{ok ? (int32_t)lt : -1, ok ? (int32_t)n : 0};
@@ -111,18 +126,20 @@ __global__ __launch_bounds__(256) void k1_validate(
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta,
     int32_t* __restrict__ order, int32_t* __restrict__ ctrl, uint32_t N, uint32_t S,
-    int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, int merge_to)
+    int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, int merge_to,
+    uint32_t cs)
 {
     uint32_t i = blockIdx.x * 256u + threadIdx.x;
     int cls = -1;
     if (i < N) {
         int32_t lam = lambda[i], slo = slo_us[i];
-        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5);
+        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * cs);  // cs words per model
         // no short-circuiting: the loads of all models are independent
         int ok = in_range(lam, 1, THEMIS_VALUE_MAX) & in_range(slo, 0, slo_max);
         for (uint32_t z = 0; z < S; ++z) {
-            const int32_t* cz = cf + z * 5;
+            const int32_t* cz = cf + z * cs;
             const int32_t a = cz[0], k = cz[1], q = cz[2], pc = cz[3], o = cz[4];
+            if (cs == 6) ok &= in_range(cz[5], 0, THEMIS_VALUE_MAX);
             ok &= in_range(a, 0, THEMIS_VALUE_MAX) & in_range(k, 0, THEMIS_VALUE_MAX) &
                   in_range(q, 0, THEMIS_VALUE_MAX) & (int)(pc >= 1) & in_range(o, 1, THEMIS_VALUE_MAX);
             if (r_fixed) ok &= in_range(r_fixed[(size_t)i * S + z], 1, r_max);
@@ -168,6 +185,7 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 // sparse: rows of instances that failed the input check are left untouched.
 constexpr uint32_t STAGE_NONE = 0xFFFFu;  // lt field of an infeasible candidate in LDS
 
+template <int QUEUE>
 __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
@@ -175,7 +193,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     StepEntry* __restrict__ step_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
     uint32_t S, uint32_t K, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick,
     double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs, int copies_mask,
-    int merge_to, int sparse, uint32_t c_all)
+    int merge_to, int sparse, uint32_t c_all, uint32_t cs)
 {
     extern __shared__ uint32_t smem[];
     // per local row: hist[nb + 1], cursor[nb + 1], staging[Kp]
@@ -203,13 +221,14 @@ __global__ __launch_bounds__(256) void k1_candidates(
     if (live) {
         const uint32_t i = row / S, s = row - i * S;
         if (T >= 0) {
-            const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * 5) + s * 5;
+            const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * cs) + s * cs;
             RowHdr h;
             h.a = (double)cf[0];
             h.k = (double)cf[1];
             h.q = (double)cf[2];
             h.p = (double)cf[3];
             h.o = (double)cf[4];
+            h.d = cs == 6 ? (double)cf[5] : 0.0;
             h.lam = (double)lambda[i];
             h.rlam = recip_below(h.lam);
             h.slo = (double)slo_us[i];
@@ -226,11 +245,11 @@ __global__ __launch_bounds__(256) void k1_candidates(
             Eval ev{-1, 0};
             if (only) {
                 const uint32_t d = only < pcap ? only : pcap;
-                ev = eval_candidate(h, bh, (double)d, (double)r_max, (double)tick, rtick);
+                ev = eval_candidate<QUEUE>(h, bh, (double)d, (double)r_max, (double)tick, rtick);
             }
             for (uint32_t c = 1; c <= c_max; ++c) {
                 if (!only && c <= pcap)
-                    ev = eval_candidate(h, bh, (double)c, (double)r_max, (double)tick, rtick);
+                    ev = eval_candidate<QUEUE>(h, bh, (double)c, (double)r_max, (double)tick, rtick);
                 const bool none = ev.lt < 0 || (only && c != only);
                 const uint32_t w0 = none ? STAGE_NONE
                                          : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
@@ -372,6 +391,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     BatchList bl{};
     bl.n = p.n_batch;
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
+    const uint32_t cs = p.profile_form == THEMIS_PROFILE_EQ1 ? 6u : 5u;
     int32_t* tmeta = (int32_t*)(ws + L.tmeta_off);
     int32_t* ctrl = (int32_t*)(ws + L.ctrl_off);
     const MinplusPlan plan = make_plan(L);
@@ -379,7 +399,8 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     hipLaunchKernelGGL(k1_validate, dim3((L.N + 255) / 256), dim3(256), 0, st, d_coef,
                        d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, tmeta,
                        (int32_t*)(ws + L.order_off), ctrl, (uint32_t)L.N, (uint32_t)L.S, p.r_max,
-                       p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, plan.merge_to);
+                       p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, plan.merge_to,
+                       cs);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -389,18 +410,25 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     while (RPW > 1 && RPW * row_bytes > 52u * 1024u) --RPW;
     const uint32_t rows = (uint32_t)L.N * L.S;
     const size_t lds = (size_t)RPW * row_bytes;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k1_candidates),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k1_candidates, dim3((rows + RPW - 1) / RPW), dim3(256), lds, st, d_coef,
-                       d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, (const int32_t*)tmeta,
-                       (StepEntry*)(ws + L.step_off), (uint16_t*)(ws + L.bcum_off), bl, rows,
-                       (uint32_t)L.S, (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.c_max,
-                       (uint32_t)p.r_max, (uint32_t)p.tick_us,
-                       (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
-                       (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
-                       opts.sparse, (uint32_t)opts.c_all);
-    return hipGetLastError();
+    auto launch = [&](auto kernel) -> hipError_t {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(kernel, dim3((rows + RPW - 1) / RPW), dim3(256), lds, st, d_coef,
+                           d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, (const int32_t*)tmeta,
+                           (StepEntry*)(ws + L.step_off), (uint16_t*)(ws + L.bcum_off), bl, rows,
+                           (uint32_t)L.S, (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.c_max,
+                           (uint32_t)p.r_max, (uint32_t)p.tick_us,
+                           (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
+                           (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
+                           opts.sparse, (uint32_t)opts.c_all, cs);
+        return hipGetLastError();
+    };
+    switch (p.queue_model) {
+    case THEMIS_QUEUE_SHARED: return launch(&k1_candidates<THEMIS_QUEUE_SHARED>);
+    case THEMIS_QUEUE_WORST_CASE: return launch(&k1_candidates<THEMIS_QUEUE_WORST_CASE>);
+    default: return launch(&k1_candidates<THEMIS_QUEUE_PER_REPLICA>);
+    }
 }
 
 hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_lt,

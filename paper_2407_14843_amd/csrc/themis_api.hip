@@ -32,8 +32,10 @@ int check(const themis_problem_t* p)
     if (p->n_inst < 1 || p->n_stage < 1 || p->c_max < 1 || p->r_max < 1 || p->tick_us < 1 ||
         p->slo_max_us < 0 || (p->coef_shared != 0 && p->coef_shared != 1))
         return THEMIS_ERR_SHAPE;
-    for (int z = 0; z < 4; ++z)
-        if (p->reserved[z] != 0) return THEMIS_ERR_SHAPE;
+    if (p->queue_model < THEMIS_QUEUE_PER_REPLICA || p->queue_model > THEMIS_QUEUE_WORST_CASE ||
+        p->profile_form < THEMIS_PROFILE_5 || p->profile_form > THEMIS_PROFILE_EQ1 ||
+        p->reserved[0] != 0 || p->reserved[1] != 0)
+        return THEMIS_ERR_SHAPE;
     if (p->n_batch < 1 || p->n_batch > THEMIS_MAX_BATCH) return THEMIS_ERR_BATCH;
     for (int j = 0; j < p->n_batch; ++j) {
         if (p->batch_sizes[j] < 1 || p->batch_sizes[j] > THEMIS_MAX_BATCH_SIZE)

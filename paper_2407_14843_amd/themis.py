@@ -38,7 +38,8 @@ class ThemisProblem(ctypes.Structure):
         ("n_batch", ctypes.c_int32), ("batch_sizes", ctypes.c_int32 * MAX_BATCH),
         ("r_max", ctypes.c_int32), ("tick_us", ctypes.c_int32),
         ("slo_max_us", ctypes.c_int32), ("coef_shared", ctypes.c_int32),
-        ("reserved", ctypes.c_int32 * 4),
+        ("queue_model", ctypes.c_int32), ("profile_form", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 2),
     ]
 
 
@@ -94,8 +95,12 @@ def lib():
     return _lib
 
 
+QUEUE_PER_REPLICA, QUEUE_SHARED, QUEUE_WORST_CASE = 0, 1, 2
+PROFILE_5, PROFILE_EQ1 = 0, 1
+
+
 def make_problem(n_inst, n_stage, c_max, batch_sizes, r_max, tick_us, slo_max_us,
-                 coef_shared=False) -> ThemisProblem:
+                 coef_shared=False, queue_model=0, profile_form=0) -> ThemisProblem:
     p = ThemisProblem()
     p.n_inst, p.n_stage, p.c_max = int(n_inst), int(n_stage), int(c_max)
     p.n_batch = len(batch_sizes)
@@ -103,6 +108,7 @@ def make_problem(n_inst, n_stage, c_max, batch_sizes, r_max, tick_us, slo_max_us
         p.batch_sizes[j] = int(b)
     p.r_max, p.tick_us, p.slo_max_us = int(r_max), int(tick_us), int(slo_max_us)
     p.coef_shared = int(bool(coef_shared))
+    p.queue_model, p.profile_form = int(queue_model), int(profile_form)
     return p
 
 
@@ -244,7 +250,7 @@ def themis_probe_valu(op, iters, blocks, sink, stream=None):
 def problem_of(w) -> ThemisProblem:
     """Problem description of a workloads.Workload."""
     return make_problem(w.n_inst, w.n_stage, w.c_max, w.batch_sizes, w.r_max, w.tick_us,
-                        w.slo_max_us, w.coef_shared)
+                        w.slo_max_us, w.coef_shared, w.queue_model, w.profile_form)
 
 
 class DeviceBatch:
