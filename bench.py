@@ -36,7 +36,7 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def run_workload(themis, wl, idx, steps, warmup, n_inst=None):
+def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0):
     """Time `steps` solves of workload idx; returns a dict of measurements."""
     import numpy as np
     import torch
@@ -57,7 +57,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None):
             # joint pass this same library just produced
             st, _, _, cfg = first_results
             wp = w.with_r_fixed(wl.replicas_carried_forward(st, cfg))
-        b = themis.DeviceBatch(wp, "cuda:0")
+        b = themis.DeviceBatch(wp, "cuda:0", prune=prune)
         p = b.p
         stream = torch.cuda.current_stream()
 
@@ -259,6 +259,12 @@ def main():
             "traffic": None,
         },
     }
+    # the same solve with dominated candidates dropped before the recurrence: same
+    # answers, a fraction of the relaxations; reported beside the dense figures
+    pr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=1)
+    line["pruned"] = {k: pr[k] for k in (
+        "solves_per_s", "dp_cells_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
+    line["pruned"]["relaxations_dense"] = m["relaxations_executed"]
     if a.others:
         others = {}
         for idx in range(5):
@@ -272,6 +278,9 @@ def main():
             others[o["workload"]]["minplus_lds_frac"] = o["minplus_lds_bytes"] / k2s / 1e9 / LDS_PEAK_GBS
             others[o["workload"]]["minplus_valu_frac"] = (
                 o["relaxations_executed"] / k2s / 1e9 / VALU_PEAK_GOPS)
+            op = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=1)
+            others[o["workload"]]["pruned"] = {k: op[k] for k in (
+                "solves_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
         line["other_workloads"] = others
     if not a.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl, a.workload, 4096)

@@ -88,6 +88,14 @@ extern "C" {
 #define THEMIS_PROFILE_5 0   /* coefficients (a,k,q,p,o)                        */
 #define THEMIS_PROFILE_EQ1 1 /* coefficients (a,k,q,p,o,d)                      */
 
+/* themis_problem_t.prune */
+#define THEMIS_PRUNE_NONE 0      /* every feasible candidate enters the recurrence */
+#define THEMIS_PRUNE_DOMINATED 1 /* candidates that another candidate of the same
+                                    model beats or ties on both latency and cost
+                                    (ties: smaller index wins) are dropped first.
+                                    Results are identical: such a candidate is
+                                    in no instance's smallest assignment.       */
+
 /* per-instance status written to d_status */
 #define THEMIS_SOLVED 0
 #define THEMIS_INFEASIBLE 1 /* no assignment meets both constraints            */
@@ -117,7 +125,8 @@ typedef struct themis_problem {
                            THEMIS_PROFILE_EQ1)                                  */
     int32_t queue_model;/* THEMIS_QUEUE_*                                      */
     int32_t profile_form;/* THEMIS_PROFILE_*                                   */
-    int32_t reserved[2];/* must be zero                                        */
+    int32_t prune;      /* THEMIS_PRUNE_*                                      */
+    int32_t reserved[1];/* must be zero                                        */
 } themis_problem_t;
 
 /* Library version, major*100 + minor. */

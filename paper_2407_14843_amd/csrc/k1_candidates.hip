@@ -112,6 +112,16 @@ __device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& 
     return Eval{ok ? (int32_t)lt : -1, ok ? (int32_t)n : 0};
 }
 
+// Orders the LDS traffic of one wavefront: what its lanes wrote before is
+// visible to all its lanes after (a wavefront's LDS operations complete in
+// order; this only keeps the compiler from moving them across).
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 __device__ __forceinline__ int in_range(int32_t v, int32_t lo, int32_t hi)
 {
     return (int)(v >= lo) & (int)(v <= hi);
@@ -180,12 +190,28 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 // The order inside a bucket is whatever the LDS atomics yield; nothing
 // downstream depends on it.
 //
+// PRUNE: between the passes, candidates that cannot be part of the answer are
+// turned into infeasible ones, so that the min-plus stage never sees them.  A
+// candidate is dropped when another one of the same row is at least as fast and
+// cheaper, or as cheap and faster, or equal in both with a smaller index: swapping
+// it for that other one in any assignment gives a smaller (cost, ticks, indices)
+// key, so it is in no instance's answer, and since the rows of the recurrence
+// never increase with the budget it attains no minimum that its replacement does
+// not attain as well.  Per row one wavefront fills a table min over candidates of
+// (lt, index) by cost (costs binned by 2^prune_sh when r_max * c_max exceeds the
+// table; then only strictly cheaper bins are compared, which drops fewer
+// candidates but never a needed one), takes its running minimum, and looks every
+// candidate up in it.
+//
 // c_fixed (may be null; then c_all, 0 = free): cores given per row; the model is
 // evaluated for those cores only and every other candidate of the row is marked infeasible.
 // sparse: rows of instances that failed the input check are left untouched.
 constexpr uint32_t STAGE_NONE = 0xFFFFu;  // lt field of an infeasible candidate in LDS
 
-template <int QUEUE>
+constexpr uint32_t PRUNE_TAB_WORDS = 2560;  // per wavefront: sentinel + cost bins
+constexpr uint32_t PRUNE_KEY_SHIFT = 13;    // key = lt << 13 | index (index < 8192)
+
+template <int QUEUE, bool PRUNE>
 __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
@@ -193,7 +219,8 @@ __global__ __launch_bounds__(256) void k1_candidates(
     StepEntry* __restrict__ step_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
     uint32_t S, uint32_t K, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick,
     double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs, int copies_mask,
-    int merge_to, int sparse, uint32_t c_all, uint32_t cs)
+    int merge_to, int sparse, uint32_t c_all, uint32_t cs, uint32_t prune_sh,
+    uint32_t prune_bins)
 {
     extern __shared__ uint32_t smem[];
     // per local row: hist[nb + 1], cursor[nb + 1], staging[Kp]
@@ -254,7 +281,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
                 const uint32_t w0 = none ? STAGE_NONE
                                          : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
                 stage[(c - 1) * nbat + j] = w0;
-                atomicAdd(&hist[none ? nb : (uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
+                if (!PRUNE) atomicAdd(&hist[none ? nb : (uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
             }
         } else {
             for (uint32_t c = 1; c <= c_max; ++c) stage[(c - 1) * nbat + j] = STAGE_NONE;
@@ -276,6 +303,57 @@ __global__ __launch_bounds__(256) void k1_candidates(
             if (grow >= rows) break;
             if (sparse && tmeta[grow / S] < 0) continue;
             uint32_t* const hh = smem + r * row_words;
+            if (PRUNE && tmeta[grow / S] >= 0) {
+                // tab[0] = "nothing cheaper"; tab[1 + bin] = least (lt, index) of the bin,
+                // then of all bins up to it
+                uint32_t* const tab = smem + RPW * row_words + wv * PRUNE_TAB_WORDS;
+                const uint32_t* const stg = hh + 2 * HB;
+                for (uint32_t x = lane; x <= prune_bins; x += 64u) tab[x] = 0xFFFFFFFFu;
+                wave_lds_fence();
+                for (uint32_t kk = lane; kk < K; kk += 64u) {
+                    const uint32_t w0 = stg[kk], lt = w0 & 0xFFFFu;
+                    if (lt != STAGE_NONE)
+                        atomicMin(&tab[1u + ((w0 >> 16) >> prune_sh)], (lt << PRUNE_KEY_SHIFT) | kk);
+                }
+                wave_lds_fence();
+                {
+                    // running minimum over the bins: each lane owns a stretch
+                    const uint32_t per = (prune_bins + 63u) / 64u;
+                    const uint32_t lo = 1u + lane * per;
+                    const uint32_t hi = lo + per < prune_bins + 1u ? lo + per : prune_bins + 1u;
+                    uint32_t m = 0xFFFFFFFFu;
+                    for (uint32_t x = lo; x < hi; ++x) m = tab[x] < m ? tab[x] : m;
+                    uint32_t before = m;  // becomes the minimum of all earlier stretches
+#pragma unroll
+                    for (int d = 1; d < 64; d <<= 1) {
+                        const uint32_t t = __shfl_up(before, d, 64);
+                        if ((int)lane >= d) before = t < before ? t : before;
+                    }
+                    before = __shfl_up(before, 1, 64);
+                    if (lane == 0) before = 0xFFFFFFFFu;
+                    for (uint32_t x = lo; x < hi; ++x) {
+                        const uint32_t v0 = tab[x];
+                        before = v0 < before ? v0 : before;
+                        tab[x] = before;
+                    }
+                }
+                wave_lds_fence();
+                for (uint32_t kk = lane; kk < K; kk += 64u) {
+                    const uint32_t w0 = stg[kk], lt = w0 & 0xFFFFu;
+                    bool keep = lt != STAGE_NONE;
+                    if (keep) {
+                        const uint32_t bin = (w0 >> 16) >> prune_sh;
+                        // nothing strictly cheaper is as fast ...
+                        keep = (tab[bin] >> PRUNE_KEY_SHIFT) > lt;
+                        // ... and, where a bin is one cost, nothing as cheap is faster or
+                        // equally fast with a smaller index
+                        if (prune_sh == 0) keep = keep && tab[1u + bin] == ((lt << PRUNE_KEY_SHIFT) | kk);
+                    }
+                    if (!keep) hh[2 * HB + kk] = STAGE_NONE;
+                    atomicAdd(&hh[keep ? lt >> BUCKET_SHIFT : nb], 1u);
+                }
+                wave_lds_fence();
+            }
             const uint32_t v = lane < nb ? hh[lane] : 0u;
             uint32_t incl = v;
 #pragma unroll
@@ -407,12 +485,21 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     // rows per workgroup: as many as 256 threads cover, within 52 KB of LDS
     const uint32_t row_bytes = (uint32_t)(2 * (L.nb + 1) + L.Kp) * sizeof(uint32_t);
     uint32_t RPW = 256u / (uint32_t)p.n_batch;
-    while (RPW > 1 && RPW * row_bytes > 52u * 1024u) --RPW;
+    const bool prune = p.prune != THEMIS_PRUNE_NONE;
+    // pruning adds one cost table per wavefront; keep two workgroups per compute unit
+    const uint32_t tab_bytes = prune ? 4u * PRUNE_TAB_WORDS * (uint32_t)sizeof(uint32_t) : 0u;
+    const uint32_t stage_budget = prune ? 38u * 1024u : 52u * 1024u;
+    while (RPW > 1 && RPW * row_bytes > stage_budget) --RPW;
     const uint32_t rows = (uint32_t)L.N * L.S;
-    const size_t lds = (size_t)RPW * row_bytes;
+    const size_t lds = (size_t)RPW * row_bytes + tab_bytes;
+    // cost bins: one per cost when r_max * c_max fits the table, else 2^prune_sh costs each
+    uint32_t prune_sh = 0;
+    const uint32_t cost_top = (uint32_t)p.r_max * (uint32_t)p.c_max;
+    while ((cost_top >> prune_sh) + 2u > PRUNE_TAB_WORDS) ++prune_sh;
+    const uint32_t prune_bins = (cost_top >> prune_sh) + 1u;
     auto launch = [&](auto kernel) -> hipError_t {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         if (err != hipSuccess) return err;
         hipLaunchKernelGGL(kernel, dim3((rows + RPW - 1) / RPW), dim3(256), lds, st, d_coef,
                            d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, (const int32_t*)tmeta,
@@ -421,13 +508,19 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                            (uint32_t)p.r_max, (uint32_t)p.tick_us,
                            (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
                            (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
-                           opts.sparse, (uint32_t)opts.c_all, cs);
+                           opts.sparse, (uint32_t)opts.c_all, cs, prune_sh, prune_bins);
         return hipGetLastError();
     };
-    switch (p.queue_model) {
-    case THEMIS_QUEUE_SHARED: return launch(&k1_candidates<THEMIS_QUEUE_SHARED>);
-    case THEMIS_QUEUE_WORST_CASE: return launch(&k1_candidates<THEMIS_QUEUE_WORST_CASE>);
-    default: return launch(&k1_candidates<THEMIS_QUEUE_PER_REPLICA>);
+    switch (p.queue_model * 2 + (prune ? 1 : 0)) {
+    case THEMIS_QUEUE_SHARED * 2: return launch(&k1_candidates<THEMIS_QUEUE_SHARED, false>);
+    case THEMIS_QUEUE_SHARED * 2 + 1: return launch(&k1_candidates<THEMIS_QUEUE_SHARED, true>);
+    case THEMIS_QUEUE_WORST_CASE * 2:
+        return launch(&k1_candidates<THEMIS_QUEUE_WORST_CASE, false>);
+    case THEMIS_QUEUE_WORST_CASE * 2 + 1:
+        return launch(&k1_candidates<THEMIS_QUEUE_WORST_CASE, true>);
+    case THEMIS_QUEUE_PER_REPLICA * 2 + 1:
+        return launch(&k1_candidates<THEMIS_QUEUE_PER_REPLICA, true>);
+    default: return launch(&k1_candidates<THEMIS_QUEUE_PER_REPLICA, false>);
     }
 }
 

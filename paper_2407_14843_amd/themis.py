@@ -39,7 +39,7 @@ class ThemisProblem(ctypes.Structure):
         ("r_max", ctypes.c_int32), ("tick_us", ctypes.c_int32),
         ("slo_max_us", ctypes.c_int32), ("coef_shared", ctypes.c_int32),
         ("queue_model", ctypes.c_int32), ("profile_form", ctypes.c_int32),
-        ("reserved", ctypes.c_int32 * 2),
+        ("prune", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1),
     ]
 
 
@@ -100,7 +100,7 @@ PROFILE_5, PROFILE_EQ1 = 0, 1
 
 
 def make_problem(n_inst, n_stage, c_max, batch_sizes, r_max, tick_us, slo_max_us,
-                 coef_shared=False, queue_model=0, profile_form=0) -> ThemisProblem:
+                 coef_shared=False, queue_model=0, profile_form=0, prune=0) -> ThemisProblem:
     p = ThemisProblem()
     p.n_inst, p.n_stage, p.c_max = int(n_inst), int(n_stage), int(c_max)
     p.n_batch = len(batch_sizes)
@@ -108,7 +108,7 @@ def make_problem(n_inst, n_stage, c_max, batch_sizes, r_max, tick_us, slo_max_us
         p.batch_sizes[j] = int(b)
     p.r_max, p.tick_us, p.slo_max_us = int(r_max), int(tick_us), int(slo_max_us)
     p.coef_shared = int(bool(coef_shared))
-    p.queue_model, p.profile_form = int(queue_model), int(profile_form)
+    p.queue_model, p.profile_form, p.prune = int(queue_model), int(profile_form), int(prune)
     return p
 
 
@@ -247,18 +247,18 @@ def themis_probe_valu(op, iters, blocks, sink, stream=None):
 
 
 # ---------------------------------------------------------------- conveniences
-def problem_of(w) -> ThemisProblem:
+def problem_of(w, prune=0) -> ThemisProblem:
     """Problem description of a workloads.Workload."""
     return make_problem(w.n_inst, w.n_stage, w.c_max, w.batch_sizes, w.r_max, w.tick_us,
-                        w.slo_max_us, w.coef_shared, w.queue_model, w.profile_form)
+                        w.slo_max_us, w.coef_shared, w.queue_model, w.profile_form, prune)
 
 
 class DeviceBatch:
     """A workload's arrays resident in HBM plus output and workspace buffers."""
 
-    def __init__(self, w, device="cuda:0"):
+    def __init__(self, w, device="cuda:0", prune=0):
         self.w = w
-        self.p = problem_of(w)
+        self.p = problem_of(w, prune)
         self.device = device
         to = lambda a: None if a is None else torch.from_numpy(a).to(device).contiguous()
         self.coef, self.lam, self.slo_us, self.r_fixed = (
