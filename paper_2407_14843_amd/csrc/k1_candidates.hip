@@ -129,9 +129,13 @@ __device__ __forceinline__ int in_range(int32_t v, int32_t lo, int32_t hi)
 
 // Input check and work classification, one thread per instance:
 // tmeta[i] = budget T in ticks, or -1 when any input of the instance is out of
-// range; valid instances are appended to the list of their work class.  Lanes
-// of a wavefront that fall into the same class share one atomic.
-__global__ __launch_bounds__(256) void k1_validate(
+// range; valid instances are appended to the list of their work class.  The
+// lanes of a wavefront that fall into the same class share one LDS atomic, and
+// a workgroup reserves its stretch of every class list with one global atomic
+// per class: returning atomics on one address cost tens of nanoseconds each.
+constexpr uint32_t VALIDATE_THREADS = 1024;
+
+__global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta,
@@ -139,7 +143,12 @@ __global__ __launch_bounds__(256) void k1_validate(
     int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, int merge_to,
     uint32_t cs)
 {
-    uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    __shared__ int32_t in_block[N_CLS];   // instances of the class in this workgroup
+    __shared__ int32_t list_base[N_CLS];  // where the workgroup's stretch of the list starts
+    if (threadIdx.x < N_CLS) in_block[threadIdx.x] = 0;
+    __syncthreads();
+
+    uint32_t i = blockIdx.x * VALIDATE_THREADS + threadIdx.x;
     int cls = -1;
     if (i < N) {
         int32_t lam = lambda[i], slo = slo_us[i];
@@ -157,19 +166,29 @@ __global__ __launch_bounds__(256) void k1_validate(
         }
         int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
         tmeta[i] = T;
-        if (ok) cls = effective_class(T, merge_to);
+        // listed under its own class even when a launch of a higher class will
+        // serve it: that launch walks the lists from the longest rows down
+        if (ok) cls = class_of_budget(T);
     }
+    // place inside the workgroup's stretch: wavefront offset + rank among the lanes
     const unsigned lane = threadIdx.x & 63u;
+    int within = 0;
     for (int c = 0; c < N_CLS; ++c) {
         const unsigned long long m = __ballot(cls == c);
         if (m == 0ull) continue;
         int base = 0;
         const int leader = __builtin_ctzll(m);
-        if ((int)lane == leader) base = atomicAdd(&ctrl[c], __builtin_popcountll(m));
+        if ((int)lane == leader) base = atomicAdd(&in_block[c], __builtin_popcountll(m));
         base = __shfl(base, leader, 64);
-        if (cls == c)
-            order[(size_t)c * N + base + __builtin_popcountll(m & ((1ull << lane) - 1ull))] = (int32_t)i;
+        if (cls == c) within = base + __builtin_popcountll(m & ((1ull << lane) - 1ull));
     }
+    __syncthreads();
+    if (threadIdx.x < N_CLS) {
+        const int32_t n = in_block[threadIdx.x];
+        list_base[threadIdx.x] = n ? atomicAdd(&ctrl[threadIdx.x], n) : 0;
+    }
+    __syncthreads();
+    if (cls >= 0) order[(size_t)cls * N + list_base[cls] + within] = (int32_t)i;
 }
 
 // ctrl[0..N_CLS) = instances per class, ctrl[N_CLS..2 N_CLS) = queue cursors
@@ -474,7 +493,8 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     int32_t* ctrl = (int32_t*)(ws + L.ctrl_off);
     const MinplusPlan plan = make_plan(L);
     hipLaunchKernelGGL(k1_reset_ctrl, dim3(1), dim3(64), 0, st, ctrl);
-    hipLaunchKernelGGL(k1_validate, dim3((L.N + 255) / 256), dim3(256), 0, st, d_coef,
+    hipLaunchKernelGGL(k1_validate, dim3((L.N + VALIDATE_THREADS - 1) / VALIDATE_THREADS),
+                       dim3(VALIDATE_THREADS), 0, st, d_coef,
                        d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, tmeta,
                        (int32_t*)(ws + L.order_off), ctrl, (uint32_t)L.N, (uint32_t)L.S, p.r_max,
                        p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, plan.merge_to,

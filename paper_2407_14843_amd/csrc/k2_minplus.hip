@@ -89,6 +89,24 @@ __device__ __forceinline__ int next_instance(volatile uint32_t* slot, int32_t* c
     return as_constant(order)[idx];
 }
 
+// The same for a launch that serves the classes cls, cls - 1, ..., low: one
+// cursor runs through their lists in that order, so the longest rows start
+// first and the launch ends on the shortest ones.
+__device__ __forceinline__ int next_instance_of(volatile uint32_t* slot, int32_t* ctrl,
+                                                const int32_t* order, int N, int cls, int low)
+{
+    if (threadIdx.x == 0) *slot = (uint32_t)atomicAdd(ctrl + N_CLS + cls, 1);
+    __syncthreads();
+    int idx = __builtin_amdgcn_readfirstlane((int)*slot);
+    __syncthreads();  // slot may be rewritten by the next call
+    for (int c = cls; c >= low; --c) {
+        const int n = as_constant(ctrl)[c];
+        if (idx < n) return as_constant(order)[(size_t)c * N + idx];
+        idx -= n;
+    }
+    return -1;
+}
+
 // Entries of the row that can reach a position whose last cell is `last_cell`.
 __device__ __forceinline__ int prefix_count(const AS_CONST uint16_t* bc, int last_cell)
 {
@@ -322,7 +340,7 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
     int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int N, int S, int Kp, int nbs,
-    int row_stride, int cls, int cand_buf)
+    int row_stride, int cls, int low_cls, int cand_buf)
 {
     using G = Geo<COPIES>;
     extern __shared__ uint32_t lds[];
@@ -338,11 +356,9 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int count = as_constant(ctrl)[cls];
-    const int32_t* const my_order = order + (size_t)cls * N;
 
     for (;;) {
-        const int i = next_instance(slot, ctrl + N_CLS + cls, count, my_order);
+        const int i = next_instance_of(slot, ctrl, order, N, cls, low_cls);
         if (i < 0) break;
         const int T = as_constant(tmeta)[i];
         const int npos = (T + POSC) / POSC;  // positions that hold cells 0..T
@@ -577,7 +593,7 @@ inline int wide_groups_per_cu(int copies, int waves, int cand_buf)
 }
 
 template <int COPIES>
-hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int cus)
+hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int low, int cus)
 {
     const int nwc = CLS_WAVES[c];
     const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
@@ -592,7 +608,7 @@ hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, 
                        (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
                        (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
                        (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off), L_.N, L_.S,
-                       L_.Kp, L_.nbs, L_.row_stride, c, cand_buf);
+                       L_.Kp, L_.nbs, L_.row_stride, c, low, cand_buf);
     return hipGetLastError();
 }
 
@@ -636,8 +652,10 @@ hipError_t launch_minplus(const themis_problem_t&, const Layout& L_, char* ws, h
         if (e != hipSuccess) return e;
     }
     for (int c = pl.top_wide; c >= pl.merge_to; --c) {
-        e = class_copies(c, pl.copies_mask) == 2 ? launch_wide_class<2>(L_, ws, st, c, pl.cus)
-                                                 : launch_wide_class<4>(L_, ws, st, c, pl.cus);
+        // a merged launch also serves every class below it
+        const int low = c == pl.merge_to ? 0 : c;
+        e = class_copies(c, pl.copies_mask) == 2 ? launch_wide_class<2>(L_, ws, st, c, low, pl.cus)
+                                                 : launch_wide_class<4>(L_, ws, st, c, low, pl.cus);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
