@@ -165,7 +165,11 @@ def lds_probe():
                                        "bytes_per_clk_per_cu": gbs / N_CU / CLOCK_GHZ}
     valu = {}
     names = ["v_pk_add_u16", "v_pk_min_u16", "v_add_u32", "v_min_u32",
-             "v_pk_add_u16/v_pk_min_u16 alternating", "v_pk_add_u16 (sgpr operand)"]
+             "v_pk_add_u16/v_pk_min_u16 alternating", "v_pk_add_u16 (sgpr operand)",
+             "v_fma_f64", "v_mul_f64", "v_add_f64", "v_floor_f64", "v_rcp_f64", "v_cvt_f64_u32",
+             "v_cvt_u32_f64", "v_mul_lo_u32", "v_cmp_ge_f64", "v_cndmask_b32", "v_mul_u32_u24",
+             "v_cndmask_b32_e64 (sgpr-pair mask)", "v_max_f64", "v_add_f64 clamp",
+             "v_cmp_ge_f64_e64 (sgpr-pair result)"]
     vblocks, viters = N_CU * 8 * 4, 4000
     for op, name in enumerate(names):
         themis.themis_probe_valu(op, 10, vblocks, sink, stream)

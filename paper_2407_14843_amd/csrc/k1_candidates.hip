@@ -58,6 +58,7 @@ struct RowHdr {
     double d;            // Eq. 1's delta (0 when the profile has five coefficients)
     double p;            // core cap
     double lam, rlam;    // arrival rate and recip_below() of it
+    double lt_den, rlt_den;  // lambda * tick and recip_below() of it
     double slo, T;       // SLO in microseconds, budget in ticks
     double n_given;      // replicas (vertical) or 0 (joint: derive)
 };
@@ -89,25 +90,29 @@ __device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& 
     bool ok = proc <= h.slo;
     const double lp = h.lam * proc;  // < 2^51
     const bool derive = h.n_given <= 0.0;
-    double n = ceil_div_d(lp, bh.M, bh.rM);  // least n with lambda <= n * b / proc
-    n = n < 1.0 ? 1.0 : n;
+    // least n with lambda <= n * b / proc; at least 1 since lambda * proc >= 1
+    double n = ceil_div_d(lp, bh.M, bh.rM);
     n = derive ? n : h.n_given;
     // joint: no more than r_max replicas; vertical: the given ones must carry lambda
     ok = ok && (derive ? lp <= r_max * bh.M : lp <= n * bh.M);
     // batch-fill wait: per replica (each sees lambda / n) or Eq. 4's shared queue
     const double qn = QUEUE == THEMIS_QUEUE_PER_REPLICA ? bh.w * n : bh.w;  // < 2^45
     ok = ok && qn <= (h.slo - proc) * h.lam;  // proc + queue <= SLO
-    double queue = ceil_div_d(qn, h.lam, h.rlam);
+    double lt;
     if (QUEUE == THEMIS_QUEUE_WORST_CASE) {
+        double queue = ceil_div_d(qn, h.lam, h.rlam);
         // Eq. 3: all n instances busy.  floor(x / lambda) = ceil((x + 1) / lambda) - 1;
         // x = (n b + 1) 1e6 < 2^46
         const double x = __builtin_fma(n, bh.M, 1.0e6);
         const double busy = proc - (ceil_div_d(x + 1.0, h.lam, h.rlam) - 1.0);
         queue = busy > queue ? busy : queue;
         ok = ok && proc + queue <= h.slo;
+        lt = ceil_div_d(proc + queue, tick, rtick);
+    } else {
+        // ceil((proc + ceil(qn / lambda)) / tick) = ceil((proc lambda + qn) / (lambda tick)):
+        // one division; numerator <= SLO * lambda < 2^51 for a surviving candidate
+        lt = ceil_div_d(__builtin_fma(proc, h.lam, qn), h.lt_den, h.rlt_den);
     }
-    const double lat = proc + queue;
-    const double lt = ceil_div_d(lat, tick, rtick);
     ok = ok && lt <= h.T;
     return Eval{ok ? (int32_t)lt : -1, ok ? (int32_t)n : 0};
 }
@@ -227,7 +232,7 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 // sparse: rows of instances that failed the input check are left untouched.
 constexpr uint32_t STAGE_NONE = 0xFFFFu;  // lt field of an infeasible candidate in LDS
 
-constexpr uint32_t PRUNE_TAB_WORDS = 2560;  // per wavefront: sentinel + cost bins
+constexpr uint32_t PRUNE_TAB_WORDS = 2560;  // per wavefront, at most: sentinel + cost bins
 constexpr uint32_t PRUNE_KEY_SHIFT = 13;    // key = lt << 13 | index (index < 8192)
 
 template <int QUEUE, bool PRUNE>
@@ -239,7 +244,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     uint32_t S, uint32_t K, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick,
     double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs, int copies_mask,
     int merge_to, int sparse, uint32_t c_all, uint32_t cs, uint32_t prune_sh,
-    uint32_t prune_bins)
+    uint32_t prune_bins, uint32_t split)
 {
     extern __shared__ uint32_t smem[];
     // per local row: hist[nb + 1], cursor[nb + 1], staging[Kp]
@@ -247,7 +252,12 @@ __global__ __launch_bounds__(256) void k1_candidates(
     const uint32_t row_words = 2 * HB + Kp;
     const uint32_t nbat = (uint32_t)bl.n;
 
-    const uint32_t rl = threadIdx.x / nbat, j = threadIdx.x - rl * nbat;
+    // `split` threads share the cores of one (row, batch size): thread `part` takes
+    // c = part + 1, part + 1 + split, ...
+    const uint32_t tpr = nbat * split;
+    const uint32_t rl = threadIdx.x / tpr, rem = threadIdx.x - rl * tpr;
+    const uint32_t part = rem / nbat, j = rem - part * nbat;
+    const bool first = rem == 0;  // the row's thread for one-off work
     const uint32_t row = blockIdx.x * RPW + rl;
     bool live = rl < RPW && row < rows;
     uint32_t* const hist = smem + rl * row_words;
@@ -277,6 +287,8 @@ __global__ __launch_bounds__(256) void k1_candidates(
             h.d = cs == 6 ? (double)cf[5] : 0.0;
             h.lam = (double)lambda[i];
             h.rlam = recip_below(h.lam);
+            h.lt_den = h.lam * (double)tick;
+            h.rlt_den = recip_below(h.lt_den);
             h.slo = (double)slo_us[i];
             h.T = (double)T;
             h.n_given = r_fixed ? (double)r_fixed[(size_t)i * S + s] : 0.0;
@@ -293,9 +305,13 @@ __global__ __launch_bounds__(256) void k1_candidates(
                 const uint32_t d = only < pcap ? only : pcap;
                 ev = eval_candidate<QUEUE>(h, bh, (double)d, (double)r_max, (double)tick, rtick);
             }
-            for (uint32_t c = 1; c <= c_max; ++c) {
-                if (!only && c <= pcap)
-                    ev = eval_candidate<QUEUE>(h, bh, (double)c, (double)r_max, (double)tick, rtick);
+            bool capped = false;  // ev already is the evaluation at the core cap
+            for (uint32_t c = part + 1; c <= c_max; c += split) {
+                if (!only && !capped) {
+                    const uint32_t d = c < pcap ? c : pcap;
+                    ev = eval_candidate<QUEUE>(h, bh, (double)d, (double)r_max, (double)tick, rtick);
+                    capped = c >= pcap;
+                }
                 const bool none = ev.lt < 0 || (only && c != only);
                 const uint32_t w0 = none ? STAGE_NONE
                                          : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
@@ -303,11 +319,11 @@ __global__ __launch_bounds__(256) void k1_candidates(
                 if (!PRUNE) atomicAdd(&hist[none ? nb : (uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
             }
         } else {
-            for (uint32_t c = 1; c <= c_max; ++c) stage[(c - 1) * nbat + j] = STAGE_NONE;
-            if (j == 0) hist[nb] = K;
+            for (uint32_t c = part + 1; c <= c_max; c += split) stage[(c - 1) * nbat + j] = STAGE_NONE;
+            if (first) hist[nb] = K;
         }
         // entries that pad the row to a multiple of eight
-        if (j == 0) {
+        if (first) {
             for (uint32_t kk = K; kk < Kp; ++kk) stage[kk] = STAGE_NONE;
             atomicAdd(&hist[nb], Kp - K);
         }
@@ -325,7 +341,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
             if (PRUNE && tmeta[grow / S] >= 0) {
                 // tab[0] = "nothing cheaper"; tab[1 + bin] = least (lt, index) of the bin,
                 // then of all bins up to it
-                uint32_t* const tab = smem + RPW * row_words + wv * PRUNE_TAB_WORDS;
+                uint32_t* const tab = smem + RPW * row_words + wv * ((prune_bins + 4u) & ~3u);
                 const uint32_t* const stg = hh + 2 * HB;
                 for (uint32_t x = lane; x <= prune_bins; x += 64u) tab[x] = 0xFFFFFFFFu;
                 wave_lds_fence();
@@ -418,8 +434,8 @@ __global__ __launch_bounds__(256) void k1_candidates(
             se.ck = (none ? 0u : w0 >> 16) | (kk << 16);
             out[slot] = se;
         };
-        for (uint32_t c = 1; c <= c_max; ++c) place((c - 1) * nbat + j);
-        if (j == 0)
+        for (uint32_t c = part + 1; c <= c_max; c += split) place((c - 1) * nbat + j);
+        if (first)
             for (uint32_t kk = K; kk < Kp; ++kk) place(kk);  // the padding entries
     }
 }
@@ -502,21 +518,30 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    // rows per workgroup: as many as 256 threads cover, within 52 KB of LDS
-    const uint32_t row_bytes = (uint32_t)(2 * (L.nb + 1) + L.Kp) * sizeof(uint32_t);
-    uint32_t RPW = 256u / (uint32_t)p.n_batch;
     const bool prune = p.prune != THEMIS_PRUNE_NONE;
-    // pruning adds one cost table per wavefront; keep two workgroups per compute unit
-    const uint32_t tab_bytes = prune ? 4u * PRUNE_TAB_WORDS * (uint32_t)sizeof(uint32_t) : 0u;
-    const uint32_t stage_budget = prune ? 38u * 1024u : 52u * 1024u;
-    while (RPW > 1 && RPW * row_bytes > stage_budget) --RPW;
-    const uint32_t rows = (uint32_t)L.N * L.S;
-    const size_t lds = (size_t)RPW * row_bytes + tab_bytes;
-    // cost bins: one per cost when r_max * c_max fits the table, else 2^prune_sh costs each
+    // cost bins of the pruning table: one per cost when r_max * c_max fits, else
+    // 2^prune_sh costs each; one table (sentinel + bins) per wavefront
     uint32_t prune_sh = 0;
     const uint32_t cost_top = (uint32_t)p.r_max * (uint32_t)p.c_max;
     while ((cost_top >> prune_sh) + 2u > PRUNE_TAB_WORDS) ++prune_sh;
     const uint32_t prune_bins = (cost_top >> prune_sh) + 1u;
+    const uint32_t tab_bytes = prune ? 4u * ((prune_bins + 4u) & ~3u) * (uint32_t)sizeof(uint32_t) : 0u;
+
+    // This kernel is bound by latency (dependent double-precision chains, LDS
+    // atomics, the loads at its start), so it needs wavefronts more than it needs
+    // every lane busy.  Where one thread per (row, batch size) would make a
+    // workgroup hold more than 32 KB of LDS, two threads share the cores of a
+    // (row, batch size): half the rows and LDS per workgroup, twice the workgroups
+    // per compute unit, for one extra model evaluation per thread.
+    const uint32_t row_bytes = (uint32_t)(2 * (L.nb + 1) + L.Kp) * sizeof(uint32_t);
+    const uint32_t split =
+        p.c_max >= 8 && 256u / (uint32_t)p.n_batch * row_bytes + tab_bytes > 32u * 1024u ? 2u : 1u;
+    // rows per workgroup: as many as 256 threads cover, within 76 KB of LDS
+    uint32_t RPW = 256u / ((uint32_t)p.n_batch * split);
+    if (RPW == 0) RPW = 1;
+    while (RPW > 1 && RPW * row_bytes + tab_bytes > 76u * 1024u) --RPW;
+    const uint32_t rows = (uint32_t)L.N * L.S;
+    const size_t lds = (size_t)RPW * row_bytes + tab_bytes;
     auto launch = [&](auto kernel) -> hipError_t {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
@@ -528,7 +553,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                            (uint32_t)p.r_max, (uint32_t)p.tick_us,
                            (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
                            (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
-                           opts.sparse, (uint32_t)opts.c_all, cs, prune_sh, prune_bins);
+                           opts.sparse, (uint32_t)opts.c_all, cs, prune_sh, prune_bins, split);
         return hipGetLastError();
     };
     switch (p.queue_model * 2 + (prune ? 1 : 0)) {

@@ -112,6 +112,58 @@ __global__ __launch_bounds__(256) void k_valu_probe(uint32_t* __restrict__ sink,
     if (x == 0x12345678u) sink[0] = x;
 }
 
+// The same for the double-precision and conversion instructions the candidate
+// kernel is made of: 8 independent register pairs per lane, 16 instructions a round.
+template <int OP>
+__global__ __launch_bounds__(256) void k_valu64_probe(uint32_t* __restrict__ sink, int iters,
+                                                      uint32_t seed)
+{
+    double r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = 1.0 + 1e-3 * (double)(seed * (threadIdx.x + 1) + j);
+    const double c = 1.0 + 1e-9 * (double)seed;
+    uint32_t u[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) u[j] = seed + j;
+    unsigned long long mask = 0x5555555555555555ull * seed;  // uniform: lives in an SGPR pair
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if constexpr (OP == 6) asm volatile("v_fma_f64 %0, %0, %1, %1" : "+v"(r[j]) : "v"(c));
+                if constexpr (OP == 7) asm volatile("v_mul_f64 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+                if constexpr (OP == 8) asm volatile("v_add_f64 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+                if constexpr (OP == 9) asm volatile("v_floor_f64 %0, %0" : "+v"(r[j]));
+                if constexpr (OP == 10) asm volatile("v_rcp_f64 %0, %0" : "+v"(r[j]));
+                if constexpr (OP == 11) asm volatile("v_cvt_f64_u32 %0, %1" : "=v"(r[j]) : "v"(u[j]));
+                if constexpr (OP == 12) asm volatile("v_cvt_u32_f64 %0, %1" : "=v"(u[j]) : "v"(r[j]));
+                if constexpr (OP == 13) asm volatile("v_mul_lo_u32 %0, %0, %1" : "+v"(u[j]) : "v"(seed));
+                if constexpr (OP == 14)
+                    asm volatile("v_cmp_ge_f64 vcc, %0, %1" : : "v"(r[j]), "v"(c) : "vcc");
+                if constexpr (OP == 15)
+                    asm volatile("v_cndmask_b32 %0, %0, %1, vcc" : "+v"(u[j]) : "v"(seed) : "vcc");
+                if constexpr (OP == 16) asm volatile("v_mul_u32_u24 %0, %0, %1" : "+v"(u[j]) : "v"(seed));
+                if constexpr (OP == 17)
+                    asm volatile("v_cndmask_b32_e64 %0, %0, %1, %2"
+                                 : "+v"(u[j]) : "v"(seed), "s"(mask));
+                if constexpr (OP == 18) asm volatile("v_max_f64 %0, %0, %1" : "+v"(r[j]) : "v"(c));
+                if constexpr (OP == 19)
+                    asm volatile("v_add_f64 %0, %0, %1 clamp" : "+v"(r[j]) : "v"(c));
+                if constexpr (OP == 20)
+                    asm volatile("v_cmp_ge_f64_e64 %0, %1, %2" : "=s"(mask) : "v"(r[j]), "v"(c));
+            }
+    }
+    double x = 0;
+    uint32_t y = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        x += r[j];
+        y ^= u[j];
+    }
+    if (x == 0.123456 || y == 0x12345678u || mask == 1ull) sink[0] = y;
+}
+
 template <int WIDTH, int MIS>
 hipError_t launch_probe(uint32_t* sink, int iters, int blocks, hipStream_t st)
 {
@@ -156,6 +208,15 @@ hipError_t launch_valu_probe(int op, int iters, int blocks, uint32_t* sink, hipS
     }
     VALU_CASE(0) VALU_CASE(1) VALU_CASE(2) VALU_CASE(3) VALU_CASE(4) VALU_CASE(5)
 #undef VALU_CASE
+#define VALU64_CASE(O) \
+    if (op == O) { \
+        hipLaunchKernelGGL(k_valu64_probe<O>, dim3(blocks), dim3(256), 0, st, sink, iters, 3u); \
+        return hipGetLastError(); \
+    }
+    VALU64_CASE(6) VALU64_CASE(7) VALU64_CASE(8) VALU64_CASE(9) VALU64_CASE(10) VALU64_CASE(11)
+    VALU64_CASE(12) VALU64_CASE(13) VALU64_CASE(14) VALU64_CASE(15) VALU64_CASE(16)
+    VALU64_CASE(17) VALU64_CASE(18) VALU64_CASE(19) VALU64_CASE(20)
+#undef VALU64_CASE
     return hipErrorInvalidValue;
 }
 
