@@ -28,7 +28,7 @@ LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {"w1-joint-4096x5": 117107021, "w3-joint-65536x8": 10943633238}
+K2_HBM_TRAFFIC = {"w1-joint-4096x5": 120163688, "w3-joint-65536x8": 10896121177}
 
 
 def _events(n):
@@ -197,6 +197,11 @@ def main():
     ap.add_argument("--others", action="store_true",
                     help="also time the other numbered workloads (fewer steps)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    ap.add_argument("--prune", action="store_true",
+                    help="time the solve with dominated candidates pruned as the main figure "
+                         "(same answers, fewer relaxations); the default times the dense solve")
+    ap.add_argument("--no-pruned", action="store_true",
+                    help="skip the extra leg that times the pruned solve beside the dense one")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run one 1 GiB device-to-device copy kernel (reference point for "
                          "HBM byte counters)")
@@ -225,7 +230,7 @@ def main():
                           "copy_calib_bytes_written": dst.numel() * 4}), flush=True)
         return
 
-    m = run_workload(themis, wl, a.workload, a.steps, a.warmup)
+    m = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=int(a.prune))
     k2_ms = m["kernel_ms"]["minplus"]
     k2_gbs = m["minplus_lds_bytes"] / (k2_ms * 1e-3) / 1e9
     line = {
@@ -242,7 +247,7 @@ def main():
         "dtype": "u16",
         "data": "synthetic",
         "config": {"workload": m["workload"], "n_inst": m["n_inst"], "n_stage": m["n_stage"],
-                   "candidates_per_stage": m["n_cand"]},
+                   "candidates_per_stage": m["n_cand"], "prune": bool(a.prune)},
         "dp_cells_per_s": m["dp_cells_per_s"],
         "relaxations_per_s": m["relaxations_per_s"],
         "feasible_fraction": m["feasible_fraction"],
@@ -265,16 +270,17 @@ def main():
     }
     # the same solve with dominated candidates dropped before the recurrence: same
     # answers, a fraction of the relaxations; reported beside the dense figures
-    pr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=1)
-    line["pruned"] = {k: pr[k] for k in (
-        "solves_per_s", "dp_cells_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
-    line["pruned"]["relaxations_dense"] = m["relaxations_executed"]
+    if not a.prune and not a.no_pruned:
+        pr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=1)
+        line["pruned"] = {k: pr[k] for k in (
+            "solves_per_s", "dp_cells_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
+        line["pruned"]["relaxations_dense"] = m["relaxations_executed"]
     if a.others:
         others = {}
         for idx in range(5):
             if idx == a.workload:
                 continue
-            o = run_workload(themis, wl, idx, max(3, a.steps // 4), 1)
+            o = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=int(a.prune))
             others[o["workload"]] = {k: o[k] for k in (
                 "solves_per_s", "dp_cells_per_s", "relaxations_per_s", "ms_per_step",
                 "feasible_fraction", "kernel_ms", "candidates_GBs")}
@@ -282,9 +288,10 @@ def main():
             others[o["workload"]]["minplus_lds_frac"] = o["minplus_lds_bytes"] / k2s / 1e9 / LDS_PEAK_GBS
             others[o["workload"]]["minplus_valu_frac"] = (
                 o["relaxations_executed"] / k2s / 1e9 / VALU_PEAK_GOPS)
-            op = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=1)
-            others[o["workload"]]["pruned"] = {k: op[k] for k in (
-                "solves_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
+            if not a.prune and not a.no_pruned:
+                op = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=1)
+                others[o["workload"]]["pruned"] = {k: op[k] for k in (
+                    "solves_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
         line["other_workloads"] = others
     if not a.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl, a.workload, 4096)

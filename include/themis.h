@@ -336,8 +336,13 @@ int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32
  * issues iters * 16 independent vector instructions of one kind and nothing
  * else (op 0 v_pk_add_u16, 1 v_pk_min_u16, 2 v_add_u32, 3 v_min_u32,
  * 4 v_pk_add_u16 / v_pk_min_u16 alternating, 5 v_pk_add_u16 with a scalar
- * operand).  One launch issues blocks * 256 * iters * 16 lane-instructions;
- * time it to obtain the vector-ALU rate the min-plus stage is priced against.
+ * operand; 6..20 the instructions of the candidate stage: v_fma_f64,
+ * v_mul_f64, v_add_f64, v_floor_f64, v_rcp_f64, v_cvt_f64_u32, v_cvt_u32_f64,
+ * v_mul_lo_u32, v_cmp_ge_f64, v_cndmask_b32 on vcc, v_mul_u32_u24,
+ * v_cndmask_b32 on a scalar pair, v_max_f64, v_add_f64 with clamp,
+ * v_cmp_ge_f64 into a scalar pair).  One launch issues
+ * blocks * 256 * iters * 16 lane-instructions; time it to obtain the
+ * vector-ALU rates the stages are priced against.  Unknown op: THEMIS_ERR_SHAPE.
  */
 int themis_probe_valu(int op, int iters, int blocks, uint32_t *d_sink, void *stream);
 
