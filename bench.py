@@ -125,6 +125,77 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0):
     return out
 
 
+def _time_calls(fn, steps, warmup):
+    """Wall time per call of fn() (enqueue only), bracketed by synchronisation."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def next_rows(themis, wl, steps, warmup):
+    """Timings of the entry points beyond the two plain solves, each on a seeded
+    workload of the shapes above: horizontal-only solve and stability test
+    (Algorithm 2, Section 5.1.3) and the paper's printed model forms on workload 1;
+    the vertical solve with Algorithm 1's fallback on workload 2 with its arrival
+    rates multiplied by U{1..5}, so that the running replicas often do not suffice."""
+    import numpy as np
+    out = {}
+    w1 = wl.workload(1)
+    rng = np.random.default_rng(wl.BASE_SEED + 101)
+
+    b = themis.DeviceBatch(w1)
+    ms = _time_calls(lambda: b.solve_horizontal(None), steps, warmup)
+    st = b.results()[0]
+    out["horizontal_one_core"] = {"workload": w1.name, "ms_per_call": ms,
+                                  "solves_per_s": w1.n_inst / (ms * 1e-3),
+                                  "feasible_fraction": float((st == 0).mean())}
+
+    pred = np.clip(w1.lam.astype(np.int64) + rng.integers(-20, 40, w1.n_inst), 1, 1 << 20)
+    ms = _time_calls(lambda: b.check_stability(pred.astype(np.int32)), steps, warmup)
+    import torch
+    torch.cuda.synchronize()
+    out["stability_test"] = {"workload": w1.name, "ms_per_call": ms,
+                             "instances_per_s": w1.n_inst / (ms * 1e-3),
+                             "stable_fraction": float(b.stable.float().mean().item()),
+                             "passes": 2}
+    del b
+
+    d = rng.integers(0, 1500, size=w1.coef.shape[:-1])
+    wv = w1.with_model(1, d)
+    bv = themis.DeviceBatch(wv)
+    ms = _time_calls(lambda: bv.solve(), steps, warmup)
+    out["paper_forms_eq4_eq1"] = {"workload": w1.name, "ms_per_call": ms,
+                                  "solves_per_s": w1.n_inst / (ms * 1e-3),
+                                  "feasible_fraction": float((bv.results()[0] == 0).mean())}
+    del bv
+
+    w2 = wl.workload(2)
+    w2.lam = np.minimum(w2.lam.astype(np.int64) * rng.integers(1, 6, w2.n_inst),
+                        1 << 20).astype(np.int32)
+    lam_max = int(w2.lam.max())
+    for prune in (0, 1):
+        bf = themis.DeviceBatch(w2, prune=prune)
+        ms = _time_calls(lambda: bf.solve_vertical_fallback(lam_max), max(2, steps // 4), 1)
+        r = bf.fallback_results()
+        lv = r["lambda_v"]
+        out["vertical_fallback" + ("_pruned" if prune else "")] = {
+            "workload": w2.name + ", rates x U{1..5}", "ms_per_call": ms,
+            "instances_per_s": w2.n_inst / (ms * 1e-3),
+            "vertical_passes": 2 + max(0, int(np.ceil(np.log2(max(lam_max - 1, 1))))),
+            "absorbed_outright": float((lv == w2.lam).mean()),
+            "split_between_old_and_new_instances": float(((lv > 0) & (lv < w2.lam)).mean()),
+            "remainder_served": float((r["status_h"][(lv > 0) & (lv < w2.lam)] == 0).mean())}
+        del bf
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(wl, idx, max_inst):
     """The CPU checker, as it stands, timed on this machine's host cores."""
     from oracle import oracle
@@ -293,6 +364,7 @@ def main():
                 others[o["workload"]]["pruned"] = {k: op[k] for k in (
                     "solves_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
         line["other_workloads"] = others
+        line["next_rows"] = next_rows(themis, wl, max(3, a.steps // 2), 2)
     if not a.no_cpu:
         line["cpu_baseline"] = cpu_baseline(wl, a.workload, 4096)
     print(json.dumps(line), flush=True)
