@@ -343,19 +343,38 @@ __global__ __launch_bounds__(256) void k1_candidates(
                 // then of all bins up to it
                 uint32_t* const tab = smem + RPW * row_words + wv * ((prune_bins + 4u) & ~3u);
                 const uint32_t* const stg = hh + 2 * HB;
-                for (uint32_t x = lane; x <= prune_bins; x += 64u) tab[x] = 0xFFFFFFFFu;
+                // The fastest candidate (least lt, then least cost) beats everything
+                // that costs more than it does, so only the bins up to its own take
+                // part in the table: usually a small part of the cost range.
+                uint32_t fastest = 0xFFFFFFFFu;  // lt << 16 | cost
+                for (uint32_t kk = lane; kk < K; kk += 64u) {
+                    const uint32_t w0 = stg[kk];
+                    const uint32_t key = (w0 << 16) | (w0 >> 16);
+                    fastest = key < fastest ? key : fastest;
+                }
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) {
+                    const uint32_t o = __shfl_xor(fastest, d, 64);
+                    fastest = o < fastest ? o : fastest;
+                }
+                // no feasible candidate: lt field 0xFFFF, the bins below stay empty
+                const uint32_t top_bin = (fastest & 0xFFFFu) >> prune_sh;
+                const uint32_t bins = (fastest >> 16) == STAGE_NONE ? 1u
+                                      : (top_bin + 1u < prune_bins ? top_bin + 1u : prune_bins);
+                for (uint32_t x = lane; x <= bins; x += 64u) tab[x] = 0xFFFFFFFFu;
                 wave_lds_fence();
                 for (uint32_t kk = lane; kk < K; kk += 64u) {
                     const uint32_t w0 = stg[kk], lt = w0 & 0xFFFFu;
-                    if (lt != STAGE_NONE)
-                        atomicMin(&tab[1u + ((w0 >> 16) >> prune_sh)], (lt << PRUNE_KEY_SHIFT) | kk);
+                    const uint32_t bin = (w0 >> 16) >> prune_sh;
+                    if (lt != STAGE_NONE && bin < bins)
+                        atomicMin(&tab[1u + bin], (lt << PRUNE_KEY_SHIFT) | kk);
                 }
                 wave_lds_fence();
                 {
                     // running minimum over the bins: each lane owns a stretch
-                    const uint32_t per = (prune_bins + 63u) / 64u;
+                    const uint32_t per = (bins + 63u) / 64u;
                     const uint32_t lo = 1u + lane * per;
-                    const uint32_t hi = lo + per < prune_bins + 1u ? lo + per : prune_bins + 1u;
+                    const uint32_t hi = lo + per < bins + 1u ? lo + per : bins + 1u;
                     uint32_t m = 0xFFFFFFFFu;
                     for (uint32_t x = lo; x < hi; ++x) m = tab[x] < m ? tab[x] : m;
                     uint32_t before = m;  // becomes the minimum of all earlier stretches
@@ -375,9 +394,9 @@ __global__ __launch_bounds__(256) void k1_candidates(
                 wave_lds_fence();
                 for (uint32_t kk = lane; kk < K; kk += 64u) {
                     const uint32_t w0 = stg[kk], lt = w0 & 0xFFFFu;
-                    bool keep = lt != STAGE_NONE;
+                    const uint32_t bin = (w0 >> 16) >> prune_sh;
+                    bool keep = lt != STAGE_NONE && bin < bins;
                     if (keep) {
-                        const uint32_t bin = (w0 >> 16) >> prune_sh;
                         // nothing strictly cheaper is as fast ...
                         keep = (tab[bin] >> PRUNE_KEY_SHIFT) > lt;
                         // ... and, where a bin is one cost, nothing as cheap is faster or

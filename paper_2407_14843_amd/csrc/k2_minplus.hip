@@ -76,6 +76,14 @@ __device__ __forceinline__ const AS_CONST T* as_constant(const T* p)
     return (const AS_CONST T*)(uintptr_t)p;
 }
 
+// Workgroup barrier that orders LDS traffic only: global stores in flight are not
+// waited for (the barrier of __syncthreads() waits until they have reached L2,
+// a microsecond or more per model that nothing here depends on).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Pull the next instance of this class, or -1 when the list is exhausted.
 // Every wavefront of the workgroup gets the same answer.
 __device__ __forceinline__ int next_instance(volatile uint32_t* slot, int32_t* cursor, int count,
@@ -229,12 +237,10 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
 
 // Clamp a finished position and store it to the HBM row (cells <= T only).
 template <int COPIES>
-__device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* out, int pos,
-                                                int lane, int T)
+__device__ __forceinline__ void store_position(const uint32_t (&acc)[AD], uint16_t* out, int pos,
+                                               int lane, int T)
 {
     using G = Geo<COPIES>;
-#pragma unroll
-    for (int u = 0; u < AD; ++u) acc[u] = pk_min(acc[u], F_INF2);
 #pragma unroll
     for (int q = 0; q < G::NE; ++q) {
         const int cell = (G::ELT / 2) * (pos * (64 * G::NE) + q * 64 + lane);
@@ -249,6 +255,21 @@ __device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* o
             }
         }
     }
+}
+
+// F_INF + cost back to F_INF
+__device__ __forceinline__ void clamp_position(uint32_t (&acc)[AD])
+{
+#pragma unroll
+    for (int u = 0; u < AD; ++u) acc[u] = pk_min(acc[u], F_INF2);
+}
+
+template <int COPIES>
+__device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* out, int pos,
+                                                int lane, int T)
+{
+    clamp_position(acc);
+    store_position<COPIES>(acc, out, pos, lane, T);
 }
 
 // Write one lane element of the new row into the shifted LDS copies.  `p` is
@@ -277,6 +298,26 @@ __device__ __forceinline__ void publish_pair(char* p, int CSB, uint32_t v)
     *reinterpret_cast<volatile uint32_t*>(p) = v;                              // copy 0
     *reinterpret_cast<volatile uint16_t*>(p + CSB - 2) = (uint16_t)v;          // copy 1
     *reinterpret_cast<volatile uint16_t*>(p + CSB) = (uint16_t)(v >> 16);
+}
+
+// Write a finished position from the registers of the wavefront that computed
+// it into the LDS copies (cells beyond T stay as they are; nothing reads them).
+template <int COPIES>
+__device__ __forceinline__ void publish_position(const uint32_t (&acc)[AD], char* ldsb, int CSB,
+                                                 int pos, int lane, int T)
+{
+    using G = Geo<COPIES>;
+#pragma unroll
+    for (int q = 0; q < G::NE; ++q) {
+        const int el = pos * (64 * G::NE) + q * 64 + lane;
+        if ((G::ELT / 2) * el <= T) {
+            char* const at = ldsb + PADB + G::ELT * el;
+            if constexpr (COPIES == 4)
+                publish_quad(at, CSB, acc[2 * q], acc[2 * q + 1]);
+            else
+                publish_pair(at, CSB, acc[q]);
+        }
+    }
 }
 
 // Entries of one row held in registers on their way from HBM to the LDS
@@ -335,7 +376,16 @@ __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntr
 // back (it is still in L2) and spreads it over the LDS copies.  (Keeping a
 // second set of copies to publish into directly costs more in occupancy than
 // the round trip through L2 does.)
-template <int COPIES>
+//
+// FIXED (used when dominated candidates were pruned, so that a position is a
+// handful of entries and the round trip dominates): every wavefront owns the
+// w-th position from the top and, where the row has more positions than the
+// workgroup has wavefronts, the w-th from the bottom, keeps both results in
+// registers and writes them into the LDS copies itself after the barrier; the
+// HBM row is written for stage 3 only.  It needs more registers than the
+// dealt-out form, which costs the longest classes a resident workgroup when the
+// sweeps are long, hence the two forms.
+template <int COPIES, bool FIXED>
 __global__ __launch_bounds__(1024) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
@@ -399,7 +449,28 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                 prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
             }
 
-            if (n_all <= cand_buf) {
+            const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+            const int nw = (int)blockDim.x >> 6;
+            const int p_hi = npos - 1 - w;
+            const int p_lo = w < npos - nw ? w : -1;
+            uint32_t r_hi[AD], r_lo[AD];
+            const bool in_regs = FIXED && n_all <= cand_buf;
+            if (in_regs) {
+                if (p_hi >= 0) {
+#pragma unroll
+                    for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
+                    sweep<COPIES>(r_hi, ldsb, ent, 0, bc[p_hi + 1], G::lane_byte(p_hi, lane),
+                                  G::park(p_hi));
+                    clamp_position(r_hi);
+                }
+                if (p_lo >= 0) {
+#pragma unroll
+                    for (int u = 0; u < AD; ++u) r_lo[u] = 0xFFFFFFFFu;
+                    sweep<COPIES>(r_lo, ldsb, ent, 0, bc[p_lo + 1], G::lane_byte(p_lo, lane),
+                                  G::park(p_lo));
+                    clamp_position(r_lo);
+                }
+            } else if (n_all <= cand_buf) {
                 // the whole row is in the staging buffer (the usual case)
                 for (;;) {
                     int p = 0;
@@ -416,8 +487,6 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                 // a long row goes through the buffer in parts; every wavefront keeps
                 // its positions (w, w + nw, ...) across the parts, with the partial
                 // minimum parked in the HBM row in between
-                const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-                const int nw = (int)blockDim.x >> 6;
                 for (int p0 = w; p0 < npos; p0 += nw) {
                     uint32_t acc[AD];
 #pragma unroll
@@ -460,6 +529,22 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                         finish_position<COPIES>(acc, out, p0, lane, T);
                     }
                 }
+            }
+            if (in_regs) {
+                // The row goes to HBM for stage 3 only, after the next model's entries
+                // have been waited for: the stores then have a whole model's sweeps to
+                // complete in, and neither barrier waits for them.
+                if (s > 0) {
+                    lds_barrier();  // every wavefront is done with the old row
+                    if (p_hi >= 0) publish_position<COPIES>(r_hi, ldsb, CSB, p_hi, lane, T);
+                    if (p_lo >= 0) publish_position<COPIES>(r_lo, ldsb, CSB, p_lo, lane, T);
+                    commit_row(pf, grow_next, cbuf);
+                }
+                if (p_hi >= 0) store_position<COPIES>(r_hi, out, p_hi, lane, T);
+                if (p_lo >= 0) store_position<COPIES>(r_lo, out, p_lo, lane, T);
+                if (s == 0) break;
+                lds_barrier();
+                continue;
             }
             if (s == 0) break;  // nothing reads the LDS copies of the last row
 
@@ -592,19 +677,19 @@ inline int wide_groups_per_cu(int copies, int waves, int cand_buf)
     return per_cu < 1 ? 1 : per_cu;
 }
 
-template <int COPIES>
+template <int COPIES, bool FIXED>
 hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int low, int cus)
 {
     const int nwc = CLS_WAVES[c];
     const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
     const size_t lds_bytes = wide_lds_bytes(COPIES, nwc, cand_buf);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_wide<COPIES>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_wide<COPIES, FIXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(LDS_PER_CU - 1024));
     if (e != hipSuccess) return e;
     long long grid = (long long)cus * wide_groups_per_cu(COPIES, nwc, cand_buf);
     if (grid > L_.N) grid = L_.N;
-    hipLaunchKernelGGL(k2_minplus_wide<COPIES>, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
+    hipLaunchKernelGGL((k2_minplus_wide<COPIES, FIXED>), dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
                        (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
                        (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
                        (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off), L_.N, L_.S,
@@ -630,8 +715,9 @@ MinplusPlan make_plan(const Layout& L_)
     return pl;
 }
 
-hipError_t launch_minplus(const themis_problem_t&, const Layout& L_, char* ws, hipStream_t st)
+hipError_t launch_minplus(const themis_problem_t& p, const Layout& L_, char* ws, hipStream_t st)
 {
+    const bool fixed = p.prune != THEMIS_PRUNE_NONE;
     const MinplusPlan pl = make_plan(L_);
     hipError_t e;
 
@@ -654,8 +740,12 @@ hipError_t launch_minplus(const themis_problem_t&, const Layout& L_, char* ws, h
     for (int c = pl.top_wide; c >= pl.merge_to; --c) {
         // a merged launch also serves every class below it
         const int low = c == pl.merge_to ? 0 : c;
-        e = class_copies(c, pl.copies_mask) == 2 ? launch_wide_class<2>(L_, ws, st, c, low, pl.cus)
-                                                 : launch_wide_class<4>(L_, ws, st, c, low, pl.cus);
+        if (class_copies(c, pl.copies_mask) == 2)
+            e = fixed ? launch_wide_class<2, true>(L_, ws, st, c, low, pl.cus)
+                      : launch_wide_class<2, false>(L_, ws, st, c, low, pl.cus);
+        else
+            e = fixed ? launch_wide_class<4, true>(L_, ws, st, c, low, pl.cus)
+                      : launch_wide_class<4, false>(L_, ws, st, c, low, pl.cus);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
