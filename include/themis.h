@@ -302,7 +302,9 @@ int themis_stage_backtrack(const themis_problem_t *p, int32_t *d_status,
 /*
  * Copy stage 1's tables out of the workspace for inspection:
  * d_lt, d_cost int32 [N][S][K], K = c_max*n_batch; infeasible entries are -1
- * in both.  The replica count of a feasible entry is cost / c.
+ * in both (under THEMIS_PRUNE_DOMINATED the dropped candidates too: what is
+ * left is the cost/latency staircase of each row).  The replica count of a
+ * feasible entry is cost / c.
  */
 int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
                              size_t workspace_bytes, int32_t *d_lt, int32_t *d_cost,
