@@ -145,8 +145,7 @@ __global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta,
     int32_t* __restrict__ order, int32_t* __restrict__ ctrl, uint32_t N, uint32_t S,
-    int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, int merge_to,
-    uint32_t cs)
+    int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, uint32_t cs)
 {
     __shared__ int32_t in_block[N_CLS];   // instances of the class in this workgroup
     __shared__ int32_t list_base[N_CLS];  // where the workgroup's stretch of the list starts
@@ -532,8 +531,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                        dim3(VALIDATE_THREADS), 0, st, d_coef,
                        d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, tmeta,
                        (int32_t*)(ws + L.order_off), ctrl, (uint32_t)L.N, (uint32_t)L.S, p.r_max,
-                       p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, plan.merge_to,
-                       cs);
+                       p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, cs);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 

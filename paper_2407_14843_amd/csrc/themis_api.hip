@@ -98,7 +98,7 @@ int solve(const themis_problem_t* p, const int32_t* d_coef, const int32_t* d_lam
 
 extern "C" {
 
-int themis_version(void) { return 100; }
+int themis_version(void) { return 101; }
 
 int themis_check_problem(const themis_problem_t* p) { return check(p); }
 
