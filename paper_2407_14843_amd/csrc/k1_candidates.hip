@@ -551,8 +551,11 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     // (row, batch size): half the rows and LDS per workgroup, twice the workgroups
     // per compute unit, for one extra model evaluation per thread.
     const uint32_t row_bytes = (uint32_t)(2 * (L.nb + 1) + L.Kp) * sizeof(uint32_t);
+    // The same split serves small batches, whose workgroups would not fill the chip.
+    const uint32_t rpw1 = 256u / (uint32_t)p.n_batch;
+    const bool few = ((uint32_t)L.N * L.S + rpw1 - 1) / rpw1 < 4u * (uint32_t)plan.cus;
     const uint32_t split =
-        p.c_max >= 8 && 256u / (uint32_t)p.n_batch * row_bytes + tab_bytes > 32u * 1024u ? 2u : 1u;
+        p.c_max >= 8 && (rpw1 * row_bytes + tab_bytes > 32u * 1024u || few) ? 2u : 1u;
     // rows per workgroup: as many as 256 threads cover, within 76 KB of LDS
     uint32_t RPW = 256u / ((uint32_t)p.n_batch * split);
     if (RPW == 0) RPW = 1;
