@@ -179,6 +179,36 @@ def test_rows_longer_than_the_staging_buffer(T, oracle):
     assert (want[0] == 0).any()
 
 
+@pytest.mark.parametrize("prune", [0, 1])
+def test_largest_candidate_count(T, oracle, prune):
+    """K = 8192 candidates per model (512 cores x 16 batch sizes), the most the
+    interface takes: one row no longer fits the staging buffer of stage 2 and
+    stage 1 is down to two rows per workgroup."""
+    rng = np.random.default_rng(31)
+    n, S, c_max, r_max = 7, 1, 512, 60
+    bs = [1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256]
+    coef = np.stack([rng.integers(lo, hi + 1, size=(n, S)) for lo, hi in
+                     ((200_000, 900_000), (5_000, 50_000), (0, 50), (1, 700), (100, 1000))],
+                    axis=-1).astype(np.int32)
+    lam = rng.integers(50, 3000, n).astype(np.int32)
+    slo = rng.integers(100_000, 2_000_000, n).astype(np.int32)
+    w = wl.Workload("kmax", wl.JOINT, n, S, c_max, bs, r_max, 1000, 2_000_000, False, coef,
+                    lam, slo)
+    assert w.n_cand == 8192
+    print(f"[case] largest K prune={prune}", flush=True)
+    b = T.DeviceBatch(w, prune=prune)
+    assert T.check_problem(b.p) == T.OK
+    if not prune:
+        lt_g, cost_g = b.candidates()
+        lt_o, cost_o, _ = oracle.candidates(w)
+        assert (lt_g == lt_o).all() and (cost_g == cost_o).all()
+        assert (lt_o >= 0).sum(axis=2).max() > 512      # more feasible entries than the buffer
+    want = oracle.solve(w, threads=7)
+    b.solve()
+    assert_same(b.results(), want)
+    assert (want[0] == 0).sum() >= 4
+
+
 def test_shared_coefficients(T, oracle):
     w = wl.workload(4, 333)
     want = oracle.solve(w, threads=8)
