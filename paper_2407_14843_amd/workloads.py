@@ -222,3 +222,25 @@ def tiny_random(rng: np.random.Generator, variant: int = JOINT, n_inst: int = 1,
         r_fixed = rng.integers(1, r_max + 1, size=(n_inst, S)).astype(np.int32)
     return Workload("tiny", variant, n_inst, S, c_max, batch_sizes, r_max, tick,
                     120_000, False, coef, lam, slo_us, r_fixed=r_fixed)
+
+
+def medium_random(rng: np.random.Generator, variant: int = JOINT) -> Workload:
+    """A random batch with a search space of realistic size (up to 32 cores x 8
+    batch sizes, up to 9000 grid cells, up to 5 models) that the CPU checker still
+    solves in a fraction of a second; every shape parameter is drawn."""
+    n = int(rng.integers(1, 40))
+    S = int(rng.integers(1, 6))
+    c_max = int(rng.integers(1, 33))
+    batch_sizes = sorted(set(int(x) for x in rng.integers(1, 129, int(rng.integers(1, 9)))))
+    r_max = min(int(rng.integers(1, 32767 // (S * c_max) + 1)), 64)
+    tick = int(rng.choice([100, 250, 500, 1000]))
+    slo_max = int(rng.integers(1, 9000)) * tick
+    coef = _draw_coef(rng, (n, S), a=(1000, 40000), k=(100, 10000), q=(0, 100), p=(1, 40),
+                      o=(1, 2000))
+    lam = rng.integers(1, 6000, n).astype(np.int32)
+    slo_us = rng.integers(0, slo_max + 1, n).astype(np.int32)
+    r_fixed = None
+    if variant == VERTICAL:
+        r_fixed = rng.integers(1, r_max + 1, size=(n, S)).astype(np.int32)
+    return Workload("medium", variant, n, S, c_max, batch_sizes, r_max, tick, slo_max, False,
+                    coef, lam, slo_us, r_fixed=r_fixed)
