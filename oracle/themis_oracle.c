@@ -381,9 +381,8 @@ int themis_oracle_solve(int32_t n_stage, int32_t c_max, int32_t n_batch,
  * lambda; if there is no solution, binary-search the largest arrival rate the
  * given replicas can absorb, keep the vertical configuration at that rate, and
  * serve the remaining lambda - lambda_v by NEW instances found with the
- * horizontal dynamic program (Algorithm 2: choose instance count and batch)
- * "with the same CPU", i.e. with each model's cores pinned to the vertical
- * configuration's.
+ * horizontal dynamic program (Algorithm 2: choose instance count and batch),
+ * each model keeping the core allocation of the vertical configuration.
  *
  * Readings where the listing is garbled: the midpoint is (left+right)/2, and a
  * FEASIBLE midpoint raises `left` (the printed midpoint formula and branches
