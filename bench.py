@@ -28,7 +28,7 @@ LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {"w1-joint-4096x5": 120163688, "w3-joint-65536x8": 10896121177}
+K2_HBM_TRAFFIC = {"w1-joint-4096x5": 120922093, "w3-joint-65536x8": 10904465211}
 
 
 def _events(n):
@@ -36,7 +36,7 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0):
+def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=False):
     """Time `steps` solves of workload idx; returns a dict of measurements."""
     import numpy as np
     import torch
@@ -47,6 +47,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0):
         passes = [w, None]          # second pass is built from the first one's output
     out = {"workload": w.name, "n_inst": w.n_inst, "n_stage": w.n_stage, "n_cand": w.n_cand}
     total_ms = 0.0
+    copy_ms = 0.0
     k_ms = [0.0, 0.0, 0.0]
     cells = 0
     relax = 0
@@ -85,6 +86,19 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0):
             for j in range(3):
                 k_ms[j] += e[j].elapsed_time(e[j + 1])
 
+        # the same steps with the results copied to pinned host memory after each
+        # (the boundary hands over device buffers, so this leg is extra)
+        host = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+                for t in (b.status, b.cost, b.ticks, b.cfg)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps if copy_leg else 0):
+            step()
+            for h, t in zip(host, (b.status, b.cost, b.ticks, b.cfg)):
+                h.copy_(t, non_blocking=True)
+        torch.cuda.synchronize()
+        copy_ms += (time.perf_counter() - t0) * 1e3
+
         res = b.results()
         if pi == 0:
             first_results = res
@@ -104,6 +118,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0):
     out.update({
         "solves_per_step": n_solves,
         "ms_per_step": ms_per_step,
+        "ms_per_step_with_result_copy": copy_ms / steps if copy_leg else None,
         "solves_per_s": n_solves / (ms_per_step * 1e-3),
         "dp_cells_per_s": cells / (ms_per_step * 1e-3),
         "relaxations_per_s": relax / (ms_per_step * 1e-3),
@@ -206,9 +221,15 @@ def cpu_baseline(wl, idx, max_inst):
     t0 = time.perf_counter()
     oracle.solve(w, threads=threads)
     dt = time.perf_counter() - t0
+    one = w.head(min(256, w.n_inst))
+    t0 = time.perf_counter()
+    oracle.solve(one, threads=1)
+    dt1 = time.perf_counter() - t0
     return {"value": w.n_inst / dt, "unit": "solves/s", "cores": threads, "kind": "oracle",
             "sample": f"first {w.n_inst} instances of {w.name}, instance range sharded over "
-                      f"{threads} threads, {dt:.2f} s wall"}
+                      f"{threads} threads, {dt:.2f} s wall",
+            "single_thread_value": one.n_inst / dt1,
+            "single_thread_sample": f"first {one.n_inst} instances, {dt1:.2f} s"}
 
 
 def lds_probe():
@@ -271,6 +292,9 @@ def main():
     ap.add_argument("--prune", action="store_true",
                     help="time the solve with dominated candidates pruned as the main figure "
                          "(same answers, fewer relaxations); the default times the dense solve")
+    ap.add_argument("--no-result-copy", action="store_true",
+                    help="skip the extra leg that repeats the steps with the results copied to "
+                         "the host (keeps a profiler's kernel counts to the timed steps)")
     ap.add_argument("--no-pruned", action="store_true",
                     help="skip the extra leg that times the pruned solve beside the dense one")
     ap.add_argument("--copy-calib", action="store_true",
@@ -301,7 +325,8 @@ def main():
                           "copy_calib_bytes_written": dst.numel() * 4}), flush=True)
         return
 
-    m = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=int(a.prune))
+    m = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=int(a.prune),
+                     copy_leg=not a.no_result_copy)
     k2_ms = m["kernel_ms"]["minplus"]
     k2_gbs = m["minplus_lds_bytes"] / (k2_ms * 1e-3) / 1e9
     line = {
@@ -312,6 +337,7 @@ def main():
         "steps": a.steps,
         "warmup": a.warmup,
         "ms_per_step": m["ms_per_step"],
+        "ms_per_step_with_result_copy": m["ms_per_step_with_result_copy"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
