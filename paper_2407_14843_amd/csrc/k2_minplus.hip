@@ -12,37 +12,41 @@
 // that stage 3 can rebuild the choice forward from model 0).
 //
 // Mapping.  One workgroup per instance.  Lanes run over t and the candidate
-// loop is wave-uniform: lt and cost live in SGPRs, and a candidate contributes
-// f[s+1] shifted by lt, a unit-stride LDS read.  There is no cross-lane traffic
-// and no argmin bookkeeping in the loop: only f is kept, and stage 3 recovers
-// the argmin from the stored rows.
+// loop is wave-uniform: a candidate contributes f[s+1] shifted by lt, a
+// unit-stride LDS read.  The row's entries (shift, cost) are staged in LDS once
+// per model and every lane reads the same entry (a broadcast), so they arrive in
+// VGPRs in order with the row reads.  There is no cross-lane traffic and no
+// argmin bookkeeping in the loop: only f is kept, and stage 3 recovers the
+// argmin from the stored rows.
 //
 // f is 16 bits wide (totals are bounded by THEMIS_COST_LIMIT), so a dword holds
-// two cells and one v_pk_add_u16 + one v_pk_min_u16 relax two cells.  On
-// gfx950 the LDS delivers twice the bytes per clock to 64-bit reads that it
-// does to 32-bit ones, but only at natural alignment (a misaligned ds_read is
-// ~25x slower).  A shift by lt moves the row by an arbitrary number of 2-byte
-// cells, so the previous row is kept in LDS once per residue of the shift:
-//   wide kernel   4 copies, copy m shifted by m cells, ds_read_b64 (4 cells)
-//   narrow kernel 2 copies, copy m shifted by m cells, ds_read_b32 (2 cells)
-// and a candidate reads the copy with m = (-lt) mod 4 (resp. lt mod 2), always
-// aligned.  New values stay in registers while the old row is being read.
+// two cells and one v_pk_add_u16 + one v_pk_min_u16 relax two cells.  LDS reads
+// are only fast at natural alignment (a misaligned ds_read is ~25x slower), and
+// a shift by lt moves the row by an arbitrary number of 2-byte cells, so the
+// previous row is kept in LDS once per residue of the shift: copy m is the row
+// shifted by m cells, and a candidate reads the copy whose residue fits, always
+// aligned.  Two copies with 32-bit reads (lt mod 2) are the default; four copies
+// with 64-bit reads ((-lt) mod 4) deliver twice the bytes per clock but double
+// the LDS footprint, and the resident wavefronts that costs weigh more.  Rows of
+// more than 16384 cells go to the narrow kernel (two copies, static chunks).
+// New values stay in registers while the old row is being read.
 //
 // The row is cut into positions of 512 cells.  A candidate only reaches the
 // positions whose last cell is >= lt, and stage 1 ordered every row of the
 // candidate table by lt / 512, so the candidates that reach position p are the
 // first bcum[p+1] entries of the row: the inner loops run over a prefix with no
-// test per candidate.  Work per position therefore grows with p; to keep the
-// wavefronts of an instance level, wavefront w takes position w from the
-// bottom of the row and position npos-1-w from the top (the row folded in the
-// middle).  A stretch of F_INF in front of every copy serves the reads that
-// reach below t = 0, and doubles as the harmless target of the few entries
-// that pad a batch of eight beyond the prefix.
+// test per candidate.  Work per position therefore grows with p; the wavefronts
+// of a workgroup take positions from a counter, most expensive first (or, in the
+// form used for pruned rows, own a late and an early position each).  A stretch
+// of F_INF in front of every copy serves the reads that reach below t = 0, and
+// doubles as the harmless target of the entries that pad a group of four beyond
+// the prefix.
 //
 // Scheduling.  Instances were grouped by row length in stage 1.  Every group is
 // launched once, with a workgroup of exactly the wavefronts its rows need and
 // just enough workgroups to fill the chip; the workgroups pull instances from
-// the group's list through an atomic cursor until it is exhausted.
+// the group's list through an atomic cursor until it is exhausted.  A small
+// batch is served by one launch that walks all the lists, longest rows first.
 #include "themis_internal.h"
 
 namespace themis {

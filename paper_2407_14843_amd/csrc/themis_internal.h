@@ -37,13 +37,12 @@ constexpr int MAX_CAND = THEMIS_MAX_CANDIDATES; // candidates per model (LDS sta
 
 // ---- work classes of the min-plus stage ---------------------------------
 // An instance with budget T owns T+1 cells.  The "wide" kernel gives every
-// wavefront WIDE_CHUNK cells (two positions of 512: 64 lanes x 2 quads of 4
-// cells each), so an instance needs ceil((T+1)/WIDE_CHUNK) wavefronts;
-// instances are grouped by that count (rounded up to the next entry of
-// CLS_WAVES) and each group is launched with a workgroup of exactly that many
-// wavefronts and the LDS that goes with it.  Budgets beyond 16 chunks go to
-// the "narrow" kernel, which keeps two instead of four row copies and so fits
-// rows twice as long.
+// wavefront WIDE_CHUNK cells (two positions of 512), so an instance needs
+// ceil((T+1)/WIDE_CHUNK) wavefronts; instances are grouped by that count
+// (rounded up to the next entry of CLS_WAVES) and each group is launched with a
+// workgroup of exactly that many wavefronts and the LDS that goes with it.
+// Budgets beyond 16 chunks go to the "narrow" kernel, whose sixteen wavefronts
+// take static chunks of a row twice as long.
 constexpr int WIDE_CHUNK = 1024;                 // cells per wavefront
 constexpr int N_WIDE_CLS = 10;
 constexpr int CLS_WAVES[N_WIDE_CLS] = {1, 2, 3, 4, 6, 8, 10, 12, 14, 16};
@@ -62,7 +61,7 @@ __host__ __device__ inline int class_of_budget(int T)
 }
 
 // ---- LDS geometry of the min-plus stage (stage 1 bakes it into StepEntry) --
-// Wide kernel: four copies of the row, copy m holds cell t at half-word
+// Wide kernel: two or four copies of the row, copy m holds cell t at half-word
 // (WIDE_PAD_BYTES/2 + t - m); each copy is WIDE_PAD_BYTES of F_INF followed by
 // two positions (2 * 512 cells) per wavefront of the class.
 constexpr int WIDE_PAD_BYTES = BUCKET_CELLS * 2;
@@ -72,9 +71,8 @@ __host__ __device__ inline int wide_copy_bytes(int waves)
     return WIDE_PAD_BYTES + waves * WIDE_CHUNK * 2;
 }
 
-// Row copies a work class keeps: four (64-bit reads) where two workgroups of
-// the class still fit a compute unit's LDS, two (32-bit reads) for the longest
-// rows, which would otherwise be alone on their compute unit.
+// Row copies a work class keeps: two (32-bit reads) or four (64-bit reads, twice
+// the LDS footprint).  Two for every class unless the tuning knob says otherwise.
 int wide_copies_mask();  // bit c set: wide class c keeps two copies
 __host__ __device__ inline int class_copies(int cls, int mask) { return (mask >> cls) & 1 ? 2 : 4; }
 
