@@ -3,9 +3,10 @@
 // Algorithms 1 and 2 (Section 4.4) recompute a candidate's latency l, queueing
 // delay q and throughput h inside the budget loop although none of them depends
 // on the budget.  This kernel evaluates each (model, cores, batch) candidate of
-// each instance exactly once and writes its latency in grid ticks and its cost
-// (replicas * cores) to HBM, packed into one word, each row ordered by latency
-// bucket so that the min-plus stage can work on prefixes of a row.
+// each instance exactly once and writes it to HBM as an 8-byte entry (its cost,
+// its index, and its latency in grid ticks in the form of the LDS offset the
+// min-plus stage will read at), each row ordered by latency bucket so that the
+// min-plus stage can work on prefixes of a row.
 //
 // Integer model (microseconds, all roundings upward), after Eq. 1, Eq. 4 and
 // the throughput constraint of Eq. 6:
@@ -203,10 +204,11 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 
 // Candidate evaluation plus a counting sort of each row by bucket.
 //
-// One thread per (row, batch size); a workgroup of 256 threads covers
-// RPW = 256 / n_batch rows ((instance, model) pairs).  The thread walks the
-// cores c = 1 .. c_max: the latency model only depends on min(c, p), so it is
-// evaluated for c <= p and reused (with cost n*c) beyond.  Pass 1 parks every
+// One thread per (row, batch size), or `split` threads taking alternate cores; a
+// workgroup of 256 threads covers RPW = 256 / (n_batch * split) rows ((instance,
+// model) pairs).  The thread walks its cores c <= c_max: the latency model only
+// depends on min(c, p), so it is evaluated for c <= p and reused (with cost n*c)
+// beyond.  Pass 1 parks every
 // candidate's (lt, cost) in LDS and counts its bucket; a wavefront scan turns
 // the counts into bucket offsets; pass 2 hands every entry a slot inside its
 // bucket's range and writes it to HBM in the form the min-plus stage reads.
