@@ -149,3 +149,14 @@ def test_model_options_accepted(T):
                 p = T.make_problem(64, 3, 8, [1, 2], 8, 1000, 300_000, queue_model=qm,
                                    profile_form=pf, prune=pr)
                 assert T.check_problem(p) == T.OK
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    """No CPU fallback: without the built HIP library the binding raises."""
+    from paper_2407_14843_amd import themis
+    monkeypatch.setattr(themis, "_lib", None)
+    monkeypatch.setattr(themis, "LIB_PATH", "/nonexistent/libthemis_hip.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        themis.lib()
+    with pytest.raises(RuntimeError):
+        themis.check_problem(themis.make_problem(1, 1, 1, [1], 1, 1, 1))
