@@ -3,7 +3,10 @@
 
 A step is one pass of the whole solve (candidate tables -> min-plus DP ->
 selection and reconstruction) over one batch of synthetic instances whose
-inputs are already resident in HBM.  Prints ONE JSON line.
+inputs are already resident in HBM.  The steps are timed twice: as single calls
+of the solve entry point (`value`, `ms_per_step`), and stage by stage with HIP
+events between the stages (`kernel_ms`, the roofline figures,
+`ms_per_step_stage_by_stage`).  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..4] [--others]
 """
@@ -28,7 +31,7 @@ LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {"w1-joint-4096x5": 120922093, "w3-joint-65536x8": 10904465211}
+K2_HBM_TRAFFIC = {"w1-joint-4096x5": 120586855, "w3-joint-65536x8": 10902658292}
 
 
 def _events(n):
@@ -47,6 +50,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
         passes = [w, None]          # second pass is built from the first one's output
     out = {"workload": w.name, "n_inst": w.n_inst, "n_stage": w.n_stage, "n_cand": w.n_cand}
     total_ms = 0.0
+    staged_ms = 0.0
     copy_ms = 0.0
     k_ms = [0.0, 0.0, 0.0]
     cells = 0
@@ -72,8 +76,16 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
             themis.themis_stage_backtrack(p, b.status, b.cost, b.ticks, b.cfg, b.workspace, stream)
 
         for _ in range(warmup):
-            step()
+            b.solve(stream)
         torch.cuda.synchronize()
+        # the timed steps: one call of the whole solve each, nothing in between
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            b.solve(stream)
+        torch.cuda.synchronize()
+        total_ms += (time.perf_counter() - t0) * 1e3
+        # the same steps issued stage by stage with HIP events between the stages
+        # (an event costs a few microseconds of GPU time, so this leg is a little slower)
         evs = [_events(4) for _ in range(steps)]
         t0 = time.perf_counter()
         for e in evs:
@@ -81,7 +93,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
             step(e)
             e[3].record(stream)
         torch.cuda.synchronize()
-        total_ms += (time.perf_counter() - t0) * 1e3
+        staged_ms += (time.perf_counter() - t0) * 1e3
         for e in evs:
             for j in range(3):
                 k_ms[j] += e[j].elapsed_time(e[j + 1])
@@ -93,7 +105,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps if copy_leg else 0):
-            step()
+            b.solve(stream)
             for h, t in zip(host, (b.status, b.cost, b.ticks, b.cfg)):
                 h.copy_(t, non_blocking=True)
         torch.cuda.synchronize()
@@ -119,6 +131,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
         "solves_per_step": n_solves,
         "ms_per_step": ms_per_step,
         "ms_per_step_with_result_copy": copy_ms / steps if copy_leg else None,
+        "ms_per_step_stage_by_stage": staged_ms / steps,
         "solves_per_s": n_solves / (ms_per_step * 1e-3),
         "dp_cells_per_s": cells / (ms_per_step * 1e-3),
         "relaxations_per_s": relax / (ms_per_step * 1e-3),
@@ -338,6 +351,7 @@ def main():
         "warmup": a.warmup,
         "ms_per_step": m["ms_per_step"],
         "ms_per_step_with_result_copy": m["ms_per_step_with_result_copy"],
+        "ms_per_step_stage_by_stage": m["ms_per_step_stage_by_stage"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
