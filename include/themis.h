@@ -196,8 +196,8 @@ int themis_solve_horizontal(const themis_problem_t *p, const int32_t *d_coef,
 
 /*
  * Bytes of device workspace themis_solve_vertical_fallback needs (0 if `p` is
- * not acceptable): themis_workspace_bytes(p) plus the search state, a few words
- * per instance and model.  256-byte aligned, contents need not be initialised.
+ * not acceptable): themis_workspace_bytes(p) plus a few words per instance and
+ * model for the rates and cores handed from pass to pass.  256-byte aligned, contents need not be initialised.
  */
 size_t themis_fallback_workspace_bytes(const themis_problem_t *p);
 
@@ -214,11 +214,14 @@ size_t themis_fallback_workspace_bytes(const themis_problem_t *p);
  * sooner), so like the paper's search this is a heuristic for "the largest
  * rate"; its steps are fixed and the result is deterministic.
  *
+ * The search itself does not run the dynamic program: the replicas can absorb
+ * a rate exactly when the fastest feasible candidate of every model (with the
+ * replicas given, the one at the core cap) fits the budget together, which one
+ * thread per instance tests with the candidate stage's arithmetic.  The three
+ * stages run three times: at lambda for all instances, then at lambda_v and
+ * for the remainder over the instances the first pass left open.
+ *
  *   d_r_fixed   int32 [N][S]  running replicas, 1..r_max
- *   lambda_max  host value: no instance's rate exceeds it (1..THEMIS_VALUE_MAX,
- *               0 = THEMIS_VALUE_MAX).  It fixes the number of passes,
- *               2 + ceil(log2(lambda_max - 1)); an instance with a larger rate
- *               is reported THEMIS_INVALID.
  * Outputs, all int32 on the device:
  *   d_status/d_cost/d_ticks [N], d_cfg [N][S][3]   the vertical part at
  *               lambda_v; THEMIS_INFEASIBLE when not even rate 1 fits
@@ -235,7 +238,7 @@ size_t themis_fallback_workspace_bytes(const themis_problem_t *p);
  */
 int themis_solve_vertical_fallback(const themis_problem_t *p, const int32_t *d_coef,
                                    const int32_t *d_lambda, const int32_t *d_slo_us,
-                                   const int32_t *d_r_fixed, int32_t lambda_max,
+                                   const int32_t *d_r_fixed,
                                    int32_t *d_status, int32_t *d_cost, int32_t *d_ticks,
                                    int32_t *d_cfg, int32_t *d_lambda_v,
                                    int32_t *d_status_h, int32_t *d_cost_h,

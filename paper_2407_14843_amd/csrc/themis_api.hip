@@ -149,17 +149,15 @@ size_t themis_fallback_workspace_bytes(const themis_problem_t* p)
 
 int themis_solve_vertical_fallback(const themis_problem_t* p, const int32_t* d_coef,
                                    const int32_t* d_lambda, const int32_t* d_slo_us,
-                                   const int32_t* d_r_fixed, int32_t lambda_max,
-                                   int32_t* d_status, int32_t* d_cost, int32_t* d_ticks,
-                                   int32_t* d_cfg, int32_t* d_lambda_v, int32_t* d_status_h,
-                                   int32_t* d_cost_h, int32_t* d_ticks_h, int32_t* d_cfg_h,
-                                   void* d_workspace, size_t workspace_bytes, void* stream)
+                                   const int32_t* d_r_fixed, int32_t* d_status, int32_t* d_cost,
+                                   int32_t* d_ticks, int32_t* d_cfg, int32_t* d_lambda_v,
+                                   int32_t* d_status_h, int32_t* d_cost_h, int32_t* d_ticks_h,
+                                   int32_t* d_cfg_h, void* d_workspace, size_t workspace_bytes,
+                                   void* stream)
 {
     if (!d_coef || !d_lambda || !d_slo_us || !d_r_fixed || !d_status || !d_cost || !d_ticks ||
         !d_cfg || !d_lambda_v || !d_status_h || !d_cost_h || !d_ticks_h || !d_cfg_h)
         return THEMIS_ERR_NULL;
-    if (lambda_max < 0 || lambda_max > THEMIS_VALUE_MAX) return THEMIS_ERR_RANGE;
-    if (lambda_max == 0) lambda_max = THEMIS_VALUE_MAX;
     int rc = check(p);
     if (rc != THEMIS_OK) return rc;
     const Layout L = make_layout(*p);
@@ -171,24 +169,22 @@ int themis_solve_vertical_fallback(const themis_problem_t* p, const int32_t* d_c
     char* w = static_cast<char*>(d_workspace);
     const FallbackOut out{d_status, d_cost,     d_ticks, d_cfg,    d_lambda_v,
                           d_status_h, d_cost_h, d_ticks_h, d_cfg_h};
-    const int32_t* lam_cur = (const int32_t*)(w + F.lam_cur_off);
 
     // the plain vertical solve, reported for every instance
     rc = pass(*p, L, d_coef, d_lambda, d_slo_us, d_r_fixed, d_status, d_cost, d_ticks, d_cfg, w,
               st, PassOpts());
     if (rc != THEMIS_OK) return rc;
-    if (launch_fallback_step(L, F, 1, d_lambda, lambda_max, out, w, st) != hipSuccess)
+    // the search, for the instances it found no configuration for
+    if (launch_fallback_search(*p, L, F, d_coef, d_lambda, d_slo_us, d_r_fixed, out, w, st) !=
+        hipSuccess)
         return THEMIS_ERR_LAUNCH;
-    // the search: each pass only touches the instances that are still looking
+    // their vertical configuration at the rate the search settled on
     PassOpts only_active;
     only_active.sparse = 1;
-    for (int r = fallback_rounds(lambda_max); r > 0; --r) {
-        rc = pass(*p, L, d_coef, lam_cur, d_slo_us, d_r_fixed, d_status, d_cost, d_ticks, d_cfg,
-                  w, st, only_active);
-        if (rc != THEMIS_OK) return rc;
-        if (launch_fallback_step(L, F, 0, d_lambda, lambda_max, out, w, st) != hipSuccess)
-            return THEMIS_ERR_LAUNCH;
-    }
+    rc = pass(*p, L, d_coef, (const int32_t*)(w + F.lam_cur_off), d_slo_us, d_r_fixed, d_status,
+              d_cost, d_ticks, d_cfg, w, st, only_active);
+    if (rc != THEMIS_OK) return rc;
+    if (launch_fallback_finish(L, F, d_lambda, out, w, st) != hipSuccess) return THEMIS_ERR_LAUNCH;
     // new instances for what the running replicas could not absorb
     PassOpts rest;
     rest.sparse = 1;

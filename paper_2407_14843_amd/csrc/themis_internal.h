@@ -217,15 +217,14 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L,
                             int32_t* d_cfg, char* ws, hipStream_t st,
                             const PassOpts& opts = PassOpts());
 
-// Search state of the vertical solve with fallback, appended to the workspace
-// after Layout::total (every region 256-byte aligned):
-//   lam_cur int32 [N]  arrival rate of the next pass, 0 = instance switched off
-//   left, right int32 [N]  ends of the binary search
+// State of the vertical solve with fallback, appended to the workspace after
+// Layout::total (every region 256-byte aligned):
+//   lam_cur int32 [N]  rate of the second vertical pass, 0 = instance switched off
 //   state   int32 [N]  see k4_fallback.hip
 //   lam_rem int32 [N]  rate left for new instances, 0 = none
 //   cores   int32 [N][S] cores of the vertical configuration
 struct FallbackLayout {
-    size_t lam_cur_off, left_off, right_off, state_off, lam_rem_off, cores_off, total;
+    size_t lam_cur_off, state_off, lam_rem_off, cores_off, total;
 };
 
 inline FallbackLayout make_fallback_layout(const Layout& L)
@@ -234,8 +233,6 @@ inline FallbackLayout make_fallback_layout(const Layout& L)
     size_t at = L.total;
     const size_t n4 = (size_t)L.N * sizeof(int32_t);
     F.lam_cur_off = at; at = align256(at + n4);
-    F.left_off = at;    at = align256(at + n4);
-    F.right_off = at;   at = align256(at + n4);
     F.state_off = at;   at = align256(at + n4);
     F.lam_rem_off = at; at = align256(at + n4);
     F.cores_off = at;   at = align256(at + n4 * L.S);
@@ -243,23 +240,19 @@ inline FallbackLayout make_fallback_layout(const Layout& L)
     return F;
 }
 
-// Passes after the first that the search needs when no rate exceeds lambda_max:
-// one per halving of the interval (1, lambda_max), plus the solve at its lower end.
-inline int fallback_rounds(int32_t lambda_max)
-{
-    int rounds = 1;
-    for (int64_t w = (int64_t)lambda_max - 1; w > 1; w = (w + 1) / 2) ++rounds;
-    return rounds;
-}
-
 struct FallbackOut {
     int32_t *status, *cost, *ticks, *cfg;          // vertical part
     int32_t* lambda_v;
     int32_t *status_h, *cost_h, *ticks_h, *cfg_h;  // new instances
 };
-hipError_t launch_fallback_step(const Layout& L, const FallbackLayout& F, int first,
-                                const int32_t* d_lambda, int32_t lambda_max,
-                                const FallbackOut& out, char* ws, hipStream_t st);
+hipError_t launch_fallback_search(const themis_problem_t& p, const Layout& L,
+                                  const FallbackLayout& F, const int32_t* d_coef,
+                                  const int32_t* d_lambda, const int32_t* d_slo_us,
+                                  const int32_t* d_r_fixed, const FallbackOut& out, char* ws,
+                                  hipStream_t st);
+hipError_t launch_fallback_finish(const Layout& L, const FallbackLayout& F,
+                                  const int32_t* d_lambda, const FallbackOut& out, char* ws,
+                                  hipStream_t st);
 // Results of the solve at the predicted rate, appended to the workspace after
 // Layout::total for the stability test: status, cost, ticks int32 [N] each and
 // cfg int32 [N][S][3].

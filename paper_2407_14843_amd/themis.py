@@ -72,7 +72,7 @@ def lib():
         L.themis_fallback_workspace_bytes.argtypes = [P]
         L.themis_solve_vertical_fallback.restype = ctypes.c_int
         L.themis_solve_vertical_fallback.argtypes = (
-            [P, vp, vp, vp, vp, ctypes.c_int32] + [vp] * 9 + [vp, sz, vp])
+            [P, vp, vp, vp, vp] + [vp] * 9 + [vp, sz, vp])
         L.themis_stability_workspace_bytes.restype = sz
         L.themis_stability_workspace_bytes.argtypes = [P]
         L.themis_check_stability.restype = ctypes.c_int
@@ -184,11 +184,11 @@ def fallback_workspace_bytes(p: ThemisProblem) -> int:
     return int(lib().themis_fallback_workspace_bytes(ctypes.byref(p)))
 
 
-def themis_solve_vertical_fallback(p, coef, lam, slo_us, r_fixed, lambda_max, status, cost,
+def themis_solve_vertical_fallback(p, coef, lam, slo_us, r_fixed, status, cost,
                                    ticks, cfg, lambda_v, status_h, cost_h, ticks_h, cfg_h,
                                    workspace, stream=None):
     _chk("themis_solve_vertical_fallback", lib().themis_solve_vertical_fallback(
-        ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(r_fixed), int(lambda_max),
+        ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(r_fixed),
         _dp(status), _dp(cost), _dp(ticks), _dp(cfg), _dp(lambda_v), _dp(status_h),
         _dp(cost_h), _dp(ticks_h), _dp(cfg_h), _dp(workspace, torch.uint8),
         workspace.numel(), _stream(stream)))
@@ -298,7 +298,7 @@ class DeviceBatch:
         self.stability_workspace = ws
         return self.stable
 
-    def solve_vertical_fallback(self, lambda_max=0, stream=None):
+    def solve_vertical_fallback(self, stream=None):
         """Enqueue the vertical solve with fallback; results via fallback_results()."""
         if getattr(self, "fb", None) is None:
             n = fallback_workspace_bytes(self.p)
@@ -306,7 +306,7 @@ class DeviceBatch:
             self.lambda_v = torch.empty(self.p.n_inst, dtype=torch.int32, device=self.device)
             self.fb = alloc_outputs(self.p, self.device)
         themis_solve_vertical_fallback(self.p, self.coef, self.lam, self.slo_us, self.r_fixed,
-                                       lambda_max, self.status, self.cost, self.ticks, self.cfg,
+                                       self.status, self.cost, self.ticks, self.cfg,
                                        self.lambda_v, *self.fb, self.fb_workspace, stream)
 
     def fallback_results(self):

@@ -90,10 +90,10 @@ def overloaded(idx, n, seed, factor):
     return w
 
 
-def run_fallback(T, w, lambda_max=None):
+def run_fallback(T, w):
     print(f"[case] fallback {w.name} N={w.n_inst} S={w.n_stage} K={w.n_cand}", flush=True)
     b = T.DeviceBatch(w)
-    b.solve_vertical_fallback(int(w.lam.max()) if lambda_max is None else lambda_max)
+    b.solve_vertical_fallback()
     return b, b.fallback_results()
 
 
@@ -120,7 +120,7 @@ def test_fallback_tiny_random(T, oracle):
         w.lam = np.minimum(w.lam.astype(np.int64) * rng.integers(1, 12, w.n_inst),
                            1 << 20).astype(np.int32)
         want = oracle.vertical_fallback(w)
-        _, got = run_fallback(T, w, lambda_max=0 if rep % 5 == 0 else None)
+        _, got = run_fallback(T, w)
         same([got[k] for k in FB_KEYS], [want[k] for k in FB_KEYS], FB_KEYS)
         lv = want["lambda_v"]
         mix += [(lv == w.lam).sum(), ((lv > 0) & (lv < w.lam)).sum(),
@@ -130,7 +130,7 @@ def test_fallback_tiny_random(T, oracle):
 
 def test_fallback_edge_rates_and_invalid(T, oracle):
     """Rates 1, 2 and 3 (search intervals of width 0, 1 and 2), the largest
-    rate, invalid instances, and an instance above the caller's bound."""
+    rate, and invalid instances."""
     w = overloaded(2, 40, 3, 6)
     w.slo_us[:12] = w.slo_us[:12] // 40           # hopeless at any rate, mostly
     w.lam[0:3] = [1, 2, 3]
@@ -138,19 +138,9 @@ def test_fallback_edge_rates_and_invalid(T, oracle):
     w.lam[4] = 0                                   # invalid
     w.r_fixed[5, 0] = w.r_max + 1                  # invalid
     want = oracle.vertical_fallback(w)
-    _, got = run_fallback(T, w, lambda_max=0)
+    _, got = run_fallback(T, w)
     same([got[k] for k in FB_KEYS], [want[k] for k in FB_KEYS], FB_KEYS)
     assert got["status"][4] == T.INVALID and got["status_h"][5] == T.INVALID
-
-    # a bound below some rates: those instances are reported invalid, the rest as before
-    bound = int(np.sort(w.lam)[len(w.lam) // 2])
-    _, got2 = run_fallback(T, w, lambda_max=bound)
-    over = w.lam > bound
-    assert over.any() and (~over).any()
-    for k in FB_KEYS:
-        assert (got2[k][~over] == want[k][~over]).all(), k
-    assert (got2["status"][over] == T.INVALID).all() and (got2["status_h"][over] == T.INVALID).all()
-    assert (got2["lambda_v"][over] == 0).all() and not got2["cfg"][over].any()
 
 
 def test_fallback_shortest_searches(T, oracle):
@@ -178,7 +168,7 @@ def test_fallback_twice_on_one_workspace(T, oracle):
     b.r_fixed.copy_(torch.from_numpy(w2.r_fixed))
     b.slo_us.copy_(torch.from_numpy(w2.slo_us))
     b.coef.copy_(torch.from_numpy(w2.coef))
-    b.solve_vertical_fallback(int(w2.lam.max()))
+    b.solve_vertical_fallback()
     got2 = b.fallback_results()
     for got, w in ((got1, w1), (got2, w2)):
         want = oracle.vertical_fallback(w, threads=8)

@@ -55,15 +55,14 @@ def test_captured_fallback_replays(T, oracle):
     want = oracle.vertical_fallback(w, threads=8)
     print("[case] graph capture fallback", flush=True)
     b = T.DeviceBatch(w)
-    lam_max = int(w.lam.max())
     s = torch.cuda.Stream()
     s.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(s):
-        b.solve_vertical_fallback(lam_max, stream=s)
+        b.solve_vertical_fallback(stream=s)
     s.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=s):
-        b.solve_vertical_fallback(lam_max, stream=torch.cuda.current_stream())
+        b.solve_vertical_fallback(stream=torch.cuda.current_stream())
     for rep in range(2):
         b.lambda_v.fill_(-7)
         b.status.fill_(-7)

@@ -118,7 +118,7 @@ def test_pruned_multi_pass_entry_points(T, oracle):
     want = oracle.vertical_fallback(w, threads=8)
     print("[case] pruned fallback", flush=True)
     b = T.DeviceBatch(w, prune=1)
-    b.solve_vertical_fallback(int(w.lam.max()))
+    b.solve_vertical_fallback()
     got = b.fallback_results()
     keys = ("status", "cost", "ticks", "cfg", "lambda_v", "status_h", "cost_h", "ticks_h", "cfg_h")
     same([got[k] for k in keys], [want[k] for k in keys], keys)

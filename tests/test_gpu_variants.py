@@ -123,7 +123,7 @@ def test_fallback_and_stability_under_paper_forms(T, oracle):
     want = oracle.vertical_fallback(w, threads=8)
     print("[case] fallback under Eq. 4 / Eq. 1", flush=True)
     b = T.DeviceBatch(w)
-    b.solve_vertical_fallback(int(w.lam.max()))
+    b.solve_vertical_fallback()
     got = b.fallback_results()
     keys = ("status", "cost", "ticks", "cfg", "lambda_v", "status_h", "cost_h", "ticks_h", "cfg_h")
     same([got[k] for k in keys], [want[k] for k in keys], keys)
