@@ -190,3 +190,38 @@ def test_given_cores_out_of_range_are_invalid(oracle):
     cores[3, -1] = w.c_max + 1
     st = oracle.solve(w, c_fixed=cores)[0]
     assert st[1] == 2 and st[3] == 2 and (st[[0, 2, 4]] != 2).all()
+
+
+def test_replicas_given_latency_never_grows_with_cores(oracle):
+    """With the replicas given, more cores never slow a candidate down and never
+    make a feasible one infeasible (Eq. 1 divides by the cores; none of the
+    queue terms of Eqs. 3-4 grows).  Hence the replicas can absorb a rate
+    exactly when the fastest candidates of all models fit the budget together,
+    which is what a search on the rate may test instead of solving the whole
+    recurrence.  Checked on the checker's own candidate tables and statuses,
+    under every queue model and both profile forms."""
+    rng = np.random.default_rng(77)
+    seen = np.zeros(2, int)
+    for rep in range(60):
+        w = wl.medium_random(rng, wl.VERTICAL)
+        if rep % 2:
+            w.lam = np.minimum(w.lam.astype(np.int64) * rng.integers(1, 8, w.n_inst),
+                               1 << 20).astype(np.int32)
+        d = rng.integers(0, 2000, size=w.coef.shape[:-1]) if rep % 3 == 0 else None
+        w = w.with_model(rep % 3, d)
+        lt, _, _ = oracle.candidates(w)
+        status = oracle.solve(w)[0]
+        nb = len(w.batch_sizes)
+        lt = lt.reshape(w.n_inst, w.n_stage, w.c_max, nb).astype(np.int64)
+        big = np.int64(1) << 40
+        filled = np.where(lt < 0, big, lt)
+        # along the cores axis: non-increasing, and infeasible only below feasible
+        assert (np.diff(filled, axis=2) <= 0).all()
+        fastest = filled[:, :, -1, :].min(axis=2)          # at the largest core count
+        assert (fastest == filled.min(axis=(2, 3))).all()
+        T = w.slo_us.astype(np.int64) // w.tick_us
+        fits = (fastest < big).all(axis=1) & (np.where(fastest < big, fastest, 0).sum(axis=1) <= T)
+        valid = status != 2
+        assert ((status == 0) == fits)[valid].all()
+        seen += [(status == 0).sum(), (status == 1).sum()]
+    assert (seen > 50).all(), seen
