@@ -273,7 +273,9 @@ def lds_probe():
              "v_fma_f64", "v_mul_f64", "v_add_f64", "v_floor_f64", "v_rcp_f64", "v_cvt_f64_u32",
              "v_cvt_u32_f64", "v_mul_lo_u32", "v_cmp_ge_f64", "v_cndmask_b32", "v_mul_u32_u24",
              "v_cndmask_b32_e64 (sgpr-pair mask)", "v_max_f64", "v_add_f64 clamp",
-             "v_cmp_ge_f64_e64 (sgpr-pair result)"]
+             "v_cmp_ge_f64_e64 (sgpr-pair result)", "v_mad_u32_u16",
+             "v_pk_add_u16 op_sel (one half to both lanes)", "v_lshl_add_u32",
+             "v_add_u32_sdwa (16-bit operand)"]
     vblocks, viters = N_CU * 8 * 4, 4000
     for op, name in enumerate(names):
         themis.themis_probe_valu(op, 10, vblocks, sink, stream)

@@ -345,7 +345,9 @@ int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32
  * v_mul_f64, v_add_f64, v_floor_f64, v_rcp_f64, v_cvt_f64_u32, v_cvt_u32_f64,
  * v_mul_lo_u32, v_cmp_ge_f64, v_cndmask_b32 on vcc, v_mul_u32_u24,
  * v_cndmask_b32 on a scalar pair, v_max_f64, v_add_f64 with clamp,
- * v_cmp_ge_f64 into a scalar pair).  One launch issues
+ * v_cmp_ge_f64 into a scalar pair; 21..24 address and operand-select forms
+ * of the min-plus stage: v_mad_u32_u16, v_pk_add_u16 with op_sel,
+ * v_lshl_add_u32, v_add_u32_sdwa).  One launch issues
  * blocks * 256 * iters * 16 lane-instructions; time it to obtain the
  * vector-ALU rates the stages are priced against.  Unknown op: THEMIS_ERR_SHAPE.
  */

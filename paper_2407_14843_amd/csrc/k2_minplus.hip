@@ -44,9 +44,10 @@
 //
 // Scheduling.  Instances were grouped by row length in stage 1.  Every group is
 // launched once, with a workgroup of exactly the wavefronts its rows need and
-// just enough workgroups to fill the chip; the workgroups pull instances from
-// the group's list through an atomic cursor until it is exhausted.  A small
-// batch is served by one launch that walks all the lists, longest rows first.
+// just enough workgroups to fill the chip; each workgroup starts on the list
+// entry of its own index and then pulls further ones through an atomic cursor
+// until the list is exhausted.  A small batch is served by one launch that
+// walks all the lists, longest rows first.
 #include "themis_internal.h"
 
 namespace themis {
@@ -62,6 +63,23 @@ __device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
+// a + (high half of e) in both cells: the operand-select bits of the packed add
+// route the entry's cost to both lanes, so it need not be replicated first.
+__device__ __forceinline__ uint32_t pk_add_hi(uint32_t a, uint32_t e)
+{
+    uint32_t r;
+    asm("v_pk_add_u16 %0, %1, %2 op_sel:[0,1] op_sel_hi:[1,1]" : "=v"(r) : "v"(a), "v"(e));
+    return r;
+}
+
+// base + 4 * (low half of e): one multiply-add on 16-bit operands
+__device__ __forceinline__ uint32_t add_dwords_lo(uint32_t base, uint32_t e)
+{
+    uint32_t r;
+    asm("v_mad_u32_u16 %0, %1, 4, %2" : "=v"(r) : "v"(e), "v"(base));
+    return r;
+}
+
 __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
 {
     u16x2 r = __builtin_elementwise_min(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b));
@@ -73,6 +91,14 @@ __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
 // otherwise counts as a possible writer), which lets it fetch wave-uniform
 // entries with scalar loads into SGPRs.
 #define AS_CONST __attribute__((address_space(4)))
+
+#define AS_LDS __attribute__((address_space(3)))
+
+// LDS address (byte offset within the workgroup's allocation) of a pointer into it
+__device__ __forceinline__ uint32_t lds_address(const void* p)
+{
+    return (uint32_t)(uintptr_t)(const AS_LDS char*)p;
+}
 
 template <typename T>
 __device__ __forceinline__ const AS_CONST T* as_constant(const T* p)
@@ -88,29 +114,43 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// Pull the next instance of this class, or -1 when the list is exhausted.
-// Every wavefront of the workgroup gets the same answer.
-__device__ __forceinline__ int next_instance(volatile uint32_t* slot, int32_t* cursor, int count,
-                                             const int32_t* order)
+// Instances are handed to the workgroups of a launch from the launch's list
+// (one class, or several classes one after the other).  The first gridDim.x
+// entries are dealt out by workgroup index; the rest are pulled one at a time
+// through an atomic cursor, so that a workgroup that drew long rows takes fewer.
+// The static first round matters for small batches: read-modify-writes on one
+// address complete at a rate of one per some tens of nanoseconds device-wide, which
+// a launch of thousands of short rows that all begin (and end) with a pull would
+// be bound by.  A launch whose list is no longer than its grid never touches the
+// cursor at all.
+//
+// Returns the list index of the workgroup's next instance, or -1 when the list
+// is exhausted; every wavefront of the workgroup gets the same answer.
+// `prev` is the previous answer (-1 before the first call).
+__device__ __forceinline__ int next_index(volatile uint32_t* slot, int32_t* cursor, int count,
+                                          int prev)
 {
+    if (prev < 0) return (int)blockIdx.x < count ? (int)blockIdx.x : -1;
+    if (count <= (int)gridDim.x) return -1;
     if (threadIdx.x == 0) *slot = (uint32_t)atomicAdd(cursor, 1);
     __syncthreads();
-    const int idx = __builtin_amdgcn_readfirstlane((int)*slot);
+    const int idx = (int)gridDim.x + __builtin_amdgcn_readfirstlane((int)*slot);
     __syncthreads();  // slot may be rewritten by the next call
-    if (idx >= count) return -1;
-    return as_constant(order)[idx];
+    return idx < count ? idx : -1;
 }
 
-// The same for a launch that serves the classes cls, cls - 1, ..., low: one
-// cursor runs through their lists in that order, so the longest rows start
-// first and the launch ends on the shortest ones.
-__device__ __forceinline__ int next_instance_of(volatile uint32_t* slot, int32_t* ctrl,
-                                                const int32_t* order, int N, int cls, int low)
+// The list of a launch that serves the classes cls, cls - 1, ..., low, in that
+// order: the longest rows start first and the launch ends on the shortest ones.
+__device__ __forceinline__ int list_length(const int32_t* ctrl, int cls, int low)
 {
-    if (threadIdx.x == 0) *slot = (uint32_t)atomicAdd(ctrl + N_CLS + cls, 1);
-    __syncthreads();
-    int idx = __builtin_amdgcn_readfirstlane((int)*slot);
-    __syncthreads();  // slot may be rewritten by the next call
+    int n = 0;
+    for (int c = cls; c >= low; --c) n += as_constant(ctrl)[c];
+    return n;
+}
+
+__device__ __forceinline__ int list_entry(const int32_t* ctrl, const int32_t* order, int N,
+                                          int cls, int low, int idx)
+{
     for (int c = cls; c >= low; --c) {
         const int n = as_constant(ctrl)[c];
         if (idx < n) return as_constant(order)[(size_t)c * N + idx];
@@ -137,6 +177,15 @@ constexpr int POSC = BUCKET_CELLS;    // cells per position
 constexpr int PADB = WIDE_PAD_BYTES;  // bytes of F_INF in front of every copy
 constexpr int AD = 4;                 // accumulator dwords per lane per position
 constexpr int CAND_BUF = 512;         // entries of a row staged in LDS at a time
+// Staged entries (the form the sweep reads from LDS) are one dword: the cost in
+// the high half, and in the low half the shift in dwords plus SHIFT_BIAS, which
+// makes it unsigned (shifts reach from -2 * 16384 bytes to +3 copies).
+constexpr uint32_t SHIFT_BIAS = 8192;
+static_assert(4 * SHIFT_BIAS >= 2 * WIDE_MAX_CELLS, "the bias covers the longest shift down");
+static_assert(SHIFT_BIAS + 3 * (WIDE_PAD_BYTES + WIDE_MAX_CELLS * 2) / 4 < 65536,
+              "biased shifts fit sixteen bits");
+static_assert(4 * SHIFT_BIAS >= WIDE_PAD_BYTES + (WIDE_MAX_CELLS / BUCKET_CELLS - 1) * BUCKET_CELLS * 2,
+              "the bias covers the parking shift of the last position");
 static_assert(WIDE_CHUNK == 2 * POSC, "a wavefront holds two positions");
 static_assert(PADB == POSC * 2, "the pad is as long as one position");
 
@@ -144,20 +193,24 @@ template <int COPIES>
 struct Geo {
     static constexpr int ELT = COPIES == 4 ? 8 : 4;   // bytes per lane element
     static constexpr int NE = AD * 4 / ELT;           // lane elements per position
-    // byte offset (inside a copy) of a lane's first element of position pos
+    // byte offset (inside a copy) of a lane's first element of position pos,
+    // less the bias that staged entries carry in their shift
     static __device__ __forceinline__ uint32_t lane_byte(int pos, int lane)
     {
-        return (uint32_t)(PADB + ELT * (pos * (64 * NE) + lane));
+        return (uint32_t)(PADB + ELT * (pos * (64 * NE) + lane)) - 4u * SHIFT_BIAS;
     }
-    // added to lane_byte: lands the position's reads on the F_INF pad of copy 0
+    // a staged entry (cost 0) whose shift lands the position's reads on the F_INF
+    // pad of copy 0
     static __device__ __forceinline__ uint32_t park(int pos)
     {
-        return 0u - (uint32_t)(PADB + ELT * pos * (64 * NE));
+        return SHIFT_BIAS - (uint32_t)((PADB + ELT * pos * (64 * NE)) / 4);
     }
-    static __device__ __forceinline__ void read(uint32_t (&dst)[AD], const char* at)
+    // `at` is an LDS address (an integer, so that the lane's base and the start
+    // of the copies fold into one register outside the loop)
+    static __device__ __forceinline__ void read(uint32_t (&dst)[AD], uint32_t at)
     {
         if constexpr (COPIES == 4) {
-            const u32x2* src = reinterpret_cast<const u32x2*>(at);
+            const AS_LDS u32x2* src = (const AS_LDS u32x2*)(size_t)at;
 #pragma unroll
             for (int q = 0; q < NE; ++q) {
                 const u32x2 r = src[q * 64];
@@ -165,76 +218,82 @@ struct Geo {
                 dst[2 * q + 1] = r.y;
             }
         } else {
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(at);
+            const AS_LDS uint32_t* src = (const AS_LDS uint32_t*)(size_t)at;
 #pragma unroll
             for (int u = 0; u < NE; ++u) dst[u] = src[u * 64];
         }
     }
 };
 
-// Sweep entries [kb, ke) of the staged part of a bucket-ordered row over one
-// position.  `ent` points at the staged entries in LDS; every lane reads the
-// same entry (a broadcast), so shift and cost arrive in VGPRs without touching
-// the scalar unit.
+// Sweep the first ke staged entries of a bucket-ordered row over one position.
+// `ent` points at the staged entries in LDS; every lane reads the same words (a
+// broadcast), so shift and cost arrive in VGPRs without touching the scalar
+// unit, four entries per read.
 //
-// The loop is software-pipelined by hand: the row reads of entry k+1 are issued
-// before the arithmetic of entry k, into the other half of a double buffer, and
-// the entries themselves are fetched three ahead, so a wavefront always has reads
-// in flight while it works.  The scheduling barriers keep the compiler from
-// undoing that order.  In the last steps the entries at or beyond ke are
-// parked on the F_INF pad, where they change nothing.
-template <int COPIES>
-__device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, const u32x2* ent,
-                                      int kb, int ke, uint32_t byte_pos, uint32_t park)
-{
-    using G = Geo<COPIES>;
-    if (kb >= ke) return;
-    uint32_t buf[2][AD], bcost[2];
+// The loop is software-pipelined by hand: the row reads of entry k+D are issued
+// before the arithmetic of entry k, into a ring of D+1 buffers, and the entries
+// themselves are fetched one (D = 1) or two (D = 3) groups of four ahead, so a
+// wavefront always has reads in flight while it works.  The scheduling barriers
+// keep the compiler from undoing that order.  Entries at or beyond ke (the
+// rest of the row, or the padding behind it) are parked on the F_INF pad, where
+// they change nothing.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-    auto issue = [&](u32x2 en, bool live, int slot) {
-        bcost[slot] = en.y;
-        G::read(buf[slot], ldsb + (byte_pos + (live ? en.x : park)));
+template <int COPIES, int D>
+__device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, const uint32_t* ent,
+                                      int ke, uint32_t byte_pos, uint32_t park)
+{
+    static_assert(D == 1 || D == 3, "the buffer ring must divide the group of four");
+    using G = Geo<COPIES>;
+    if (ke <= 0) return;
+    constexpr int NQ = D == 1 ? 2 : 3;  // groups of entries held in registers
+    const uint32_t lane_base = lds_address(ldsb) + byte_pos;
+    const AS_LDS u32x4* const ent4 = (const AS_LDS u32x4*)(size_t)lds_address(ent);
+    uint32_t buf[D + 1][AD];
+    u32x4 q[NQ];
+
+    auto issue = [&](uint32_t en, int slot) {
+        G::read(buf[slot], add_dwords_lo(lane_base, en));
     };
-    auto consume = [&](int slot) {
-        const uint32_t c = bcost[slot];
+    auto consume = [&](uint32_t en, int slot) {
         uint32_t t[AD];
         // all the adds, then all the mins: no add feeds the instruction after it
 #pragma unroll
-        for (int u = 0; u < AD; ++u) t[u] = pk_add(buf[slot][u], c);
+        for (int u = 0; u < AD; ++u) t[u] = pk_add_hi(buf[slot][u], en);
 #pragma unroll
         for (int u = 0; u < AD; ++u) acc[u] = pk_min(acc[u], t[u]);
     };
 
-    // ring of four entries: while entry k is being relaxed, the row reads of k+1
-    // are in flight and entry k+3 is being fetched (the slot of entry k-1, whose
-    // cost was copied out when its reads were issued)
-    u32x2 e[4];
-    e[0] = ent[kb];
-    e[1] = ent[kb + 1];
-    e[2] = ent[kb + 2];
-    issue(e[0], true, 0);
-    int k0 = kb;
-    // groups of four whose entries and the one after them all lie inside [kb, ke)
-    for (; k0 + 5 <= ke; k0 += 4) {
+#pragma unroll
+    for (int r = 0; r < NQ - 1; ++r) q[r] = ent4[r];
+#pragma unroll
+    for (int z = 0; z < D; ++z) issue(z < ke ? q[0][z] : park, z);
+
+    // One group: entries k0 .. k0+3 are relaxed while the reads of k0+D .. k0+3+D
+    // are issued; `cur` is the register group that holds entries k0 .. k0+3.
+    auto group = [&](int k0, int cur, bool tail) {
+        q[(cur + NQ - 1) % NQ] = ent4[(k0 >> 2) + NQ - 1];
 #pragma unroll
         for (int z = 0; z < 4; ++z) {
-            e[(z + 3) & 3] = ent[k0 + z + 3];
-            issue(e[(z + 1) & 3], true, (z + 1) & 1);
+            const int x = z + D;
+            uint32_t en = x < 4 ? q[cur][x & 3] : q[(cur + 1) % NQ][x & 3];
+            if (tail) en = k0 + x < ke ? en : park;
+            issue(en, x % (D + 1));
             __builtin_amdgcn_sched_barrier(0);
-            consume(z & 1);
+            consume(q[cur][z], z % (D + 1));
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
-    // the rest: entries at or beyond ke are parked (k0 - kb is a multiple of
-    // four here, so the ring and the double buffer are back at slot 0)
-    for (; k0 < ke; k0 += 4) {
+    };
+
+    for (int k0 = 0; k0 < ke; k0 += 4 * NQ) {
 #pragma unroll
-        for (int z = 0; z < 4; ++z) {
-            e[(z + 3) & 3] = ent[k0 + z + 3];
-            issue(e[(z + 1) & 3], k0 + z + 1 < ke, (z + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
-            consume(z & 1);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int r = 0; r < NQ; ++r) {
+            const int k = k0 + 4 * r;
+            if (k >= ke) break;
+            if (k + 4 + D <= ke)
+                group(k, r, false);
+            else
+                group(k, r, true);
         }
     }
 }
@@ -328,17 +387,17 @@ __device__ __forceinline__ void publish_position(const uint32_t (&acc)[AD], char
 // staging buffer (loaded before a model's sweeps, stored after them).
 constexpr int PREFETCH = 4;  // entries per thread
 
-// An entry as the sweep wants it in LDS: the cost replicated into both halves
-// of the second word (the operand of the packed add), the index dropped.
-__device__ __forceinline__ StepEntry staged(StepEntry se)
+// An entry as the sweep wants it in LDS (see SHIFT_BIAS); the index is dropped.
+// (The padding entries behind a row are only ever fetched, never relaxed: the
+// sweep parks whatever lies at or beyond its end.)
+__device__ __forceinline__ uint32_t staged(StepEntry se)
 {
-    se.ck = (se.ck & 0xFFFFu) * 0x10001u;
-    return se;
+    return (se.ck << 16) | (((uint32_t)((int32_t)se.shift >> 2) + SHIFT_BIAS) & 0xFFFFu);
 }
 
 struct RowPrefetch {
-    StepEntry e[PREFETCH];
-    int cnt;  // entries of the row to stage (at most CAND_BUF); 16 zero entries follow
+    uint32_t e[PREFETCH];  // staged form
+    int cnt;  // entries of the row to stage (at most CAND_BUF); 16 padding entries follow
 };
 
 __device__ __forceinline__ void prefetch_row(RowPrefetch& pf, const StepEntry* grow, int cnt)
@@ -347,19 +406,21 @@ __device__ __forceinline__ void prefetch_row(RowPrefetch& pf, const StepEntry* g
 #pragma unroll
     for (int j = 0; j < PREFETCH; ++j) {
         const int x = (int)threadIdx.x + j * (int)blockDim.x;
-        pf.e[j].shift = 0u;
-        pf.e[j].ck = 0u;
-        if (x < cnt) pf.e[j] = grow[x];
+        StepEntry se;
+        se.shift = 0u;
+        se.ck = 0u;
+        if (x < cnt) se = grow[x];
+        pf.e[j] = staged(se);
     }
 }
 
 __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntry* grow,
-                                           StepEntry* cbuf)
+                                           uint32_t* cbuf)
 {
 #pragma unroll
     for (int j = 0; j < PREFETCH; ++j) {
         const int x = (int)threadIdx.x + j * (int)blockDim.x;
-        if (x < pf.cnt + 16) cbuf[x] = staged(pf.e[j]);
+        if (x < pf.cnt + 16) cbuf[x] = pf.e[j];
     }
     // whatever the registers did not cover
     for (int x = (int)threadIdx.x + PREFETCH * (int)blockDim.x; x < pf.cnt + 16;
@@ -390,13 +451,14 @@ __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntr
 // dealt-out form, which costs the longest classes a resident workgroup when the
 // sweeps are long, hence the two forms.
 template <int COPIES, bool FIXED>
-__global__ __launch_bounds__(1024) void k2_minplus_wide(
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
     int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int N, int S, int Kp, int nbs,
     int row_stride, int cls, int low_cls, int cand_buf)
 {
     using G = Geo<COPIES>;
+    constexpr int DEPTH = 1;
     extern __shared__ uint32_t lds[];
     const int CSB = wide_copy_bytes(CLS_WAVES[cls]);  // bytes per copy: pad + the longest row
     const int SETB = COPIES * CSB;                    // bytes of all copies
@@ -405,15 +467,18 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
     // counter, then the staging buffer for cand_buf (+16) candidate entries
     volatile uint32_t* const slot = reinterpret_cast<volatile uint32_t*>(ldsb + SETB);
     int* const next_pos = reinterpret_cast<int*>(ldsb + SETB + 4);
-    StepEntry* const cbuf = reinterpret_cast<StepEntry*>(ldsb + SETB + 16);
-    const u32x2* const ent = reinterpret_cast<const u32x2*>(cbuf);
+    uint32_t* const cbuf = reinterpret_cast<uint32_t*>(ldsb + SETB + 16);
+    const uint32_t* const ent = cbuf;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
 
+    const int count = list_length(ctrl, cls, low_cls);
+    int idx = -1;
     for (;;) {
-        const int i = next_instance_of(slot, ctrl, order, N, cls, low_cls);
-        if (i < 0) break;
+        idx = next_index(slot, ctrl + N_CLS + cls, count, idx);
+        if (idx < 0) break;
+        const int i = list_entry(ctrl, order, N, cls, low_cls, idx);
         const int T = as_constant(tmeta)[i];
         const int npos = (T + POSC) / POSC;  // positions that hold cells 0..T
 
@@ -463,14 +528,14 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                 if (p_hi >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
-                    sweep<COPIES>(r_hi, ldsb, ent, 0, bc[p_hi + 1], G::lane_byte(p_hi, lane),
+                    sweep<COPIES, DEPTH>(r_hi, ldsb, ent, bc[p_hi + 1], G::lane_byte(p_hi, lane),
                                   G::park(p_hi));
                     clamp_position(r_hi);
                 }
                 if (p_lo >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_lo[u] = 0xFFFFFFFFu;
-                    sweep<COPIES>(r_lo, ldsb, ent, 0, bc[p_lo + 1], G::lane_byte(p_lo, lane),
+                    sweep<COPIES, DEPTH>(r_lo, ldsb, ent, bc[p_lo + 1], G::lane_byte(p_lo, lane),
                                   G::park(p_lo));
                     clamp_position(r_lo);
                 }
@@ -484,7 +549,7 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                     uint32_t acc[AD];
 #pragma unroll
                     for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
-                    sweep<COPIES>(acc, ldsb, ent, 0, bc[p + 1], G::lane_byte(p, lane), G::park(p));
+                    sweep<COPIES, DEPTH>(acc, ldsb, ent, bc[p + 1], G::lane_byte(p, lane), G::park(p));
                     finish_position<COPIES>(acc, out, p, lane, T);
                 }
             } else {
@@ -529,7 +594,7 @@ __global__ __launch_bounds__(1024) void k2_minplus_wide(
                                                    : F_INF2;
                             }
                         }
-                        sweep<COPIES>(acc, ldsb, ent, 0, ke, G::lane_byte(p0, lane), G::park(p0));
+                        sweep<COPIES, DEPTH>(acc, ldsb, ent, ke, G::lane_byte(p0, lane), G::park(p0));
                         finish_position<COPIES>(acc, out, p0, lane, T);
                     }
                 }
@@ -596,9 +661,11 @@ __global__ __launch_bounds__(NAR_NW * 64) void k2_minplus_narrow(
     const int32_t* const my_order = order + (size_t)NARROW_CLS * N;
     const int last_cell = 2 * (j0 + NAR_CHUNK) - 1;
 
+    int idx = -1;
     for (;;) {
-        const int i = next_instance(slot, ctrl + N_CLS + NARROW_CLS, count, my_order);
-        if (i < 0) break;
+        idx = next_index(slot, ctrl + N_CLS + NARROW_CLS, count, idx);
+        if (idx < 0) break;
+        const int i = as_constant(my_order)[idx];
         const int T = as_constant(tmeta)[i];
         const int ndw = (T >> 1) + 1;  // dwords that hold cells 0..T
         const bool active = j0 < ndw;
@@ -671,7 +738,7 @@ constexpr size_t LDS_PER_CU = 160 * 1024;
 
 inline size_t wide_lds_bytes(int copies, int waves, int cand_buf)
 {
-    return (size_t)copies * wide_copy_bytes(waves) + 16 + (cand_buf + 16) * sizeof(StepEntry);
+    return (size_t)copies * wide_copy_bytes(waves) + 16 + (cand_buf + 16) * sizeof(uint32_t);
 }
 
 inline int wide_groups_per_cu(int copies, int waves, int cand_buf)

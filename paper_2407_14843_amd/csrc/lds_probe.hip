@@ -152,6 +152,16 @@ __global__ __launch_bounds__(256) void k_valu64_probe(uint32_t* __restrict__ sin
                     asm volatile("v_add_f64 %0, %0, %1 clamp" : "+v"(r[j]) : "v"(c));
                 if constexpr (OP == 20)
                     asm volatile("v_cmp_ge_f64_e64 %0, %1, %2" : "=s"(mask) : "v"(r[j]), "v"(c));
+                if constexpr (OP == 21)
+                    asm volatile("v_mad_u32_u16 %0, %0, 4, %1" : "+v"(u[j]) : "v"(seed));
+                if constexpr (OP == 22)
+                    asm volatile("v_pk_add_u16 %0, %0, %1 op_sel:[0,1] op_sel_hi:[1,1]"
+                                 : "+v"(u[j]) : "v"(seed));
+                if constexpr (OP == 23)
+                    asm volatile("v_lshl_add_u32 %0, %0, 2, %1" : "+v"(u[j]) : "v"(seed));
+                if constexpr (OP == 24)
+                    asm volatile("v_add_u32_sdwa %0, %0, %1 dst_sel:DWORD dst_unused:UNUSED_PAD "
+                                 "src0_sel:WORD_0 src1_sel:DWORD" : "+v"(u[j]) : "v"(seed));
             }
     }
     double x = 0;
@@ -216,6 +226,7 @@ hipError_t launch_valu_probe(int op, int iters, int blocks, uint32_t* sink, hipS
     VALU64_CASE(6) VALU64_CASE(7) VALU64_CASE(8) VALU64_CASE(9) VALU64_CASE(10) VALU64_CASE(11)
     VALU64_CASE(12) VALU64_CASE(13) VALU64_CASE(14) VALU64_CASE(15) VALU64_CASE(16)
     VALU64_CASE(17) VALU64_CASE(18) VALU64_CASE(19) VALU64_CASE(20)
+    VALU64_CASE(21) VALU64_CASE(22) VALU64_CASE(23) VALU64_CASE(24)
 #undef VALU64_CASE
     return hipErrorInvalidValue;
 }
