@@ -445,11 +445,17 @@ __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntr
 // FIXED (used when dominated candidates were pruned, so that a position is a
 // handful of entries and the round trip dominates): every wavefront owns the
 // w-th position from the top and, where the row has more positions than the
-// workgroup has wavefronts, the w-th from the bottom, keeps both results in
-// registers and writes them into the LDS copies itself after the barrier; the
-// HBM row is written for stage 3 only.  It needs more registers than the
-// dealt-out form, which costs the longest classes a resident workgroup when the
-// sweeps are long, hence the two forms.
+// workgroup has wavefronts, one of the rest, dealt so that the wavefront with
+// the cheapest first position gets the dearest second one; it keeps both
+// results in registers and writes them into the LDS copies itself after the
+// barrier; the HBM row is written for stage 3 only.  It needs more registers
+// than the dealt-out form (a few are spilled to keep eight wavefronts per SIMD),
+// and measured on dense rows it is slower than that form on four of five
+// workloads, hence the two forms.
+//
+// Both forms are compiled for eight wavefronts per SIMD (64 VGPRs): the LDS
+// footprints of the work classes are sized for 32 resident wavefronts per
+// compute unit, which a few registers more would silently cut to 28.
 template <int COPIES, bool FIXED>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
@@ -521,7 +527,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
             const int nw = (int)blockDim.x >> 6;
             const int p_hi = npos - 1 - w;
-            const int p_lo = w < npos - nw ? w : -1;
+            const int p_lo = npos - 2 * nw + w;  // negative: none
             uint32_t r_hi[AD], r_lo[AD];
             const bool in_regs = FIXED && n_all <= cand_buf;
             if (in_regs) {
