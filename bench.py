@@ -166,6 +166,26 @@ def _time_calls(fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def two_streams(themis, wl, idx, steps, warmup):
+    """The same steps issued alternately on two streams, each with its own batch
+    object and workspace (what a caller with several batches in flight does):
+    the thinning end of one solve overlaps the start of the next."""
+    import torch
+    w = wl.workload(idx)
+    bs = [themis.DeviceBatch(w, "cuda:0") for _ in range(2)]
+    ss = [torch.cuda.Stream() for _ in range(2)]
+    torch.cuda.synchronize()
+    for k in range(2 * warmup):
+        bs[k % 2].solve(ss[k % 2])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        bs[k % 2].solve(ss[k % 2])
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    return {"ms_per_step": ms, "solves_per_s": w.n_inst / (ms * 1e-3)}
+
+
 def next_rows(themis, wl, steps, warmup):
     """Timings of the entry points beyond the two plain solves, each on a seeded
     workload of the shapes above: horizontal-only solve and stability test
@@ -380,6 +400,8 @@ def main():
             "traffic": None,
         },
     }
+    if a.workload != 4:
+        line["two_streams"] = two_streams(themis, wl, a.workload, a.steps, a.warmup)
     # the same solve with dominated candidates dropped before the recurrence: same
     # answers, a fraction of the relaxations; reported beside the dense figures
     if not a.prune and not a.no_pruned:

@@ -319,6 +319,25 @@ def test_non_default_stream(T, oracle):
     assert_same(b.results(), oracle.solve(w))
 
 
+def test_two_solves_in_flight_on_two_streams(T, oracle):
+    """Two batches of different shape, each with its own workspace, solved
+    concurrently on two streams several times over: nothing in the library is
+    shared between calls except read-only tables."""
+    import torch
+    wa, wb = wl.workload(1, 600), wl.workload(2, 300)
+    want_a, want_b = oracle.solve(wa, threads=8), oracle.solve(wb, threads=8)
+    print("[case] two streams", wa.name, wb.name, flush=True)
+    ba, bb = T.DeviceBatch(wa), T.DeviceBatch(wb, prune=1)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(4):
+        ba.solve(stream=sa)
+        bb.solve(stream=sb)
+    torch.cuda.synchronize()
+    assert_same(ba.results(), want_a)
+    assert_same(bb.results(), want_b)
+
+
 def test_argument_errors_launch_nothing(T):
     import ctypes
     w = wl.workload(0, 8)
