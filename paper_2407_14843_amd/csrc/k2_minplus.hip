@@ -13,9 +13,10 @@
 //
 // Mapping.  One workgroup per instance.  Lanes run over t and the candidate
 // loop is wave-uniform: a candidate contributes f[s+1] shifted by lt, a
-// unit-stride LDS read.  The row's entries (shift, cost) are staged in LDS once
-// per model and every lane reads the same entry (a broadcast), so they arrive in
-// VGPRs in order with the row reads.  There is no cross-lane traffic and no
+// unit-stride LDS read.  The row's entries (shift and cost packed into one dword)
+// are staged in LDS once per model and every lane reads the same words (a
+// broadcast, four entries at a time), so they arrive in VGPRs in order with the
+// row reads.  There is no cross-lane traffic and no
 // argmin bookkeeping in the loop: only f is kept, and stage 3 recovers the
 // argmin from the stored rows.
 //
@@ -26,8 +27,8 @@
 // previous row is kept in LDS once per residue of the shift: copy m is the row
 // shifted by m cells, and a candidate reads the copy whose residue fits, always
 // aligned.  Two copies with 32-bit reads (lt mod 2) are the default; four copies
-// with 64-bit reads ((-lt) mod 4) deliver twice the bytes per clock but double
-// the LDS footprint, and the resident wavefronts that costs weigh more.  Rows of
+// with 64-bit reads ((-lt) mod 4) halve the LDS instructions but double the LDS
+// footprint, and the resident wavefronts that costs weigh more (measured).  Rows of
 // more than 16384 cells go to the narrow kernel (two copies, static chunks).
 // New values stay in registers while the old row is being read.
 //
@@ -55,7 +56,6 @@ namespace {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
 {
