@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     StepEntry* __restrict__ step_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
     uint32_t S, uint32_t K, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick,
     double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs, int copies_mask,
-    int merge_to, int sparse, uint32_t c_all, uint32_t cs, uint32_t prune_sh,
+    uint64_t class_map, int sparse, uint32_t c_all, uint32_t cs, uint32_t prune_sh,
     uint32_t prune_bins, uint32_t split)
 {
     extern __shared__ uint32_t smem[];
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     __syncthreads();
     if (live) {
         // the LDS geometry the min-plus stage will use for this instance
-        const int cls = T >= 0 ? effective_class(T, merge_to) : 0;
+        const int cls = T >= 0 ? effective_class(T, class_map) : 0;
         // wide_shift() / narrow_shift() in one branch-free form:
         //   shift = base + ((-lt) & cm) * step - (((lt + add) >> sh) << (sh + 1))
         uint32_t cm, sh, add, step, base;
@@ -360,7 +360,7 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
                                                 int32_t* __restrict__ lt,
                                                 int32_t* __restrict__ cost, uint32_t rows,
                                                 uint32_t S, uint32_t K, uint32_t Kp, uint32_t nb,
-                                                uint32_t nbs, int copies_mask, int merge_to)
+                                                uint32_t nbs, int copies_mask, uint64_t class_map)
 {
     uint32_t g = blockIdx.x * 256u + threadIdx.x;
     if (g >= rows * Kp) return;
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
     if (k >= K) return;  // padding entry
     const int32_t T = tmeta[row / S];
     const bool none = T < 0 || e >= bcum[(size_t)row * nbs + nb];
-    lt[(size_t)row * K + k] = none ? -1 : (int32_t)lt_of_entry(se.shift, T, merge_to, copies_mask);
+    lt[(size_t)row * K + k] = none ? -1 : (int32_t)lt_of_entry(se.shift, T, class_map, copies_mask);
     cost[(size_t)row * K + k] = none ? -1 : (int32_t)(se.ck & 0xFFFFu);
 }
 
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
                                                      unsigned long long* __restrict__ out,
                                                      uint32_t N, uint32_t S, uint32_t Kp,
                                                      uint32_t nb, uint32_t nbs, int copies_mask,
-                                                     int merge_to)
+                                                     uint64_t class_map)
 {
     __shared__ unsigned long long part[256];
     unsigned long long acc = 0;
@@ -393,7 +393,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
             const uint32_t n = bcum[row * nbs + nb];
             for (uint32_t e = threadIdx.x; e < n; e += 256)
                 acc += (unsigned long long)(T + 1) -
-                       lt_of_entry(step_tab[row * Kp + e].shift, T, merge_to, copies_mask);
+                       lt_of_entry(step_tab[row * Kp + e].shift, T, class_map, copies_mask);
         }
     }
     part[threadIdx.x] = acc;
@@ -465,7 +465,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                            (uint32_t)L.S, (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.c_max,
                            (uint32_t)p.r_max, (uint32_t)p.tick_us,
                            (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
-                           (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.merge_to,
+                           (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.class_map,
                            opts.sparse, (uint32_t)opts.c_all, cs, prune_sh, prune_bins, split);
         return hipGetLastError();
     };
@@ -492,7 +492,7 @@ hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), d_lt, d_cost, rows, (uint32_t)L.S,
                        (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs,
-                       plan.copies_mask, plan.merge_to);
+                       plan.copies_mask, plan.class_map);
     return hipGetLastError();
 }
 
@@ -508,7 +508,7 @@ hipError_t launch_count_relaxations(const Layout& L, const char* ws,
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), d_count, (uint32_t)L.N, (uint32_t)L.S,
                        (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask,
-                       plan.merge_to);
+                       plan.class_map);
     return hipGetLastError();
 }
 

@@ -43,12 +43,13 @@
 // doubles as the harmless target of the entries that pad a group of four beyond
 // the prefix.
 //
-// Scheduling.  Instances were grouped by row length in stage 1.  Every group is
-// launched once, with a workgroup of exactly the wavefronts its rows need and
-// just enough workgroups to fill the chip; each workgroup starts on the list
-// entry of its own index and then pulls further ones through an atomic cursor
-// until the list is exhausted.  A small batch is served by one launch that
-// walks all the lists, longest rows first.
+// Scheduling.  Instances were listed by row length (work class) in stage 1.  A
+// launch serves a group of classes with the geometry of the group's longest
+// rows: a workgroup of exactly the wavefronts those need, and just enough
+// workgroups to fill the chip.  Each workgroup starts on the list entry of its
+// own index and then pulls further ones through an atomic cursor until the
+// lists are exhausted, longest rows first, so the launch ends on the short
+// ones.  Usually one launch serves every class; see make_plan().
 #include "themis_internal.h"
 
 namespace themis {
@@ -783,12 +784,28 @@ MinplusPlan make_plan(const Layout& L_)
     pl.top = class_of_budget(L_.t_max);
     pl.top_wide = pl.top == NARROW_CLS ? N_WIDE_CLS - 1 : pl.top;
     pl.copies_mask = wide_copies_mask();
-    // few instances: one launch with the top class's geometry for all of them
-    const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
-    const long long resident =
-        (long long)pl.cus * wide_groups_per_cu(class_copies(pl.top_wide, pl.copies_mask),
-                                               CLS_WAVES[pl.top_wide], cand_buf);
-    pl.merge_to = L_.N <= 4 * resident ? pl.top_wide : 0;
+    // Heads of the class groups (bit c set = class c has a launch of its own).
+    // One launch for everything is best until the batch is large and its longest
+    // rows need twelve wavefronts or more; then the rows of up to eight chunks get
+    // a launch with the eight-wavefront geometry (four workgroups per compute
+    // unit), where short rows leave fewer wavefronts idle.  Measured: more heads
+    // than that lose to the starts and thinning ends of the extra launches.
+    unsigned heads = 1u << pl.top_wide;
+    constexpr int SECOND_HEAD = 5;  // CLS_WAVES[5] == 8
+    static_assert(CLS_WAVES[SECOND_HEAD] == 8, "the second head is the eight-wavefront class");
+    {
+        const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
+        const long long resident =
+            (long long)pl.cus * wide_groups_per_cu(class_copies(pl.top_wide, pl.copies_mask),
+                                                   CLS_WAVES[pl.top_wide], cand_buf);
+        if (CLS_WAVES[pl.top_wide] >= 12 && L_.N >= 16 * resident) heads |= 1u << SECOND_HEAD;
+    }
+    pl.class_map = 0;
+    int head = pl.top_wide;
+    for (int c = pl.top_wide; c >= 0; --c) {
+        if ((heads >> c) & 1u) head = c;
+        pl.class_map |= (uint64_t)head << (4 * c);
+    }
     return pl;
 }
 
@@ -814,9 +831,10 @@ hipError_t launch_minplus(const themis_problem_t& p, const Layout& L_, char* ws,
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    for (int c = pl.top_wide; c >= pl.merge_to; --c) {
-        // a merged launch also serves every class below it
-        const int low = c == pl.merge_to ? 0 : c;
+    for (int c = pl.top_wide; c >= 0; --c) {
+        if (head_of_class(c, pl.class_map) != c) continue;  // served by the launch of its head
+        int low = c;
+        while (low > 0 && head_of_class(low - 1, pl.class_map) == c) --low;
         if (class_copies(c, pl.copies_mask) == 2)
             e = fixed ? launch_wide_class<2, true>(L_, ws, st, c, low, pl.cus)
                       : launch_wide_class<2, false>(L_, ws, st, c, low, pl.cus);

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum, const int32_t* __restrict__ tmeta,
     const uint16_t* __restrict__ frow, int32_t* __restrict__ status,
     int32_t* __restrict__ cost_out, int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg,
-    BatchList bl, int N, int S, int Kp, int nbs, int row_stride, int copies_mask, int merge_to,
+    BatchList bl, int N, int S, int Kp, int nbs, int row_stride, int copies_mask, uint64_t class_map,
     int sparse)
 {
     const int lane = threadIdx.x & 63;
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
             const int e = e0 + lane;
             if (e < n) {
                 const StepEntry se = sp[e];  // every entry below n is feasible
-                const int lt = (int)lt_of_entry(se.shift, T, merge_to, copies_mask);
+                const int lt = (int)lt_of_entry(se.shift, T, class_map, copies_mask);
                 if (lt <= t) {
                     const uint32_t co = se.ck & 0xFFFFu;
                     const uint32_t rest = (s + 1 < S) ? (uint32_t)next[t - lt] : 0u;
@@ -141,7 +141,7 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
                        d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.Kp, L.nbs, L.row_stride,
-                       plan.copies_mask, plan.merge_to, opts.sparse);
+                       plan.copies_mask, plan.class_map, opts.sparse);
     return hipGetLastError();
 }
 

@@ -118,13 +118,18 @@ __host__ __device__ inline uint32_t narrow_lt_of_shift(uint32_t shift)
                              : 2u * (uint32_t)(NAR_COPY_DW + NAR_CHUNK_DW - 1 - x) + 1u;
 }
 
-// With few instances, one launch per class leaves the chip mostly idle and
-// pays a launch and a tail per class; then every wide class up to merge_to is
-// served by class merge_to's launch (its geometry fits all shorter rows).
-__host__ __device__ inline int effective_class(int T, int merge_to)
+// One launch per class pays a start and a thinning end per class, so classes
+// are served in groups: the launch of a group's highest class (the "head", whose
+// geometry fits every shorter row) also serves the classes below it down to the
+// next head.  class_map holds, four bits per wide class, the head that serves it.
+__host__ __device__ inline int head_of_class(int c, uint64_t class_map)
 {
-    const int c = class_of_budget(T);
-    return (c != NARROW_CLS && c < merge_to) ? merge_to : c;
+    return c == NARROW_CLS ? c : (int)((class_map >> (4 * c)) & 15u);
+}
+
+__host__ __device__ inline int effective_class(int T, uint64_t class_map)
+{
+    return head_of_class(class_of_budget(T), class_map);
 }
 
 struct Layout;
@@ -132,7 +137,7 @@ struct MinplusPlan {
     int cus;          // compute units of the current device
     int top;          // highest class any instance can be in
     int top_wide;     // highest wide class in use
-    int merge_to;     // see effective_class(); 0 = nothing merged
+    uint64_t class_map;  // see head_of_class()
     int copies_mask;  // see wide_copies_mask()
 };
 MinplusPlan make_plan(const Layout& L);
@@ -203,10 +208,10 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
 hipError_t launch_minplus(const themis_problem_t& p, const Layout& L, char* ws,
                           hipStream_t st);
 // lt of an entry of an instance with budget T (see StepEntry)
-__host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, int merge_to,
+__host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, uint64_t class_map,
                                                 int copies_mask)
 {
-    const int cls = effective_class(T, merge_to);
+    const int cls = effective_class(T, class_map);
     if (cls == NARROW_CLS) return narrow_lt_of_shift(shift);
     return wide_lt_of_shift(shift, class_copies(cls, copies_mask),
                             wide_copy_bytes(CLS_WAVES[cls]));
