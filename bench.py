@@ -31,7 +31,7 @@ LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {"w1-joint-4096x5": 137424576, "w3-joint-65536x8": 13269079769}
+K2_HBM_TRAFFIC = {"w1-joint-4096x5": 137453167, "w3-joint-65536x8": 13138039197}
 
 
 def _events(n):
@@ -333,6 +333,8 @@ def main():
     ap.add_argument("--no-result-copy", action="store_true",
                     help="skip the extra leg that repeats the steps with the results copied to "
                          "the host (keeps a profiler's kernel counts to the timed steps)")
+    ap.add_argument("--no-two-streams", action="store_true",
+                    help="skip the leg that issues the steps on two streams")
     ap.add_argument("--no-pruned", action="store_true",
                     help="skip the extra leg that times the pruned solve beside the dense one")
     ap.add_argument("--copy-calib", action="store_true",
@@ -404,7 +406,7 @@ def main():
             "traffic": None,
         },
     }
-    if a.workload != 4:
+    if a.workload != 4 and not a.no_two_streams:
         line["two_streams"] = two_streams(themis, wl, a.workload, a.steps, a.warmup)
     # the same solve with dominated candidates dropped before the recurrence: same
     # answers, a fraction of the relaxations; reported beside the dense figures
