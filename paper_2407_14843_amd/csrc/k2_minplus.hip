@@ -208,12 +208,14 @@ struct Geo {
     }
     // `at` is an LDS address (an integer, so that the lane's base and the start
     // of the copies fold into one register outside the loop)
+    // reads the first NEA of the lane's NE elements
+    template <int NEA>
     static __device__ __forceinline__ void read(uint32_t (&dst)[AD], uint32_t at)
     {
         if constexpr (COPIES == 4) {
             const AS_LDS u32x2* src = (const AS_LDS u32x2*)(size_t)at;
 #pragma unroll
-            for (int q = 0; q < NE; ++q) {
+            for (int q = 0; q < NEA; ++q) {
                 const u32x2 r = src[q * 64];
                 dst[2 * q] = r.x;
                 dst[2 * q + 1] = r.y;
@@ -221,8 +223,16 @@ struct Geo {
         } else {
             const AS_LDS uint32_t* src = (const AS_LDS uint32_t*)(size_t)at;
 #pragma unroll
-            for (int u = 0; u < NE; ++u) dst[u] = src[u * 64];
+            for (int u = 0; u < NEA; ++u) dst[u] = src[u * 64];
         }
+    }
+    // Lane elements of position pos that hold any cell <= T (pos is one of the
+    // row's positions, so at least one does): element q starts 64 * ELT / 2 cells
+    // after element q - 1.
+    static __device__ __forceinline__ int live_elements(int pos, int T)
+    {
+        const int n = (T - pos * POSC) / (64 * (ELT / 2)) + 1;
+        return n < NE ? n : NE;
     }
 };
 
@@ -240,12 +250,13 @@ struct Geo {
 // they change nothing.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int COPIES, int D>
+template <int COPIES, int D, int NEA = Geo<COPIES>::NE>
 __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, const uint32_t* ent,
                                       int ke, uint32_t byte_pos, uint32_t park)
 {
     static_assert(D == 1 || D == 3, "the buffer ring must divide the group of four");
     using G = Geo<COPIES>;
+    constexpr int ADA = NEA * (G::ELT / 4);  // accumulator dwords in use
     if (ke <= 0) return;
     constexpr int NQ = D == 1 ? 2 : 3;  // groups of entries held in registers
     const uint32_t lane_base = lds_address(ldsb) + byte_pos;
@@ -254,15 +265,15 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
     u32x4 q[NQ];
 
     auto issue = [&](uint32_t en, int slot) {
-        G::read(buf[slot], add_dwords_lo(lane_base, en));
+        G::template read<NEA>(buf[slot], add_dwords_lo(lane_base, en));
     };
     auto consume = [&](uint32_t en, int slot) {
         uint32_t t[AD];
         // all the adds, then all the mins: no add feeds the instruction after it
 #pragma unroll
-        for (int u = 0; u < AD; ++u) t[u] = pk_add_hi(buf[slot][u], en);
+        for (int u = 0; u < ADA; ++u) t[u] = pk_add_hi(buf[slot][u], en);
 #pragma unroll
-        for (int u = 0; u < AD; ++u) acc[u] = pk_min(acc[u], t[u]);
+        for (int u = 0; u < ADA; ++u) acc[u] = pk_min(acc[u], t[u]);
     };
 
 #pragma unroll
@@ -296,6 +307,31 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
             else
                 group(k, r, true);
         }
+    }
+}
+
+// The same for a position of which only the first `nea` lane elements hold
+// cells of the row (the top position of a row whose length is not a multiple of
+// the position size): the elements beyond T are neither read nor relaxed.  The
+// top position is the one every entry reaches, so on short rows this is a
+// sizeable part of all the work.
+template <int COPIES, int D>
+__device__ __forceinline__ void sweep_live(uint32_t (&acc)[AD], const char* ldsb,
+                                           const uint32_t* ent, int ke, uint32_t byte_pos,
+                                           uint32_t park, int nea)
+{
+    using G = Geo<COPIES>;
+    if (nea >= G::NE) {
+        sweep<COPIES, D>(acc, ldsb, ent, ke, byte_pos, park);
+    } else if constexpr (G::NE == 2) {
+        sweep<COPIES, D, 1>(acc, ldsb, ent, ke, byte_pos, park);
+    } else {
+        if (nea == 1)
+            sweep<COPIES, D, 1>(acc, ldsb, ent, ke, byte_pos, park);
+        else if (nea == 2)
+            sweep<COPIES, D, 2>(acc, ldsb, ent, ke, byte_pos, park);
+        else
+            sweep<COPIES, D, 3>(acc, ldsb, ent, ke, byte_pos, park);
     }
 }
 
@@ -535,8 +571,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 if (p_hi >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
-                    sweep<COPIES, DEPTH>(r_hi, ldsb, ent, bc[p_hi + 1], G::lane_byte(p_hi, lane),
-                                  G::park(p_hi));
+                    sweep_live<COPIES, DEPTH>(r_hi, ldsb, ent, bc[p_hi + 1], G::lane_byte(p_hi, lane),
+                                              G::park(p_hi), G::live_elements(p_hi, T));
                     clamp_position(r_hi);
                 }
                 if (p_lo >= 0) {
@@ -556,7 +592,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                     uint32_t acc[AD];
 #pragma unroll
                     for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
-                    sweep<COPIES, DEPTH>(acc, ldsb, ent, bc[p + 1], G::lane_byte(p, lane), G::park(p));
+                    sweep_live<COPIES, DEPTH>(acc, ldsb, ent, bc[p + 1], G::lane_byte(p, lane),
+                                              G::park(p), G::live_elements(p, T));
                     finish_position<COPIES>(acc, out, p, lane, T);
                 }
             } else {
