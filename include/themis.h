@@ -317,7 +317,11 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
  * Number of min-plus relaxations stage 2 executes for the tables currently
  * in the workspace, summed over all instances, written to d_count[0]
  * (uint64): for every valid instance, model and feasible candidate,
- * T + 1 - lt.  For throughput accounting only.
+ * T + 1 - lt, except for the model the recurrence starts with (the last of
+ * the pipeline), whose row is a running minimum over its candidates and takes
+ * no relaxations (rows of more than 16384 cells and pruned problems
+ * excepted: there it is swept like the others).  For throughput accounting
+ * only.
  */
 int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
                              size_t workspace_bytes, unsigned long long *d_count,

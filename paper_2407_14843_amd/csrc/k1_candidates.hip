@@ -374,21 +374,25 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
     cost[(size_t)row * K + k] = none ? -1 : (int32_t)(se.ck & 0xFFFFu);
 }
 
-// Sum over valid instances, models and feasible candidates of (T + 1 - lt).
+// Sum over valid instances, models and feasible candidates of (T + 1 - lt): the
+// relaxations stage 2 executes.  The model it handles first (s = S-1) is left
+// out where the wide kernel serves the instance and nothing is pruned: it then
+// builds that row with a scatter and a scan, not with relaxations.
 __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict__ step_tab,
                                                      const uint16_t* __restrict__ bcum,
                                                      const int32_t* __restrict__ tmeta,
                                                      unsigned long long* __restrict__ out,
                                                      uint32_t N, uint32_t S, uint32_t Kp,
                                                      uint32_t nb, uint32_t nbs, int copies_mask,
-                                                     uint64_t class_map)
+                                                     uint64_t class_map, int all_swept)
 {
     __shared__ unsigned long long part[256];
     unsigned long long acc = 0;
     for (uint32_t i = blockIdx.x; i < N; i += gridDim.x) {
         const int32_t T = tmeta[i];
         if (T < 0) continue;
-        for (uint32_t s = 0; s < S; ++s) {
+        const uint32_t swept = (all_swept || class_of_budget(T) == NARROW_CLS) ? S : S - 1;
+        for (uint32_t s = 0; s < swept; ++s) {
             const size_t row = (size_t)i * S + s;
             const uint32_t n = bcum[row * nbs + nb];
             for (uint32_t e = threadIdx.x; e < n; e += 256)
@@ -496,7 +500,7 @@ hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_
     return hipGetLastError();
 }
 
-hipError_t launch_count_relaxations(const Layout& L, const char* ws,
+hipError_t launch_count_relaxations(const themis_problem_t& p, const Layout& L, const char* ws,
                                     unsigned long long* d_count, hipStream_t st)
 {
     const MinplusPlan plan = make_plan(L);
@@ -508,7 +512,7 @@ hipError_t launch_count_relaxations(const Layout& L, const char* ws,
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), d_count, (uint32_t)L.N, (uint32_t)L.S,
                        (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask,
-                       plan.class_map);
+                       plan.class_map, p.prune != THEMIS_PRUNE_NONE);
     return hipGetLastError();
 }
 

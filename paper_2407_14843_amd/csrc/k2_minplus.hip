@@ -525,16 +525,16 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         const int T = as_constant(tmeta)[i];
         const int npos = (T + POSC) / POSC;  // positions that hold cells 0..T
 
-        // rows before the first model: cells t < 0 are F_INF, cells t >= 0 are 0
-        for (int x = tid; x < (PADB + npos * POSC * 2) / 4; x += (int)blockDim.x) {
+        if constexpr (FIXED) {
+            // rows before the first model: cells t < 0 are F_INF, cells t >= 0 are 0
+            for (int x = tid; x < (PADB + npos * POSC * 2) / 4; x += (int)blockDim.x) {
 #pragma unroll
-            for (int m = 0; m < COPIES; ++m) {
-                const uint32_t h0 = 2 * x < PADB / 2 - m ? F_INF : 0u;
-                const uint32_t h1 = 2 * x + 1 < PADB / 2 - m ? F_INF : 0u;
-                lds[m * (CSB / 4) + x] = h0 | (h1 << 16);
+                for (int m = 0; m < COPIES; ++m) {
+                    const uint32_t h0 = 2 * x < PADB / 2 - m ? F_INF : 0u;
+                    const uint32_t h1 = 2 * x + 1 < PADB / 2 - m ? F_INF : 0u;
+                    lds[m * (CSB / 4) + x] = h0 | (h1 << 16);
+                }
             }
-        }
-        {
             // entries of the first model
             const size_t row = (size_t)i * S + (S - 1);
             const int n_all = as_constant(bcum + row * nbs)[npos];
@@ -542,10 +542,106 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             prefetch_row(pf, step_tab + row * Kp, n_all < cand_buf ? n_all : cand_buf);
             commit_row(pf, step_tab + row * Kp, cbuf);
             if (tid == 0) *next_pos = npos - 1;
+        } else {
+            // The model handled first (s = S-1) follows the all-zero row f[S], so its
+            // row is a running minimum, f[S-1][t] = least cost among the entries with
+            // lt <= t, and costs a scatter and a scan instead of a sweep per entry (in
+            // the paper's own loop this is the step that starts from the single state
+            // "nothing spent").  One dword per cell, laid over the row copies, takes
+            // the least cost per latency; a min-scan over the cells makes the row.
+            const int nt = (int)blockDim.x;
+            const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+            const size_t row = (size_t)i * S + (S - 1);
+            const StepEntry* const grow = step_tab + row * Kp;
+            uint16_t* const out = frow + row * row_stride;
+            const int n_all = as_constant(bcum + row * nbs)[npos];  // all have lt <= T
+            const int C = T + 1;
+            uint32_t* const cell_min = lds + PADB / 4;  // [C], ends inside the second copy
+
+            // start fetching the next model's entries; they are stored after the scan
+            RowPrefetch pf;
+            const StepEntry* grow_next = grow;
+            if (S > 1) {
+                const int n_next = as_constant(bcum + (row - 1) * nbs)[npos];
+                grow_next = step_tab + (row - 1) * Kp;
+                prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
+            }
+            // the F_INF stretch in front of every copy (the second copy's is covered by
+            // cell_min for now and is written again below)
+            for (int x = tid; x < PADB / 4; x += nt) {
+#pragma unroll
+                for (int m = 0; m < COPIES; ++m) lds[m * (CSB / 4) + x] = F_INF2;
+            }
+            for (int x = tid; x < C; x += nt) cell_min[x] = F_INF;
+            __syncthreads();
+            for (int e = tid; e < n_all; e += nt) {
+                const StepEntry se = grow[e];
+                atomicMin(&cell_min[wide_lt_of_shift(se.shift, COPIES, CSB)], se.ck & 0xFFFFu);
+            }
+            __syncthreads();
+            // every thread scans a run of cpt consecutive cells (a multiple of four, at
+            // most 16: a row has at most 1024 cells per wavefront)
+            const int cpt = 4 * ((C + 4 * nt - 1) / (4 * nt));
+            const int c0 = tid * cpt;
+            uint32_t v[16];
+            uint32_t run = F_INF;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int cell = c0 + j;
+                const uint32_t x = (j < cpt && cell < C) ? cell_min[cell] : F_INF;
+                run = x < run ? x : run;
+                v[j] = run;
+            }
+            // least cost of all earlier runs: scan over the lanes, then over the wavefronts
+            uint32_t incl = run;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t o = __shfl_up(incl, d, 64);
+                if (lane >= d) incl = o < incl ? o : incl;
+            }
+            uint32_t before = __shfl_up(incl, 1, 64);
+            if (lane == 0) before = F_INF;
+            __syncthreads();  // cell_min has been read: the copies can be written
+            if (lane == 63) cbuf[w] = incl;
+            for (int x = tid; x < PADB / 4; x += nt) lds[CSB / 4 + x] = F_INF2;
+            __syncthreads();
+            for (int ww = 0; ww < w; ++ww) {
+                const uint32_t o = cbuf[ww];
+                before = o < before ? o : before;
+            }
+#pragma unroll
+            for (int j = 0; j < 16; j += G::ELT / 2) {
+                const int cell = c0 + j;
+                if (j < cpt && cell <= T) {
+                    uint32_t d[G::ELT / 4];
+#pragma unroll
+                    for (int u = 0; u < G::ELT / 4; ++u) {
+                        const uint32_t lo = v[j + 2 * u] < before ? v[j + 2 * u] : before;
+                        const uint32_t hi = v[j + 2 * u + 1] < before ? v[j + 2 * u + 1] : before;
+                        d[u] = lo | (hi << 16);
+                    }
+                    char* const at = ldsb + PADB + 2 * cell;
+                    if constexpr (COPIES == 4) {
+                        publish_quad(at, CSB, d[0], d[1]);
+                        u32x2 q;
+                        q.x = d[0];
+                        q.y = d[1];
+                        *reinterpret_cast<u32x2*>(out + cell) = q;
+                    } else {
+                        publish_pair(at, CSB, d[0]);
+                        *reinterpret_cast<uint32_t*>(out + cell) = d[0];
+                    }
+                }
+            }
+            __syncthreads();  // the wavefront totals in the staging buffer have been read
+            if (S > 1) commit_row(pf, grow_next, cbuf);
+            if (tid == 0) *next_pos = npos - 1;
         }
         __syncthreads();
 
-        for (int s = S - 1; s >= 0; --s) {
+        // (the pruned form sweeps the first model like the others: with a handful of
+        // entries per position that is cheaper than the scan)
+        for (int s = FIXED ? S - 1 : S - 2; s >= 0; --s) {
             const size_t row = (size_t)i * S + s;
             const StepEntry* const grow = step_tab + row * Kp;
             const AS_CONST uint16_t* bc = as_constant(bcum + row * nbs);

@@ -297,7 +297,7 @@ int themis_count_relaxations(const themis_problem_t* p, const void* d_workspace,
     Layout L;
     int rc = check_ws(p, d_workspace, workspace_bytes, &L);
     if (rc != THEMIS_OK) return rc;
-    return launch_count_relaxations(L, static_cast<const char*>(d_workspace), d_count,
+    return launch_count_relaxations(*p, L, static_cast<const char*>(d_workspace), d_count,
                                     static_cast<hipStream_t>(stream)) == hipSuccess
                ? THEMIS_OK
                : THEMIS_ERR_LAUNCH;

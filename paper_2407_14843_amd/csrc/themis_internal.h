@@ -284,7 +284,7 @@ hipError_t launch_same_config(const Layout& L, const int32_t* status_now, const 
 
 hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_lt,
                                     int32_t* d_cost, hipStream_t st);
-hipError_t launch_count_relaxations(const Layout& L, const char* ws,
+hipError_t launch_count_relaxations(const themis_problem_t& p, const Layout& L, const char* ws,
                                     unsigned long long* d_count, hipStream_t st);
 
 hipError_t launch_lds_probe(int width, int misalign, int iters, int blocks, uint32_t* sink,
