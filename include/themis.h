@@ -318,10 +318,11 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
  * in the workspace, summed over all instances, written to d_count[0]
  * (uint64): for every valid instance, model and feasible candidate,
  * T + 1 - lt, except for the model the recurrence starts with (the last of
- * the pipeline), whose row is a running minimum over its candidates and takes
- * no relaxations (rows of more than 16384 cells and pruned problems
- * excepted: there it is swept like the others).  For throughput accounting
- * only.
+ * the pipeline), whose row is a running minimum over its candidates, and the
+ * one it ends with (the first of a pipeline of two or more), of whose row only
+ * the answer is computed: neither takes relaxations (rows of more than 16384
+ * cells and pruned problems excepted: there every model is swept alike).  For
+ * throughput accounting only.
  */
 int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
                              size_t workspace_bytes, unsigned long long *d_count,

@@ -52,7 +52,7 @@ constexpr uint32_t VALIDATE_THREADS = 1024;
 __global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
-    const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta,
+    const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta, int32_t* __restrict__ ans,
     int32_t* __restrict__ order, int32_t* __restrict__ ctrl, uint32_t N, uint32_t S,
     int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, uint32_t cs)
 {
@@ -79,6 +79,8 @@ __global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
         }
         int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
         tmeta[i] = T;
+        ans[2 * i] = 0;
+        ans[2 * i + 1] = -1;  // until stage 2 says otherwise, stage 3 reads row 0
         // listed under its own class even when a launch of a higher class will
         // serve it: that launch walks the lists from the longest rows down
         if (ok) cls = class_of_budget(T);
@@ -375,9 +377,10 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
 }
 
 // Sum over valid instances, models and feasible candidates of (T + 1 - lt): the
-// relaxations stage 2 executes.  The model it handles first (s = S-1) is left
-// out where the wide kernel serves the instance and nothing is pruned: it then
-// builds that row with a scatter and a scan, not with relaxations.
+// relaxations stage 2 executes.  Where the wide kernel serves the instance and
+// nothing is pruned, the model it handles first (s = S-1) and, in a pipeline of
+// two or more, the one it handles last (s = 0) are left out: the first row is
+// built by a scatter and a scan, and of the last only the answer is computed.
 __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict__ step_tab,
                                                      const uint16_t* __restrict__ bcum,
                                                      const int32_t* __restrict__ tmeta,
@@ -391,8 +394,9 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
     for (uint32_t i = blockIdx.x; i < N; i += gridDim.x) {
         const int32_t T = tmeta[i];
         if (T < 0) continue;
-        const uint32_t swept = (all_swept || class_of_budget(T) == NARROW_CLS) ? S : S - 1;
-        for (uint32_t s = 0; s < swept; ++s) {
+        const bool every = all_swept || class_of_budget(T) == NARROW_CLS;
+        const uint32_t from = every || S < 2 ? 0u : 1u, swept = every ? S : S - 1;
+        for (uint32_t s = from; s < swept; ++s) {
             const size_t row = (size_t)i * S + s;
             const uint32_t n = bcum[row * nbs + nb];
             for (uint32_t e = threadIdx.x; e < n; e += 256)
@@ -427,6 +431,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     hipLaunchKernelGGL(k1_validate, dim3((L.N + VALIDATE_THREADS - 1) / VALIDATE_THREADS),
                        dim3(VALIDATE_THREADS), 0, st, d_coef,
                        d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, tmeta,
+                       (int32_t*)(ws + L.ans_off),
                        (int32_t*)(ws + L.order_off), ctrl, (uint32_t)L.N, (uint32_t)L.S, p.r_max,
                        p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, cs);
     hipError_t e = hipGetLastError();

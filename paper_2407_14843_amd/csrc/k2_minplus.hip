@@ -497,8 +497,8 @@ template <int COPIES, bool FIXED>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
-    int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int N, int S, int Kp, int nbs,
-    int row_stride, int cls, int low_cls, int cand_buf)
+    int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int32_t* __restrict__ ans, int N,
+    int S, int Kp, int nbs, int row_stride, int cls, int low_cls, int cand_buf)
 {
     using G = Geo<COPIES>;
     constexpr int DEPTH = 1;
@@ -647,6 +647,77 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             const AS_CONST uint16_t* bc = as_constant(bcum + row * nbs);
             uint16_t* const out = frow + row * row_stride;
             const int n_all = bc[npos];  // entries that reach the top position: all feasible ones
+
+            if (!FIXED && s == 0) {
+                // Of the last row only two things are ever used: the least cost,
+                // f[0][T], and the least budget that attains it.  Both follow from
+                // row 1, which is in LDS, without building row 0:
+                //   f[0][T] = min_k cost_k + f[1][T - lt_k]
+                //   t*      = min_k lt_k + u_k,  u_k = first u with f[1][u] <= f[0][T] - cost_k
+                // (rows never increase with the budget, so u_k is a binary search, and
+                // c_k + f[1][u] cannot fall below the optimum for lt_k + u <= T; an
+                // entry with no such u within T - lt_k does not attain it).
+                uint32_t* const hdr = reinterpret_cast<uint32_t*>(ldsb + SETB);  // [2], [3] are free
+                const uint16_t* const row1 = reinterpret_cast<const uint16_t*>(ldsb + PADB);
+                const int nt = (int)blockDim.x;
+                if (tid == 0) {
+                    hdr[2] = 0xFFFFFFFFu;
+                    hdr[3] = 0xFFFFFFFFu;
+                }
+                __syncthreads();
+                auto entry_of = [&](int x, uint32_t& lt, uint32_t& co) {
+                    const uint32_t e = x < cand_buf ? cbuf[x] : staged(grow[x]);
+                    co = e >> 16;
+                    lt = wide_lt_of_shift(4u * ((e & 0xFFFFu) - SHIFT_BIAS), COPIES, CSB);
+                };
+                auto wave_min_into = [&](uint32_t v, uint32_t* dst) {
+#pragma unroll
+                    for (int d = 32; d >= 1; d >>= 1) {
+                        const uint32_t o = __shfl_xor(v, d, 64);
+                        v = o < v ? o : v;
+                    }
+                    if (lane == 0) atomicMin(dst, v);
+                };
+                uint32_t mine = 0xFFFFFFFFu;
+                for (int x = tid; x < n_all; x += nt) {
+                    uint32_t lt, co;
+                    entry_of(x, lt, co);
+                    const uint32_t rest = row1[T - (int)lt];
+                    const uint32_t v = rest >= F_INF ? F_INF : co + rest;
+                    mine = v < mine ? v : mine;
+                }
+                wave_min_into(mine, &hdr[2]);
+                __syncthreads();
+                const uint32_t best = hdr[2] < F_INF ? hdr[2] : F_INF;
+                mine = 0xFFFFFFFFu;
+                if (best < F_INF) {
+                    for (int x = tid; x < n_all; x += nt) {
+                        uint32_t lt, co;
+                        entry_of(x, lt, co);
+                        if (co > best) continue;
+                        const uint32_t need = best - co;
+                        int hi = T - (int)lt;
+                        if (row1[hi] > need) continue;  // this entry does not attain the optimum
+                        int lo = 0;
+                        while (lo < hi) {
+                            const int mid = (lo + hi) >> 1;
+                            if (row1[mid] <= need)
+                                hi = mid;
+                            else
+                                lo = mid + 1;
+                        }
+                        const uint32_t t = lt + (uint32_t)lo;
+                        mine = t < mine ? t : mine;
+                    }
+                }
+                wave_min_into(mine, &hdr[3]);
+                __syncthreads();
+                if (tid == 0) {
+                    ans[2 * i] = (int32_t)best;
+                    ans[2 * i + 1] = best < F_INF ? (int32_t)hdr[3] : 0;
+                }
+                break;
+            }
 
             // start fetching the next model's entries; they are stored after the sweeps
             RowPrefetch pf;
@@ -903,8 +974,9 @@ hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, 
     hipLaunchKernelGGL((k2_minplus_wide<COPIES, FIXED>), dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
                        (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
                        (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
-                       (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off), L_.N, L_.S,
-                       L_.Kp, L_.nbs, L_.row_stride, c, low, cand_buf);
+                       (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off),
+                       (int32_t*)(ws + L_.ans_off), L_.N, L_.S, L_.Kp, L_.nbs, L_.row_stride, c, low,
+                       cand_buf);
     return hipGetLastError();
 }
 

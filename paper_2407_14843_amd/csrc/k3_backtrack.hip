@@ -20,7 +20,8 @@ namespace {
 
 __global__ __launch_bounds__(256) void k3_backtrack(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum, const int32_t* __restrict__ tmeta,
-    const uint16_t* __restrict__ frow, int32_t* __restrict__ status,
+    const uint16_t* __restrict__ frow, const int32_t* __restrict__ ans,
+    int32_t* __restrict__ status,
     int32_t* __restrict__ cost_out, int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg,
     BatchList bl, int N, int S, int Kp, int nbs, int row_stride, int copies_mask, uint64_t class_map,
     int sparse)
@@ -34,8 +35,11 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     const int T = tmeta[i];
     if (sparse && T < 0) return;  // switched off in this pass: outputs stay as they are
     const uint16_t* row0 = frow + (size_t)i * S * row_stride;
+    // the least cost and the least latency attaining it: from stage 2 where it
+    // found them itself (it then left row 0 unwritten), else read off row 0
+    const int given_t = T >= 0 ? ans[2 * i + 1] : -1;
     uint32_t best = F_INF;
-    if (T >= 0) best = row0[T];
+    if (T >= 0) best = given_t >= 0 ? (uint32_t)ans[2 * i] : (uint32_t)row0[T];
     if (T < 0 || best >= F_INF) {
         for (int x = lane; x < S * 3; x += 64) my_cfg[x] = 0;
         if (lane == 0) {
@@ -46,26 +50,30 @@ __global__ __launch_bounds__(256) void k3_backtrack(
         return;
     }
 
-    // first t with f[0][t] == best: 64-ary search on a non-increasing row.
-    // invariant: f[0][hi] == best, and f[0][t] > best for every t < lo.
-    int lo = 0, hi = T;
-    while (lo < hi) {
-        const int span = hi - lo;  // probes lo + span*lane/64 all lie below hi
-        const int probe = lo + (int)(((long long)span * lane) >> 6);
-        const bool hit = row0[probe] == best;
-        const unsigned long long m = __ballot(hit);
-        if (m == 0ull) {
-            // even the last probe is above best: the answer lies beyond it
-            lo = lo + (int)(((long long)span * 63) >> 6) + 1;
-        } else {
-            const int first = __builtin_ctzll(m);
-            const int new_hi = lo + (int)(((long long)span * first) >> 6);
-            const int new_lo = first == 0 ? lo : lo + (int)(((long long)span * (first - 1)) >> 6) + 1;
-            hi = new_hi;
-            lo = new_lo;
+    int t_star = given_t;
+    if (given_t < 0) {
+        // first t with f[0][t] == best: 64-ary search on a non-increasing row.
+        // invariant: f[0][hi] == best, and f[0][t] > best for every t < lo.
+        int lo = 0, hi = T;
+        while (lo < hi) {
+            const int span = hi - lo;  // probes lo + span*lane/64 all lie below hi
+            const int probe = lo + (int)(((long long)span * lane) >> 6);
+            const bool hit = row0[probe] == best;
+            const unsigned long long m = __ballot(hit);
+            if (m == 0ull) {
+                // even the last probe is above best: the answer lies beyond it
+                lo = lo + (int)(((long long)span * 63) >> 6) + 1;
+            } else {
+                const int first = __builtin_ctzll(m);
+                const int new_hi = lo + (int)(((long long)span * first) >> 6);
+                const int new_lo =
+                    first == 0 ? lo : lo + (int)(((long long)span * (first - 1)) >> 6) + 1;
+                hi = new_hi;
+                lo = new_lo;
+            }
         }
+        t_star = lo;
     }
-    const int t_star = lo;
 
     int t = t_star;
     bool fail = false;
@@ -140,7 +148,7 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
     hipLaunchKernelGGL(k3_backtrack, dim3((L.N + 3) / 4), dim3(256), 0, st,
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
-                       d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.Kp, L.nbs, L.row_stride,
+                       (const int32_t*)(ws + L.ans_off), d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.Kp, L.nbs, L.row_stride,
                        plan.copies_mask, plan.class_map, opts.sparse);
     return hipGetLastError();
 }

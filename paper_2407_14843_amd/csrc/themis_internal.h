@@ -147,10 +147,12 @@ MinplusPlan make_plan(const Layout& L);
 //   bcum   u16 [N*S][nbs]      bcum[j] = entries of the row with bucket < j, j = 0..nb
 //   frow   u16 [N][S][row_stride] f[s][t] of the min-plus recurrence
 //   tmeta  int32 [N]           budget T of the instance, -1 = invalid instance
+//   ans    int32 [N][2]        least cost and least latency attaining it, where stage 2
+//                              finds them itself; latency -1 = stage 3 reads them off row 0
 //   order  int32 [N_CLS][N]    instance ids grouped by work class
 //   ctrl   int32 [2][N_CLS]    per class: number of instances, queue cursor
 struct Layout {
-    size_t step_off, bcum_off, frow_off, tmeta_off, order_off, ctrl_off, total;
+    size_t step_off, bcum_off, frow_off, tmeta_off, ans_off, order_off, ctrl_off, total;
     int32_t N, S, K, Kp, t_max, row_stride, nb, nbs;
 };
 
@@ -175,6 +177,7 @@ inline Layout make_layout(const themis_problem_t& p)
     L.bcum_off = at;  at = align256(at + rows * L.nbs * sizeof(uint16_t));
     L.frow_off = at;  at = align256(at + rows * L.row_stride * sizeof(uint16_t));
     L.tmeta_off = at; at = align256(at + (size_t)L.N * sizeof(int32_t));
+    L.ans_off = at;   at = align256(at + (size_t)2 * L.N * sizeof(int32_t));
     L.order_off = at; at = align256(at + (size_t)N_CLS * L.N * sizeof(int32_t));
     L.ctrl_off = at;  at = align256(at + (size_t)2 * N_CLS * sizeof(int32_t));
     L.total = at;
