@@ -317,11 +317,12 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
  * Number of min-plus relaxations stage 2 executes for the tables currently
  * in the workspace, summed over all instances, written to d_count[0]
  * (uint64): for every valid instance, model and feasible candidate,
- * T + 1 - lt, except for the model the recurrence starts with (the last of
- * the pipeline), whose row is a running minimum over its candidates, and the
- * one it ends with (the first of a pipeline of two or more), of whose row only
- * the answer is computed: neither takes relaxations (rows of more than 16384
- * cells and pruned problems excepted: there every model is swept alike).  For
+ * T + 1 - lt, except for two models that take no relaxations when they
+ * have candidates enough to make it pay: the one the recurrence starts with
+ * (the last of the pipeline), whose row is then a running minimum over its
+ * candidates, and the one it ends with (the first of a pipeline of two or
+ * more), of whose row then only the answer is computed.  (Rows of more than
+ * 16384 cells and pruned problems excepted: there every model is swept.)  For
  * throughput accounting only.
  */
 int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,

@@ -378,27 +378,34 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
 
 // Sum over valid instances, models and feasible candidates of (T + 1 - lt): the
 // relaxations stage 2 executes.  Where the wide kernel serves the instance and
-// nothing is pruned, the model it handles first (s = S-1) and, in a pipeline of
-// two or more, the one it handles last (s = 0) are left out: the first row is
-// built by a scatter and a scan, and of the last only the answer is computed.
+// nothing is pruned, the model it handles first (s = S-1) and, in a pipeline of two or more, the one it
+// handles last (s = 0) are left out when they have entries enough for their
+// shortcuts (see worth_shortcut): the first row is then built by a scatter and
+// a scan, and of the last only the answer is computed.
 __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict__ step_tab,
                                                      const uint16_t* __restrict__ bcum,
                                                      const int32_t* __restrict__ tmeta,
                                                      unsigned long long* __restrict__ out,
                                                      uint32_t N, uint32_t S, uint32_t Kp,
                                                      uint32_t nb, uint32_t nbs, int copies_mask,
-                                                     uint64_t class_map, int all_swept)
+                                                     uint64_t class_map, int pruned)
 {
     __shared__ unsigned long long part[256];
     unsigned long long acc = 0;
     for (uint32_t i = blockIdx.x; i < N; i += gridDim.x) {
         const int32_t T = tmeta[i];
         if (T < 0) continue;
-        const bool every = all_swept || class_of_budget(T) == NARROW_CLS;
-        const uint32_t from = every || S < 2 ? 0u : 1u, swept = every ? S : S - 1;
-        for (uint32_t s = from; s < swept; ++s) {
+        const int cls = effective_class(T, class_map);
+        const bool wide = cls != NARROW_CLS && !pruned;  // the kernels that have the shortcuts
+        const int npos = (T + BUCKET_CELLS) / BUCKET_CELLS;
+        for (uint32_t s = 0; s < S; ++s) {
             const size_t row = (size_t)i * S + s;
             const uint32_t n = bcum[row * nbs + nb];
+            // the wide kernel's shortcuts for the model it handles first and for the
+            // one it handles last take no relaxations
+            if (wide && (s == S - 1 || (s == 0 && S > 1)) &&
+                worth_shortcut((int)n, npos, CLS_WAVES[cls]))
+                continue;
             for (uint32_t e = threadIdx.x; e < n; e += 256)
                 acc += (unsigned long long)(T + 1) -
                        lt_of_entry(step_tab[row * Kp + e].shift, T, class_map, copies_mask);

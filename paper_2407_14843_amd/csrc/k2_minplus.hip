@@ -470,6 +470,191 @@ __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntr
     }
 }
 
+// The first model of the recurrence by scatter and scan (see the call).  Kept
+// out of line so that its registers do not weigh on the allocation of the sweep
+// loop; every thread of the workgroup calls it.
+template <int COPIES>
+__device__ __attribute__((noinline)) void first_model_by_scan(
+    uint32_t* lds, int CSB, uint32_t* cbuf, const StepEntry* __restrict__ step_tab,
+    const uint16_t* __restrict__ bcum, uint16_t* __restrict__ frow, int i, int S, int Kp, int nbs,
+    int row_stride, int T, int npos, int cand_buf)
+{
+    using G = Geo<COPIES>;
+    // The model handled first (s = S-1) follows the all-zero row f[S], so its
+    // row is a running minimum, f[S-1][t] = least cost among the entries with
+    // lt <= t, and costs a scatter and a scan instead of a sweep per entry (in
+    // the paper's own loop this is the step that starts from the single state
+    // "nothing spent").  One dword per cell, laid over the row copies, takes
+    // the least cost per latency; a min-scan over the cells makes the row.
+    const int nt = (int)blockDim.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    char* const ldsb = reinterpret_cast<char*>(lds);
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t row = (size_t)i * S + (S - 1);
+    const StepEntry* const grow = step_tab + row * Kp;
+    uint16_t* const out = frow + row * row_stride;
+    const int n_all = as_constant(bcum + row * nbs)[npos];  // all have lt <= T
+    const int C = T + 1;
+    uint32_t* const cell_min = lds + PADB / 4;  // [C], ends inside the second copy
+
+    // start fetching the next model's entries; they are stored after the scan
+    RowPrefetch pf;
+    const StepEntry* grow_next = grow;
+    if (S > 1) {
+        const int n_next = as_constant(bcum + (row - 1) * nbs)[npos];
+        grow_next = step_tab + (row - 1) * Kp;
+        prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
+    }
+    // the F_INF stretch in front of every copy (the second copy's is covered by
+    // cell_min for now and is written again below)
+    for (int x = tid; x < PADB / 4; x += nt) {
+#pragma unroll
+        for (int m = 0; m < COPIES; ++m) lds[m * (CSB / 4) + x] = F_INF2;
+    }
+    for (int x = tid; x < C; x += nt) cell_min[x] = F_INF;
+    __syncthreads();
+    for (int e = tid; e < n_all; e += nt) {
+        const StepEntry se = grow[e];
+        atomicMin(&cell_min[wide_lt_of_shift(se.shift, COPIES, CSB)], se.ck & 0xFFFFu);
+    }
+    __syncthreads();
+    // every thread scans a run of cpt consecutive cells (a multiple of four, at
+    // most 16: a row has at most 1024 cells per wavefront)
+    const int cpt = 4 * ((C + 4 * nt - 1) / (4 * nt));
+    const int c0 = tid * cpt;
+    uint32_t v[16];
+    uint32_t run = F_INF;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int cell = c0 + j;
+        const uint32_t x = (j < cpt && cell < C) ? cell_min[cell] : F_INF;
+        run = x < run ? x : run;
+        v[j] = run;
+    }
+    // least cost of all earlier runs: scan over the lanes, then over the wavefronts
+    uint32_t incl = run;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl = o < incl ? o : incl;
+    }
+    uint32_t before = __shfl_up(incl, 1, 64);
+    if (lane == 0) before = F_INF;
+    __syncthreads();  // cell_min has been read: the copies can be written
+    if (lane == 63) cbuf[w] = incl;
+    for (int x = tid; x < PADB / 4; x += nt) lds[CSB / 4 + x] = F_INF2;
+    __syncthreads();
+    for (int ww = 0; ww < w; ++ww) {
+        const uint32_t o = cbuf[ww];
+        before = o < before ? o : before;
+    }
+#pragma unroll
+    for (int j = 0; j < 16; j += G::ELT / 2) {
+        const int cell = c0 + j;
+        if (j < cpt && cell <= T) {
+            uint32_t d[G::ELT / 4];
+#pragma unroll
+            for (int u = 0; u < G::ELT / 4; ++u) {
+                const uint32_t lo = v[j + 2 * u] < before ? v[j + 2 * u] : before;
+                const uint32_t hi = v[j + 2 * u + 1] < before ? v[j + 2 * u + 1] : before;
+                d[u] = lo | (hi << 16);
+            }
+            char* const at = ldsb + PADB + 2 * cell;
+            if constexpr (COPIES == 4) {
+                publish_quad(at, CSB, d[0], d[1]);
+                u32x2 q;
+                q.x = d[0];
+                q.y = d[1];
+                *reinterpret_cast<u32x2*>(out + cell) = q;
+            } else {
+                publish_pair(at, CSB, d[0]);
+                *reinterpret_cast<uint32_t*>(out + cell) = d[0];
+            }
+        }
+    }
+    __syncthreads();  // the wavefront totals in the staging buffer have been read
+    if (S > 1) commit_row(pf, grow_next, cbuf);
+}
+
+// The answer of an instance without its last row (see the call).  Out of line
+// for the same reason as first_model_by_scan(); every thread calls it.
+template <int COPIES>
+__device__ __attribute__((noinline)) void answer_from_row_one(char* ldsb, int CSB,
+                                                              const uint32_t* cbuf,
+                                                              const StepEntry* __restrict__ grow,
+                                                              int n_all, int cand_buf, int T,
+                                                              int32_t* __restrict__ answer)
+{
+    // Of the last row only two things are ever used: the least cost,
+    // f[0][T], and the least budget that attains it.  Both follow from
+    // row 1, which is in LDS, without building row 0:
+    //   f[0][T] = min_k cost_k + f[1][T - lt_k]
+    //   t*      = min_k lt_k + u_k,  u_k = first u with f[1][u] <= f[0][T] - cost_k
+    // (rows never increase with the budget, so u_k is a binary search, and
+    // c_k + f[1][u] cannot fall below the optimum for lt_k + u <= T; an
+    // entry with no such u within T - lt_k does not attain it).
+    const int tid = threadIdx.x, lane = tid & 63;
+    uint32_t* const hdr = reinterpret_cast<uint32_t*>(ldsb + COPIES * CSB);  // [2], [3] are free
+    const uint16_t* const row1 = reinterpret_cast<const uint16_t*>(ldsb + PADB);
+    const int nt = (int)blockDim.x;
+    if (tid == 0) {
+        hdr[2] = 0xFFFFFFFFu;
+        hdr[3] = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    auto entry_of = [&](int x, uint32_t& lt, uint32_t& co) {
+        const uint32_t e = x < cand_buf ? cbuf[x] : staged(grow[x]);
+        co = e >> 16;
+        lt = wide_lt_of_shift(4u * ((e & 0xFFFFu) - SHIFT_BIAS), COPIES, CSB);
+    };
+    auto wave_min_into = [&](uint32_t v, uint32_t* dst) {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const uint32_t o = __shfl_xor(v, d, 64);
+            v = o < v ? o : v;
+        }
+        if (lane == 0) atomicMin(dst, v);
+    };
+    uint32_t mine = 0xFFFFFFFFu;
+    for (int x = tid; x < n_all; x += nt) {
+        uint32_t lt, co;
+        entry_of(x, lt, co);
+        const uint32_t rest = row1[T - (int)lt];
+        const uint32_t v = rest >= F_INF ? F_INF : co + rest;
+        mine = v < mine ? v : mine;
+    }
+    wave_min_into(mine, &hdr[2]);
+    __syncthreads();
+    const uint32_t best = hdr[2] < F_INF ? hdr[2] : F_INF;
+    mine = 0xFFFFFFFFu;
+    if (best < F_INF) {
+        for (int x = tid; x < n_all; x += nt) {
+            uint32_t lt, co;
+            entry_of(x, lt, co);
+            if (co > best) continue;
+            const uint32_t need = best - co;
+            int hi = T - (int)lt;
+            if (row1[hi] > need) continue;  // this entry does not attain the optimum
+            int lo = 0;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (row1[mid] <= need)
+                    hi = mid;
+                else
+                    lo = mid + 1;
+            }
+            const uint32_t t = lt + (uint32_t)lo;
+            mine = t < mine ? t : mine;
+        }
+    }
+    wave_min_into(mine, &hdr[3]);
+    __syncthreads();
+    if (tid == 0) {
+        answer[0] = (int32_t)best;
+        answer[1] = best < F_INF ? (int32_t)hdr[3] : 0;
+    }
+}
+
 // The positions of a row cost very different amounts of work (position p is
 // reached by bcum[p+1] entries), so they are not dealt out in advance: the
 // wavefronts of the workgroup take them one at a time from a counter in LDS,
@@ -525,7 +710,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         const int T = as_constant(tmeta)[i];
         const int npos = (T + POSC) / POSC;  // positions that hold cells 0..T
 
-        if constexpr (FIXED) {
+        // Whether the first and the last model are worth their shortcuts (below)
+        // depends on how much sweeping they replace: entries times positions per
+        // wavefront.  With a handful of entries (one-core solves; pruned rows, whose
+        // form of the kernel leaves the shortcuts out altogether) the plain sweeps
+        // are cheaper than the scan and the searches.
+        const int n_first = as_constant(bcum + ((size_t)i * S + (S - 1)) * nbs)[npos];
+        const bool scan_first = !FIXED && worth_shortcut(n_first, npos, (int)blockDim.x >> 6);
+        if (!scan_first) {
             // rows before the first model: cells t < 0 are F_INF, cells t >= 0 are 0
             for (int x = tid; x < (PADB + npos * POSC * 2) / 4; x += (int)blockDim.x) {
 #pragma unroll
@@ -543,179 +735,21 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             commit_row(pf, step_tab + row * Kp, cbuf);
             if (tid == 0) *next_pos = npos - 1;
         } else {
-            // The model handled first (s = S-1) follows the all-zero row f[S], so its
-            // row is a running minimum, f[S-1][t] = least cost among the entries with
-            // lt <= t, and costs a scatter and a scan instead of a sweep per entry (in
-            // the paper's own loop this is the step that starts from the single state
-            // "nothing spent").  One dword per cell, laid over the row copies, takes
-            // the least cost per latency; a min-scan over the cells makes the row.
-            const int nt = (int)blockDim.x;
-            const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-            const size_t row = (size_t)i * S + (S - 1);
-            const StepEntry* const grow = step_tab + row * Kp;
-            uint16_t* const out = frow + row * row_stride;
-            const int n_all = as_constant(bcum + row * nbs)[npos];  // all have lt <= T
-            const int C = T + 1;
-            uint32_t* const cell_min = lds + PADB / 4;  // [C], ends inside the second copy
-
-            // start fetching the next model's entries; they are stored after the scan
-            RowPrefetch pf;
-            const StepEntry* grow_next = grow;
-            if (S > 1) {
-                const int n_next = as_constant(bcum + (row - 1) * nbs)[npos];
-                grow_next = step_tab + (row - 1) * Kp;
-                prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
-            }
-            // the F_INF stretch in front of every copy (the second copy's is covered by
-            // cell_min for now and is written again below)
-            for (int x = tid; x < PADB / 4; x += nt) {
-#pragma unroll
-                for (int m = 0; m < COPIES; ++m) lds[m * (CSB / 4) + x] = F_INF2;
-            }
-            for (int x = tid; x < C; x += nt) cell_min[x] = F_INF;
-            __syncthreads();
-            for (int e = tid; e < n_all; e += nt) {
-                const StepEntry se = grow[e];
-                atomicMin(&cell_min[wide_lt_of_shift(se.shift, COPIES, CSB)], se.ck & 0xFFFFu);
-            }
-            __syncthreads();
-            // every thread scans a run of cpt consecutive cells (a multiple of four, at
-            // most 16: a row has at most 1024 cells per wavefront)
-            const int cpt = 4 * ((C + 4 * nt - 1) / (4 * nt));
-            const int c0 = tid * cpt;
-            uint32_t v[16];
-            uint32_t run = F_INF;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int cell = c0 + j;
-                const uint32_t x = (j < cpt && cell < C) ? cell_min[cell] : F_INF;
-                run = x < run ? x : run;
-                v[j] = run;
-            }
-            // least cost of all earlier runs: scan over the lanes, then over the wavefronts
-            uint32_t incl = run;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const uint32_t o = __shfl_up(incl, d, 64);
-                if (lane >= d) incl = o < incl ? o : incl;
-            }
-            uint32_t before = __shfl_up(incl, 1, 64);
-            if (lane == 0) before = F_INF;
-            __syncthreads();  // cell_min has been read: the copies can be written
-            if (lane == 63) cbuf[w] = incl;
-            for (int x = tid; x < PADB / 4; x += nt) lds[CSB / 4 + x] = F_INF2;
-            __syncthreads();
-            for (int ww = 0; ww < w; ++ww) {
-                const uint32_t o = cbuf[ww];
-                before = o < before ? o : before;
-            }
-#pragma unroll
-            for (int j = 0; j < 16; j += G::ELT / 2) {
-                const int cell = c0 + j;
-                if (j < cpt && cell <= T) {
-                    uint32_t d[G::ELT / 4];
-#pragma unroll
-                    for (int u = 0; u < G::ELT / 4; ++u) {
-                        const uint32_t lo = v[j + 2 * u] < before ? v[j + 2 * u] : before;
-                        const uint32_t hi = v[j + 2 * u + 1] < before ? v[j + 2 * u + 1] : before;
-                        d[u] = lo | (hi << 16);
-                    }
-                    char* const at = ldsb + PADB + 2 * cell;
-                    if constexpr (COPIES == 4) {
-                        publish_quad(at, CSB, d[0], d[1]);
-                        u32x2 q;
-                        q.x = d[0];
-                        q.y = d[1];
-                        *reinterpret_cast<u32x2*>(out + cell) = q;
-                    } else {
-                        publish_pair(at, CSB, d[0]);
-                        *reinterpret_cast<uint32_t*>(out + cell) = d[0];
-                    }
-                }
-            }
-            __syncthreads();  // the wavefront totals in the staging buffer have been read
-            if (S > 1) commit_row(pf, grow_next, cbuf);
+            first_model_by_scan<COPIES>(lds, CSB, cbuf, step_tab, bcum, frow, i, S, Kp, nbs,
+                                        row_stride, T, npos, cand_buf);
             if (tid == 0) *next_pos = npos - 1;
         }
         __syncthreads();
 
-        // (the pruned form sweeps the first model like the others: with a handful of
-        // entries per position that is cheaper than the scan)
-        for (int s = FIXED ? S - 1 : S - 2; s >= 0; --s) {
+        for (int s = scan_first ? S - 2 : S - 1; s >= 0; --s) {
             const size_t row = (size_t)i * S + s;
             const StepEntry* const grow = step_tab + row * Kp;
             const AS_CONST uint16_t* bc = as_constant(bcum + row * nbs);
             uint16_t* const out = frow + row * row_stride;
             const int n_all = bc[npos];  // entries that reach the top position: all feasible ones
 
-            if (!FIXED && s == 0) {
-                // Of the last row only two things are ever used: the least cost,
-                // f[0][T], and the least budget that attains it.  Both follow from
-                // row 1, which is in LDS, without building row 0:
-                //   f[0][T] = min_k cost_k + f[1][T - lt_k]
-                //   t*      = min_k lt_k + u_k,  u_k = first u with f[1][u] <= f[0][T] - cost_k
-                // (rows never increase with the budget, so u_k is a binary search, and
-                // c_k + f[1][u] cannot fall below the optimum for lt_k + u <= T; an
-                // entry with no such u within T - lt_k does not attain it).
-                uint32_t* const hdr = reinterpret_cast<uint32_t*>(ldsb + SETB);  // [2], [3] are free
-                const uint16_t* const row1 = reinterpret_cast<const uint16_t*>(ldsb + PADB);
-                const int nt = (int)blockDim.x;
-                if (tid == 0) {
-                    hdr[2] = 0xFFFFFFFFu;
-                    hdr[3] = 0xFFFFFFFFu;
-                }
-                __syncthreads();
-                auto entry_of = [&](int x, uint32_t& lt, uint32_t& co) {
-                    const uint32_t e = x < cand_buf ? cbuf[x] : staged(grow[x]);
-                    co = e >> 16;
-                    lt = wide_lt_of_shift(4u * ((e & 0xFFFFu) - SHIFT_BIAS), COPIES, CSB);
-                };
-                auto wave_min_into = [&](uint32_t v, uint32_t* dst) {
-#pragma unroll
-                    for (int d = 32; d >= 1; d >>= 1) {
-                        const uint32_t o = __shfl_xor(v, d, 64);
-                        v = o < v ? o : v;
-                    }
-                    if (lane == 0) atomicMin(dst, v);
-                };
-                uint32_t mine = 0xFFFFFFFFu;
-                for (int x = tid; x < n_all; x += nt) {
-                    uint32_t lt, co;
-                    entry_of(x, lt, co);
-                    const uint32_t rest = row1[T - (int)lt];
-                    const uint32_t v = rest >= F_INF ? F_INF : co + rest;
-                    mine = v < mine ? v : mine;
-                }
-                wave_min_into(mine, &hdr[2]);
-                __syncthreads();
-                const uint32_t best = hdr[2] < F_INF ? hdr[2] : F_INF;
-                mine = 0xFFFFFFFFu;
-                if (best < F_INF) {
-                    for (int x = tid; x < n_all; x += nt) {
-                        uint32_t lt, co;
-                        entry_of(x, lt, co);
-                        if (co > best) continue;
-                        const uint32_t need = best - co;
-                        int hi = T - (int)lt;
-                        if (row1[hi] > need) continue;  // this entry does not attain the optimum
-                        int lo = 0;
-                        while (lo < hi) {
-                            const int mid = (lo + hi) >> 1;
-                            if (row1[mid] <= need)
-                                hi = mid;
-                            else
-                                lo = mid + 1;
-                        }
-                        const uint32_t t = lt + (uint32_t)lo;
-                        mine = t < mine ? t : mine;
-                    }
-                }
-                wave_min_into(mine, &hdr[3]);
-                __syncthreads();
-                if (tid == 0) {
-                    ans[2 * i] = (int32_t)best;
-                    ans[2 * i + 1] = best < F_INF ? (int32_t)hdr[3] : 0;
-                }
+            if (!FIXED && s == 0 && S > 1 && worth_shortcut(n_all, npos, (int)blockDim.x >> 6)) {
+                answer_from_row_one<COPIES>(ldsb, CSB, cbuf, grow, n_all, cand_buf, T, ans + 2 * i);
                 break;
             }
 

@@ -132,6 +132,15 @@ __host__ __device__ inline int effective_class(int T, uint64_t class_map)
     return head_of_class(class_of_budget(T), class_map);
 }
 
+// The first and the last model of the recurrence have shortcuts in the wide
+// kernel (a scan instead of sweeps; the answer without the row).  They pay when
+// they replace enough sweeping: n entries over npos positions, shared by the
+// workgroup's wavefronts.  Used by the kernel and by the relaxation count.
+__host__ __device__ inline bool worth_shortcut(int n_entries, int npos, int waves)
+{
+    return n_entries * npos >= 24 * waves;
+}
+
 struct Layout;
 struct MinplusPlan {
     int cus;          // compute units of the current device
