@@ -415,6 +415,11 @@ def main():
         line["pruned"] = {k: pr[k] for k in (
             "solves_per_s", "dp_cells_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
         line["pruned"]["relaxations_dense"] = m["relaxations_executed"]
+        # and with the rows of the recurrence kept as step functions (candidates x
+        # breakpoints instead of candidates x budgets), alone and with the pruning
+        for name, mode in (("step_rows", 2), ("pruned_step_rows", 3)):
+            sr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=mode)
+            line[name] = {k: sr[k] for k in ("solves_per_s", "ms_per_step", "kernel_ms")}
     if a.others:
         others = {}
         for idx in range(5):
@@ -432,6 +437,10 @@ def main():
                 op = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=1)
                 others[o["workload"]]["pruned"] = {k: op[k] for k in (
                     "solves_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
+                for name, mode in (("step_rows", 2), ("pruned_step_rows", 3)):
+                    sr = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=mode)
+                    others[o["workload"]][name] = {k: sr[k] for k in (
+                        "solves_per_s", "ms_per_step", "kernel_ms")}
         line["other_workloads"] = others
         line["next_rows"] = next_rows(themis, wl, max(3, a.steps // 2), 2)
     if not a.no_cpu:

@@ -88,13 +88,20 @@ extern "C" {
 #define THEMIS_PROFILE_5 0   /* coefficients (a,k,q,p,o)                        */
 #define THEMIS_PROFILE_EQ1 1 /* coefficients (a,k,q,p,o,d)                      */
 
-/* themis_problem_t.prune */
-#define THEMIS_PRUNE_NONE 0      /* every feasible candidate enters the recurrence */
+/* themis_problem_t.prune: ways of doing less work for the same results; the
+   two may be combined (THEMIS_PRUNE_DOMINATED | THEMIS_PRUNE_STEPS) */
+#define THEMIS_PRUNE_NONE 0      /* every feasible candidate enters the recurrence,
+                                    which combines it with every budget          */
 #define THEMIS_PRUNE_DOMINATED 1 /* candidates that another candidate of the same
                                     model beats or ties on both latency and cost
                                     (ties: smaller index wins) are dropped first.
                                     Results are identical: such a candidate is
                                     in no instance's smallest assignment.       */
+#define THEMIS_PRUNE_STEPS 2     /* the recurrence keeps every row as the list of
+                                    budgets where it drops (rows never increase
+                                    with the budget) and combines candidates
+                                    with that list instead of with every budget.
+                                    Results are identical, rows included.       */
 
 /* per-instance status written to d_status */
 #define THEMIS_SOLVED 0

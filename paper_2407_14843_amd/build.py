@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(HERE, "libthemis_hip.so")
-SOURCES = ["themis_api.hip", "k1_candidates.hip", "k2_minplus.hip", "k3_backtrack.hip",
+SOURCES = ["themis_api.hip", "k1_candidates.hip", "k2_minplus.hip", "k2_steps.hip",
+           "k3_backtrack.hip",
            "k4_fallback.hip", "k5_stability.hip", "lds_probe.hip"]
 
 HIPCC_FLAGS = [

@@ -444,7 +444,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
-    const bool prune = p.prune != THEMIS_PRUNE_NONE;
+    const bool prune = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
     // cost bins of the pruning table: one per cost when r_max * c_max fits, else
     // 2^prune_sh costs each; one table (sentinel + bins) per wavefront
     uint32_t prune_sh = 0;

@@ -50,6 +50,7 @@
 // own index and then pulls further ones through an atomic cursor until the
 // lists are exhausted, longest rows first, so the launch ends on the short
 // ones.  Usually one launch serves every class; see make_plan().
+#include "instance_queue.h"
 #include "themis_internal.h"
 
 namespace themis {
@@ -87,77 +88,12 @@ __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
     return __builtin_bit_cast(uint32_t, r);
 }
 
-// Tables written by earlier kernels are read-only here.  Viewing them through
-// the constant address space tells the compiler so (a workgroup barrier
-// otherwise counts as a possible writer), which lets it fetch wave-uniform
-// entries with scalar loads into SGPRs.
-#define AS_CONST __attribute__((address_space(4)))
-
 #define AS_LDS __attribute__((address_space(3)))
 
 // LDS address (byte offset within the workgroup's allocation) of a pointer into it
 __device__ __forceinline__ uint32_t lds_address(const void* p)
 {
     return (uint32_t)(uintptr_t)(const AS_LDS char*)p;
-}
-
-template <typename T>
-__device__ __forceinline__ const AS_CONST T* as_constant(const T* p)
-{
-    return (const AS_CONST T*)(uintptr_t)p;
-}
-
-// Workgroup barrier that orders LDS traffic only: global stores in flight are not
-// waited for (the barrier of __syncthreads() waits until they have reached L2,
-// a microsecond or more per model that nothing here depends on).
-__device__ __forceinline__ void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// Instances are handed to the workgroups of a launch from the launch's list
-// (one class, or several classes one after the other).  The first gridDim.x
-// entries are dealt out by workgroup index; the rest are pulled one at a time
-// through an atomic cursor, so that a workgroup that drew long rows takes fewer.
-// The static first round matters for small batches: read-modify-writes on one
-// address complete at a rate of one per some tens of nanoseconds device-wide, which
-// a launch of thousands of short rows that all begin (and end) with a pull would
-// be bound by.  A launch whose list is no longer than its grid never touches the
-// cursor at all.
-//
-// Returns the list index of the workgroup's next instance, or -1 when the list
-// is exhausted; every wavefront of the workgroup gets the same answer.
-// `prev` is the previous answer (-1 before the first call).
-__device__ __forceinline__ int next_index(volatile uint32_t* slot, int32_t* cursor, int count,
-                                          int prev)
-{
-    if (prev < 0) return (int)blockIdx.x < count ? (int)blockIdx.x : -1;
-    if (count <= (int)gridDim.x) return -1;
-    if (threadIdx.x == 0) *slot = (uint32_t)atomicAdd(cursor, 1);
-    __syncthreads();
-    const int idx = (int)gridDim.x + __builtin_amdgcn_readfirstlane((int)*slot);
-    __syncthreads();  // slot may be rewritten by the next call
-    return idx < count ? idx : -1;
-}
-
-// The list of a launch that serves the classes cls, cls - 1, ..., low, in that
-// order: the longest rows start first and the launch ends on the shortest ones.
-__device__ __forceinline__ int list_length(const int32_t* ctrl, int cls, int low)
-{
-    int n = 0;
-    for (int c = cls; c >= low; --c) n += as_constant(ctrl)[c];
-    return n;
-}
-
-__device__ __forceinline__ int list_entry(const int32_t* ctrl, const int32_t* order, int N,
-                                          int cls, int low, int idx)
-{
-    for (int c = cls; c >= low; --c) {
-        const int n = as_constant(ctrl)[c];
-        if (idx < n) return as_constant(order)[(size_t)c * N + idx];
-        idx -= n;
-    }
-    return -1;
 }
 
 // Entries of the row that can reach a position whose last cell is `last_cell`.
@@ -1050,7 +986,7 @@ MinplusPlan make_plan(const Layout& L_)
 
 hipError_t launch_minplus(const themis_problem_t& p, const Layout& L_, char* ws, hipStream_t st)
 {
-    const bool fixed = p.prune != THEMIS_PRUNE_NONE;
+    const bool fixed = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
     const MinplusPlan pl = make_plan(L_);
     hipError_t e;
 
@@ -1074,6 +1010,11 @@ hipError_t launch_minplus(const themis_problem_t& p, const Layout& L_, char* ws,
         if (head_of_class(c, pl.class_map) != c) continue;  // served by the launch of its head
         int low = c;
         while (low > 0 && head_of_class(low - 1, pl.class_map) == c) --low;
+        if (p.prune & THEMIS_PRUNE_STEPS) {
+            e = launch_steps_group(L_, ws, st, c, low, pl.cus, class_copies(c, pl.copies_mask));
+            if (e != hipSuccess) return e;
+            continue;
+        }
         if (class_copies(c, pl.copies_mask) == 2)
             e = fixed ? launch_wide_class<2, true>(L_, ws, st, c, low, pl.cus)
                       : launch_wide_class<2, false>(L_, ws, st, c, low, pl.cus);

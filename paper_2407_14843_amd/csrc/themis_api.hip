@@ -34,7 +34,7 @@ int check(const themis_problem_t* p)
         return THEMIS_ERR_SHAPE;
     if (p->queue_model < THEMIS_QUEUE_PER_REPLICA || p->queue_model > THEMIS_QUEUE_WORST_CASE ||
         p->profile_form < THEMIS_PROFILE_5 || p->profile_form > THEMIS_PROFILE_EQ1 ||
-        p->prune < THEMIS_PRUNE_NONE || p->prune > THEMIS_PRUNE_DOMINATED || p->reserved[0] != 0)
+        p->prune < 0 || p->prune > (THEMIS_PRUNE_DOMINATED | THEMIS_PRUNE_STEPS) || p->reserved[0] != 0)
         return THEMIS_ERR_SHAPE;
     if (p->n_batch < 1 || p->n_batch > THEMIS_MAX_BATCH) return THEMIS_ERR_BATCH;
     for (int j = 0; j < p->n_batch; ++j) {

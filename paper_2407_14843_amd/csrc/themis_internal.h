@@ -219,6 +219,9 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                              char* ws, hipStream_t st, const PassOpts& opts = PassOpts());
 hipError_t launch_minplus(const themis_problem_t& p, const Layout& L, char* ws,
                           hipStream_t st);
+// the min-plus stage with rows as step functions, for one group of classes
+hipError_t launch_steps_group(const Layout& L, char* ws, hipStream_t st, int cls, int low,
+                              int cus, int copies);
 // lt of an entry of an instance with budget T (see StepEntry)
 __host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, uint64_t class_map,
                                                 int copies_mask)

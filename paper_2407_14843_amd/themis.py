@@ -97,6 +97,7 @@ def lib():
 
 QUEUE_PER_REPLICA, QUEUE_SHARED, QUEUE_WORST_CASE = 0, 1, 2
 PROFILE_5, PROFILE_EQ1 = 0, 1
+PRUNE_NONE, PRUNE_DOMINATED, PRUNE_STEPS = 0, 1, 2
 
 
 def make_problem(n_inst, n_stage, c_max, batch_sizes, r_max, tick_us, slo_max_us,

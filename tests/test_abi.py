@@ -62,7 +62,8 @@ def test_check_problem_accepts_good(T):
     (lambda p: setattr(p, "slo_max_us", -1), "ERR_SHAPE"),
     (lambda p: setattr(p, "coef_shared", 2), "ERR_SHAPE"),
     (lambda p: p.reserved.__setitem__(0, 7), "ERR_SHAPE"),
-    (lambda p: setattr(p, "prune", 2), "ERR_SHAPE"),
+    (lambda p: setattr(p, "prune", 4), "ERR_SHAPE"),
+    (lambda p: setattr(p, "prune", -1), "ERR_SHAPE"),
     (lambda p: setattr(p, "queue_model", 3), "ERR_SHAPE"),
     (lambda p: setattr(p, "queue_model", -1), "ERR_SHAPE"),
     (lambda p: setattr(p, "profile_form", 2), "ERR_SHAPE"),
@@ -145,7 +146,8 @@ def test_stability_workspace_and_argument_checks(T):
 def test_model_options_accepted(T):
     for qm in (T.QUEUE_PER_REPLICA, T.QUEUE_SHARED, T.QUEUE_WORST_CASE):
         for pf in (T.PROFILE_5, T.PROFILE_EQ1):
-            for pr in (0, 1):
+            for pr in (T.PRUNE_NONE, T.PRUNE_DOMINATED, T.PRUNE_STEPS,
+                       T.PRUNE_DOMINATED | T.PRUNE_STEPS):
                 p = T.make_problem(64, 3, 8, [1, 2], 8, 1000, 300_000, queue_model=qm,
                                    profile_form=pf, prune=pr)
                 assert T.check_problem(p) == T.OK

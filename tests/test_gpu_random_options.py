@@ -36,7 +36,7 @@ def test_random_options(T, oracle, seed):
         variant = int(rng.integers(0, 2))
         w = wl.medium_random(rng, variant)
         qm, form, prune = (int(rng.integers(0, 3)), int(rng.integers(0, 2)),
-                           int(rng.integers(0, 2)))
+                           int(rng.integers(0, 4)))
         w = w.with_model(qm, rng.integers(0, 3000, size=w.coef.shape[:-1]) if form else None)
         if rng.random() < 0.3:      # overload: exercises the search of the fallback
             w.lam = np.minimum(w.lam.astype(np.int64) * rng.integers(1, 20, w.n_inst),
@@ -74,4 +74,4 @@ def test_random_options(T, oracle, seed):
             got, want = [r[k] for k in FB], [o[k] for k in FB]
         for x, (g, e) in enumerate(zip(got, want)):
             assert np.array_equal(g, e), f"output {x} differs in rep {rep}"
-    assert len(seen) >= 7
+    assert len(seen) >= 12
