@@ -329,8 +329,10 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
  * (the last of the pipeline), whose row is then a running minimum over its
  * candidates, and the one it ends with (the first of a pipeline of two or
  * more), of whose row then only the answer is computed.  (Rows of more than
- * 16384 cells and pruned problems excepted: there every model is swept.)  For
- * throughput accounting only.
+ * 16384 cells and pruned problems excepted: there every model is swept.  With
+ * THEMIS_PRUNE_STEPS nothing is swept; the count is then that of sweeping
+ * every model, the work the step form replaces.)  For throughput accounting
+ * only.
  */
 int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
                              size_t workspace_bytes, unsigned long long *d_count,
