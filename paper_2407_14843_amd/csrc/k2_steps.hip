@@ -41,6 +41,12 @@ constexpr int STEP_HDR = 64;     // dwords: queue slot, list length, answer, per
 // header dwords
 enum { H_SLOT = 0, H_LEN = 1, H_KEY = 2, H_MIN = 8, H_CNT = 24 };
 
+// Where the dword of budget c lives: one dword of padding per 32 budgets, so
+// that the scans, in which lane l reads budget l * cells_per_thread + j, spread
+// over the LDS banks instead of piling onto two of them.
+__device__ __forceinline__ int cell_at(int c) { return c + (c >> 5); }
+constexpr int STEP_CELLS_PER_WAVE = WIDE_CHUNK + WIDE_CHUNK / 32;  // dwords, padding included
+
 __device__ __forceinline__ uint32_t wave_incl_min(uint32_t x, int lane)
 {
 #pragma unroll
@@ -83,8 +89,8 @@ __global__ __launch_bounds__(1024) void k2_steps(
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     // the layout stage 1 made the entries' shifts for (only their latency is used here)
     const int CSB = wide_copy_bytes(CLS_WAVES[cls]);
-    uint32_t* const cell_min = lds;                      // [nw * 1024] one dword per budget
-    uint32_t* const hdr = lds + nw * WIDE_CHUNK;         // [STEP_HDR]
+    uint32_t* const cell_min = lds;                      // one dword per budget, see cell_at()
+    uint32_t* const hdr = lds + nw * STEP_CELLS_PER_WAVE;  // [STEP_HDR]
     uint32_t* const list = hdr + STEP_HDR;               // [STEP_LIST] tau << 16 | value
     uint32_t* const ent = list + STEP_LIST;              // [STEP_ENTS] lt << 16 | cost
 
@@ -96,10 +102,10 @@ __global__ __launch_bounds__(1024) void k2_steps(
         if (idx < 0) break;
         const int i = list_entry(ctrl, order, N, cls, low_cls, idx);
         const int T = as_constant(tmeta)[i];
-        const int C = T + 1;
         const int all = (T + BUCKET_CELLS) / BUCKET_CELLS;  // bcum index of "every feasible entry"
-        const int cpt = 4 * ((C + 4 * nt - 1) / (4 * nt));  // cells per thread, <= STEP_RUN
-        const int c0 = tid * cpt;
+        // every thread scans STEP_RUN budgets; those at or beyond C hold F_INF, so
+        // they never count as a drop and need no test of their own
+        const int c0 = tid * STEP_RUN;
 
         // the row before the first model: zero from budget 0 on
         if (tid == 0) {
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(1024) void k2_steps(
 #pragma unroll
                     for (int j = 0; j < STEP_RUN; ++j) {
                         const int cell = c0 + j;
-                        if (j < cpt && cell < C && f[j] < (j ? f[j - 1] : below)) {
+                        if (f[j] < (j ? f[j - 1] : below)) {
                             for (int k = 0; k < cnt; ++k) {
                                 const uint32_t e = ent[k];
                                 const uint32_t t = (uint32_t)cell + (e >> 16);
@@ -180,13 +186,13 @@ __global__ __launch_bounds__(1024) void k2_steps(
                 break;
             }
 
-            for (int x = tid; x < C; x += nt) cell_min[x] = F_INF;
+            for (int x = tid; x < nw * STEP_CELLS_PER_WAVE; x += nt) cell_min[x] = F_INF;
             for (int e0 = 0; e0 < n_all; e0 += STEP_ENTS) {
                 const int cnt = n_all - e0 < STEP_ENTS ? n_all - e0 : STEP_ENTS;
                 if (e0) lds_barrier();
                 stage(e0, cnt);
                 lds_barrier();  // entries staged, cells initialised
-                pairs(cnt, [&](uint32_t t, uint32_t v) { atomicMin(&cell_min[t], v); });
+                pairs(cnt, [&](uint32_t t, uint32_t v) { atomicMin(&cell_min[cell_at((int)t)], v); });
             }
             lds_barrier();
 
@@ -196,7 +202,7 @@ __global__ __launch_bounds__(1024) void k2_steps(
 #pragma unroll
             for (int j = 0; j < STEP_RUN; ++j) {
                 const int cell = c0 + j;
-                const uint32_t x = (j < cpt && cell < C) ? cell_min[cell] : F_INF;
+                const uint32_t x = cell_min[cell_at(cell)];
                 run = x < run ? x : run;
                 f[j] = run;
             }
@@ -213,15 +219,14 @@ __global__ __launch_bounds__(1024) void k2_steps(
 #pragma unroll
             for (int j = 0; j < STEP_RUN; ++j) {
                 f[j] = f[j] < below ? f[j] : below;
-                if (j < cpt && c0 + j < C && f[j] < (j ? f[j - 1] : below)) ++drops;
+                drops += f[j] < (j ? f[j - 1] : below) ? 1u : 0u;
             }
             // the row, for stage 3
             uint16_t* const out = frow + row * row_stride;
 #pragma unroll
             for (int j = 0; j < STEP_RUN; j += 2) {
                 const int cell = c0 + j;
-                if (j < cpt && cell <= T)
-                    *reinterpret_cast<uint32_t*>(out + cell) = f[j] | (f[j + 1] << 16);
+                if (cell <= T) *reinterpret_cast<uint32_t*>(out + cell) = f[j] | (f[j + 1] << 16);
             }
             // where the list entries of this thread go
             const uint32_t isum = wave_incl_sum(drops, lane);
@@ -238,8 +243,7 @@ __global__ __launch_bounds__(1024) void k2_steps(
 #pragma unroll
                 for (int j = 0; j < STEP_RUN; ++j) {
                     const int cell = c0 + j;
-                    if (j < cpt && cell < C && f[j] < (j ? f[j - 1] : below))
-                        list[at++] = ((uint32_t)cell << 16) | f[j];
+                    if (f[j] < (j ? f[j - 1] : below)) list[at++] = ((uint32_t)cell << 16) | f[j];
                 }
             }
             if (tid == 0) hdr[H_LEN] = own ? 0u : total;
@@ -253,7 +257,8 @@ constexpr size_t LDS_PER_CU = 160 * 1024;
 
 size_t steps_lds_bytes(int waves)
 {
-    return ((size_t)waves * WIDE_CHUNK + STEP_HDR + STEP_LIST + STEP_ENTS) * sizeof(uint32_t);
+    return ((size_t)waves * STEP_CELLS_PER_WAVE + STEP_HDR + STEP_LIST + STEP_ENTS) *
+           sizeof(uint32_t);
 }
 
 }  // namespace
