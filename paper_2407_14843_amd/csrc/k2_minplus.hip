@@ -125,6 +125,8 @@ static_assert(4 * SHIFT_BIAS >= WIDE_PAD_BYTES + (WIDE_MAX_CELLS / BUCKET_CELLS 
               "the bias covers the parking shift of the last position");
 static_assert(WIDE_CHUNK == 2 * POSC, "a wavefront holds two positions");
 static_assert(PADB == POSC * 2, "the pad is as long as one position");
+static_assert(16 * 64 * 16 / 32 * 4 <= 2 * PADB,
+              "two copies hold a padded dword per cell of the longest row");
 
 template <int COPIES>
 struct Geo {
@@ -430,8 +432,13 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
     const StepEntry* const grow = step_tab + row * Kp;
     uint16_t* const out = frow + row * row_stride;
     const int n_all = as_constant(bcum + row * nbs)[npos];  // all have lt <= T
-    const int C = T + 1;
-    uint32_t* const cell_min = lds + PADB / 4;  // [C], ends inside the second copy
+    // One dword per cell over the first two copies, with a dword of padding per 32
+    // cells: the scan below reads it with a stride of 16 cells per lane, which
+    // unpadded lands on two LDS banks.  Every thread scans 16 cells; those beyond
+    // T hold F_INF, so no cell needs a test of its own.
+    uint32_t* const cell_min = lds;
+    auto cell_at = [](int c) { return c + (c >> 5); };
+    const int span = cell_at(16 * nt);  // dwords; fits two copies for up to 16 wavefronts
 
     // start fetching the next model's entries; they are stored after the scan
     RowPrefetch pf;
@@ -441,29 +448,26 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
         grow_next = step_tab + (row - 1) * Kp;
         prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
     }
-    // the F_INF stretch in front of every copy (the second copy's is covered by
-    // cell_min for now and is written again below)
+    // the F_INF stretch in front of the copies that cell_min does not cover (those
+    // of the first two are written once it has been read)
     for (int x = tid; x < PADB / 4; x += nt) {
 #pragma unroll
-        for (int m = 0; m < COPIES; ++m) lds[m * (CSB / 4) + x] = F_INF2;
+        for (int m = 2; m < COPIES; ++m) lds[m * (CSB / 4) + x] = F_INF2;
     }
-    for (int x = tid; x < C; x += nt) cell_min[x] = F_INF;
+    for (int x = tid; x < span; x += nt) cell_min[x] = F_INF;
     __syncthreads();
     for (int e = tid; e < n_all; e += nt) {
         const StepEntry se = grow[e];
-        atomicMin(&cell_min[wide_lt_of_shift(se.shift, COPIES, CSB)], se.ck & 0xFFFFu);
+        atomicMin(&cell_min[cell_at((int)wide_lt_of_shift(se.shift, COPIES, CSB))],
+                  se.ck & 0xFFFFu);
     }
     __syncthreads();
-    // every thread scans a run of cpt consecutive cells (a multiple of four, at
-    // most 16: a row has at most 1024 cells per wavefront)
-    const int cpt = 4 * ((C + 4 * nt - 1) / (4 * nt));
-    const int c0 = tid * cpt;
+    const int c0 = tid * 16;
     uint32_t v[16];
     uint32_t run = F_INF;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-        const int cell = c0 + j;
-        const uint32_t x = (j < cpt && cell < C) ? cell_min[cell] : F_INF;
+        const uint32_t x = cell_min[cell_at(c0 + j)];
         run = x < run ? x : run;
         v[j] = run;
     }
@@ -478,7 +482,10 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
     if (lane == 0) before = F_INF;
     __syncthreads();  // cell_min has been read: the copies can be written
     if (lane == 63) cbuf[w] = incl;
-    for (int x = tid; x < PADB / 4; x += nt) lds[CSB / 4 + x] = F_INF2;
+    for (int x = tid; x < PADB / 4; x += nt) {
+        lds[x] = F_INF2;
+        lds[CSB / 4 + x] = F_INF2;
+    }
     __syncthreads();
     for (int ww = 0; ww < w; ++ww) {
         const uint32_t o = cbuf[ww];
@@ -487,7 +494,7 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
 #pragma unroll
     for (int j = 0; j < 16; j += G::ELT / 2) {
         const int cell = c0 + j;
-        if (j < cpt && cell <= T) {
+        if (cell <= T) {
             uint32_t d[G::ELT / 4];
 #pragma unroll
             for (int u = 0; u < G::ELT / 4; ++u) {
