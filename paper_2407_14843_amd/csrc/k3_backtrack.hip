@@ -33,13 +33,14 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     int32_t* my_cfg = cfg + (size_t)i * S * 3;
 
     const int T = tmeta[i];
+    const int ans_cost = ans[2 * i], ans_t = ans[2 * i + 1];  // set for every instance by stage 1
     if (sparse && T < 0) return;  // switched off in this pass: outputs stay as they are
     const uint16_t* row0 = frow + (size_t)i * S * row_stride;
     // the least cost and the least latency attaining it: from stage 2 where it
     // found them itself (it then left row 0 unwritten), else read off row 0
-    const int given_t = T >= 0 ? ans[2 * i + 1] : -1;
+    const int given_t = T >= 0 ? ans_t : -1;
     uint32_t best = F_INF;
-    if (T >= 0) best = given_t >= 0 ? (uint32_t)ans[2 * i] : (uint32_t)row0[T];
+    if (T >= 0) best = given_t >= 0 ? (uint32_t)ans_cost : (uint32_t)row0[T];
     if (T < 0 || best >= F_INF) {
         for (int x = lane; x < S * 3; x += 64) my_cfg[x] = 0;
         if (lane == 0) {
@@ -87,19 +88,35 @@ __global__ __launch_bounds__(256) void k3_backtrack(
         // smallest index k among the entries that attain the target; lt and cost
         // ride along in the low bits of the key
         unsigned long long key = ~0ull;
-        for (int e0 = 0; e0 < n; e0 += 64) {
-            const int e = e0 + lane;
-            if (e < n) {
-                const StepEntry se = sp[e];  // every entry below n is feasible
-                const int lt = (int)lt_of_entry(se.shift, T, class_map, copies_mask);
-                if (lt <= t) {
-                    const uint32_t co = se.ck & 0xFFFFu;
-                    const uint32_t rest = (s + 1 < S) ? (uint32_t)next[t - lt] : 0u;
-                    if (rest < F_INF && co + rest == target) {
-                        const unsigned long long cand =
-                            ((unsigned long long)(se.ck >> 16) << 32) | (co << 16) | (uint32_t)lt;
-                        key = cand < key ? cand : key;
-                    }
+        // Four groups of 64 entries at a time, in two rounds of independent loads
+        // (the entries, then the cells of the next row they point at): the walk is
+        // a chain of dependent memory latencies, so loads issued together cost one.
+        constexpr int GROUPS = 4;
+        for (int e0 = 0; e0 < n; e0 += 64 * GROUPS) {
+            StepEntry se[GROUPS];
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const int e = e0 + 64 * g + lane;
+                se[g].shift = 0u;
+                se[g].ck = 0u;
+                if (e < n) se[g] = sp[e];  // every entry below n is feasible
+            }
+            int lt[GROUPS];
+            uint32_t rest[GROUPS];
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const int e = e0 + 64 * g + lane;
+                lt[g] = e < n ? (int)lt_of_entry(se[g].shift, T, class_map, copies_mask) : t + 1;
+                rest[g] = F_INF;
+                if (lt[g] <= t) rest[g] = (s + 1 < S) ? (uint32_t)next[t - lt[g]] : 0u;
+            }
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const uint32_t co = se[g].ck & 0xFFFFu;
+                if (rest[g] < F_INF && co + rest[g] == target) {
+                    const unsigned long long cand =
+                        ((unsigned long long)(se[g].ck >> 16) << 32) | (co << 16) | (uint32_t)lt[g];
+                    key = cand < key ? cand : key;
                 }
             }
         }
