@@ -55,6 +55,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
     k_ms = [0.0, 0.0, 0.0]
     cells = 0
     relax = 0
+    entries = 0
     solved = 0
     for pi, wp in enumerate(passes):
         if wp is None:
@@ -115,10 +116,11 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
         if pi == 0:
             first_results = res
         solved += int((res[0] == 0).sum())
-        cnt = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+        cnt = torch.zeros(2, dtype=torch.int64, device="cuda:0")
         themis.themis_count_relaxations(p, b.workspace, cnt)
         torch.cuda.synchronize()
-        relax += int(cnt.item())
+        relax += int(cnt[0].item())
+        entries += int(cnt[1].item())
         Ti = (wp.slo_us.astype(np.int64) // wp.tick_us)
         cells += int(((Ti + 1) * wp.n_stage).sum())
         del b
@@ -141,9 +143,11 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
         "feasible_fraction": solved / n_solves,
         "kernel_ms": {"candidates": k_ms[0], "minplus": k_ms[1], "backtrack": k_ms[2]},
     })
-    # stage 1: 8 bytes written per candidate (+ 20 bytes of coefficients per model)
-    cand = w.n_inst * w.n_stage * w.n_cand * len(passes)
-    k1_bytes = cand * 8 + w.n_inst * w.n_stage * 20 * len(passes)
+    # stage 1: 8 bytes written per candidate that reaches the table (the feasible
+    # ones, less the pruned), + 20 bytes of coefficients read per model
+    k1_bytes = entries * 8 + w.n_inst * w.n_stage * 20 * len(passes)
+    out["table_entries"] = entries
+    out["candidates_evaluated"] = w.n_inst * w.n_stage * w.n_cand * len(passes)
     out["candidates_GBs"] = k1_bytes / (k_ms[0] * 1e-3) / 1e9 if k_ms[0] > 0 else None
     # stage 2, LDS bytes: 16-bit cells, so 2 bytes read per relaxation and 2 bytes
     # written per cell into each of the two row copies; the generic figure for

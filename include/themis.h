@@ -323,7 +323,7 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
 /*
  * Number of min-plus relaxations stage 2 executes for the tables currently
  * in the workspace, summed over all instances, written to d_count[0]
- * (uint64): for every valid instance, model and feasible candidate,
+ * (d_count: uint64 [2], device): for every valid instance, model and feasible candidate,
  * T + 1 - lt, except for two models that take no relaxations when they
  * have candidates enough to make it pay: the one the recurrence starts with
  * (the last of the pipeline), whose row is then a running minimum over its
@@ -331,8 +331,9 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
  * more), of whose row then only the answer is computed.  (Rows of more than
  * 16384 cells and pruned problems excepted: there every model is swept.  With
  * THEMIS_PRUNE_STEPS nothing is swept; the count is then that of sweeping
- * every model, the work the step form replaces.)  For throughput accounting
- * only.
+ * every model, the work the step form replaces.)  d_count[1] takes the number
+ * of entries those tables hold: the feasible candidates of the valid instances
+ * (less the pruned ones), 8 bytes each.  For throughput accounting only.
  */
 int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
                              size_t workspace_bytes, unsigned long long *d_count,

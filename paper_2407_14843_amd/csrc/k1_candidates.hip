@@ -119,9 +119,12 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 // model) pairs).  The thread walks its cores c <= c_max: the latency model only
 // depends on min(c, p), so it is evaluated for c <= p and reused (with cost n*c)
 // beyond.  Pass 1 parks every
-// candidate's (lt, cost) in LDS and counts its bucket; a wavefront scan turns
-// the counts into bucket offsets; pass 2 hands every entry a slot inside its
-// bucket's range and writes it to HBM in the form the min-plus stage reads.
+// candidate's (lt, cost) in LDS and counts the bucket of the feasible ones; a
+// wavefront scan turns the counts into bucket offsets; pass 2 hands every
+// feasible entry a slot inside its bucket's range and writes it to HBM in the
+// form the min-plus stage reads.  Infeasible candidates are not written at all:
+// a row's entries are its first bcum[row][nb] slots and the rest of the row's
+// stretch of the table is never read.
 // The order inside a bucket is whatever the LDS atomics yield; nothing
 // downstream depends on it.
 //
@@ -168,7 +171,6 @@ __global__ __launch_bounds__(256) void k1_candidates(
     const uint32_t tpr = nbat * split;
     const uint32_t rl = threadIdx.x / tpr, rem = threadIdx.x - rl * tpr;
     const uint32_t part = rem / nbat, j = rem - part * nbat;
-    const bool first = rem == 0;  // the row's thread for one-off work
     const uint32_t row = blockIdx.x * RPW + rl;
     bool live = rl < RPW && row < rows;
     uint32_t* const hist = smem + rl * row_words;
@@ -210,22 +212,16 @@ __global__ __launch_bounds__(256) void k1_candidates(
                 const uint32_t w0 = none ? STAGE_NONE
                                          : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
                 stage[(c - 1) * nbat + j] = w0;
-                if (!PRUNE) atomicAdd(&hist[none ? nb : (uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
+                if (!PRUNE && !none) atomicAdd(&hist[(uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
             }
         } else {
             for (uint32_t c = part + 1; c <= c_max; c += split) stage[(c - 1) * nbat + j] = STAGE_NONE;
-            if (first) hist[nb] = K;
-        }
-        // entries that pad the row to a multiple of eight
-        if (first) {
-            for (uint32_t kk = K; kk < Kp; ++kk) stage[kk] = STAGE_NONE;
-            atomicAdd(&hist[nb], Kp - K);
         }
     }
     __syncthreads();
     {
         // exclusive prefix over the buckets, one row at a time per wavefront;
-        // bucket nb (infeasible) comes last and starts where the feasible ones end
+        // the offset of bucket nb is the number of feasible entries
         const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
         for (uint32_t r = wv; r < RPW; r += 4) {
             const uint32_t grow = blockIdx.x * RPW + r;
@@ -298,7 +294,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
                         if (prune_sh == 0) keep = keep && tab[1u + bin] == ((lt << PRUNE_KEY_SHIFT) | kk);
                     }
                     if (!keep) hh[2 * HB + kk] = STAGE_NONE;
-                    atomicAdd(&hh[keep ? lt >> BUCKET_SHIFT : nb], 1u);
+                    if (keep) atomicAdd(&hh[lt >> BUCKET_SHIFT], 1u);
                 }
                 wave_lds_fence();
             }
@@ -335,25 +331,23 @@ __global__ __launch_bounds__(256) void k1_candidates(
             cm = 1, sh = 1, add = 1, step = (uint32_t)wide_copy_bytes(CLS_WAVES[cls]), base = 0;
         }
         StepEntry* const out = step_tab + (size_t)row * Kp;
-        auto place = [&](uint32_t kk) {
+        // Only the feasible candidates are written: they fill the first
+        // bcum[row][nb] slots of the row, and nothing reads the table beyond them.
+        for (uint32_t c = part + 1; c <= c_max; c += split) {
+            const uint32_t kk = (c - 1) * nbat + j;
             const uint32_t w0 = stage[kk];
             const uint32_t lt = w0 & 0xFFFFu;
-            const bool none = lt == STAGE_NONE;
-            const uint32_t slot = atomicAdd(&cur[none ? nb : lt >> BUCKET_SHIFT], 1u);
-            const uint32_t shift =
-                base + __umul24((0u - lt) & cm, step) - (((lt + add) >> sh) << (sh + 1));
+            if (lt == STAGE_NONE) continue;
+            const uint32_t slot = atomicAdd(&cur[lt >> BUCKET_SHIFT], 1u);
             StepEntry se;
-            se.shift = none ? 0u : shift;
-            se.ck = (none ? 0u : w0 >> 16) | (kk << 16);
+            se.shift = base + __umul24((0u - lt) & cm, step) - (((lt + add) >> sh) << (sh + 1));
+            se.ck = (w0 >> 16) | (kk << 16);
             out[slot] = se;
-        };
-        for (uint32_t c = part + 1; c <= c_max; c += split) place((c - 1) * nbat + j);
-        if (first)
-            for (uint32_t kk = K; kk < Kp; ++kk) place(kk);  // the padding entries
+        }
     }
 }
 
-__global__ void k_zero64(unsigned long long* p) { *p = 0ull; }
+__global__ void k_zero64x2(unsigned long long* p) { p[0] = p[1] = 0ull; }
 
 // Undo the bucket order: separate lt / cost arrays [N][S][K], index k.
 __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ step_tab,
@@ -367,13 +361,23 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
     uint32_t g = blockIdx.x * 256u + threadIdx.x;
     if (g >= rows * Kp) return;
     const uint32_t row = g / Kp, e = g - row * Kp;
+    const int32_t T = tmeta[row / S];
+    // the table holds the feasible candidates only; the arrays were filled with -1
+    if (T < 0 || e >= bcum[(size_t)row * nbs + nb]) return;
     const StepEntry se = step_tab[g];
     const uint32_t k = se.ck >> 16;
-    if (k >= K) return;  // padding entry
-    const int32_t T = tmeta[row / S];
-    const bool none = T < 0 || e >= bcum[(size_t)row * nbs + nb];
-    lt[(size_t)row * K + k] = none ? -1 : (int32_t)lt_of_entry(se.shift, T, class_map, copies_mask);
-    cost[(size_t)row * K + k] = none ? -1 : (int32_t)(se.ck & 0xFFFFu);
+    lt[(size_t)row * K + k] = (int32_t)lt_of_entry(se.shift, T, class_map, copies_mask);
+    cost[(size_t)row * K + k] = (int32_t)(se.ck & 0xFFFFu);
+}
+
+__global__ __launch_bounds__(256) void k_fill_minus_one(int32_t* __restrict__ a,
+                                                        int32_t* __restrict__ b, size_t n)
+{
+    const size_t g = (size_t)blockIdx.x * 256u + threadIdx.x;
+    if (g < n) {
+        a[g] = -1;
+        b[g] = -1;
+    }
 }
 
 // Sum over valid instances, models and feasible candidates of (T + 1 - lt): the
@@ -381,7 +385,8 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
 // nothing is pruned, the model it handles first (s = S-1) and, in a pipeline of two or more, the one it
 // handles last (s = 0) are left out when they have entries enough for their
 // shortcuts (see worth_shortcut): the first row is then built by a scatter and
-// a scan, and of the last only the answer is computed.
+// a scan, and of the last only the answer is computed.  out[1] takes the number
+// of entries the table holds for those instances (the feasible candidates).
 __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict__ step_tab,
                                                      const uint16_t* __restrict__ bcum,
                                                      const int32_t* __restrict__ tmeta,
@@ -391,7 +396,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
                                                      uint64_t class_map, int pruned)
 {
     __shared__ unsigned long long part[256];
-    unsigned long long acc = 0;
+    unsigned long long acc = 0, entries = 0;
     for (uint32_t i = blockIdx.x; i < N; i += gridDim.x) {
         const int32_t T = tmeta[i];
         if (T < 0) continue;
@@ -401,6 +406,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
         for (uint32_t s = 0; s < S; ++s) {
             const size_t row = (size_t)i * S + s;
             const uint32_t n = bcum[row * nbs + nb];
+            entries += n;
             // the wide kernel's shortcuts for the model it handles first and for the
             // one it handles last take no relaxations
             if (wide && (s == S - 1 || (s == 0 && S > 1)) &&
@@ -417,7 +423,10 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
         if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) atomicAdd(out, part[0]);
+    if (threadIdx.x == 0) {
+        atomicAdd(out, part[0]);
+        atomicAdd(out + 1, entries);  // every thread of the workgroup counted the same rows
+    }
 }
 
 }  // namespace
@@ -504,6 +513,11 @@ hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_
     const MinplusPlan plan = make_plan(L);
     uint32_t rows = (uint32_t)L.N * L.S;
     uint32_t blocks = (rows * (uint32_t)L.Kp + 255u) / 256u;
+    const size_t cells = (size_t)rows * (size_t)L.K;
+    hipLaunchKernelGGL(k_fill_minus_one, dim3((unsigned)((cells + 255u) / 256u)), dim3(256), 0, st,
+                       d_lt, d_cost, cells);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_export, dim3(blocks), dim3(256), 0, st,
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), d_lt, d_cost, rows, (uint32_t)L.S,
@@ -516,7 +530,7 @@ hipError_t launch_count_relaxations(const themis_problem_t& p, const Layout& L, 
                                     unsigned long long* d_count, hipStream_t st)
 {
     const MinplusPlan plan = make_plan(L);
-    hipLaunchKernelGGL(k_zero64, dim3(1), dim3(1), 0, st, d_count);
+    hipLaunchKernelGGL(k_zero64x2, dim3(1), dim3(1), 0, st, d_count);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     uint32_t blocks = (uint32_t)(L.N < 4096 ? L.N : 4096);

@@ -17,7 +17,7 @@ constexpr uint32_t F_INF = 0x8000u;
 constexpr uint32_t F_INF2 = 0x80008000u;
 
 // Stage 1 leaves one table of 8-byte entries, ordered within a row by latency
-// bucket lt >> BUCKET_SHIFT (infeasible candidates last), so that the
+// bucket lt >> BUCKET_SHIFT (feasible candidates only), so that the
 // candidates that can reach a given stretch of the budget grid form a prefix
 // of the row.  An entry holds
 //   shift  the byte offset that turns "my place in row copy 0" into "the
@@ -25,7 +25,8 @@ constexpr uint32_t F_INF2 = 0x80008000u;
 //          depends on the LDS layout of the instance's work class and is
 //          invertible (lt_of_shift), so lt itself is not stored;
 //   ck     cost | k << 16: replicas * cores (<= 32767) and the candidate index.
-// Entries at or beyond bcum[nb] are infeasible candidates (shift 0, cost 0).
+// A row's entries are its first bcum[nb] slots; infeasible candidates are not
+// written, and the slots beyond hold whatever they held before.
 struct __attribute__((aligned(8))) StepEntry {
     uint32_t shift;
     uint32_t ck;

@@ -231,6 +231,8 @@ def themis_export_candidates(p, workspace, lt, cost, stream=None):
 
 
 def themis_count_relaxations(p, workspace, count, stream=None):
+    if count.numel() < 2:
+        raise ValueError("count takes two values: relaxations, table entries")
     _chk("themis_count_relaxations", lib().themis_count_relaxations(
         ctypes.byref(p), _dp(workspace, torch.uint8), workspace.numel(),
         _dp(count, torch.int64), _stream(stream)))

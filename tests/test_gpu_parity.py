@@ -370,7 +370,7 @@ def test_relaxation_count(T, oracle):
     w = wl.workload(1, 50)
     b = T.DeviceBatch(w)
     T.themis_stage_candidates(b.p, b.coef, b.lam, b.slo_us, None, b.workspace)
-    cnt = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    cnt = torch.zeros(2, dtype=torch.int64, device="cuda:0")
     T.themis_count_relaxations(b.p, b.workspace, cnt)
     torch.cuda.synchronize()
     lt, _, _ = oracle.candidates(w)
@@ -387,4 +387,5 @@ def test_relaxation_count(T, oracle):
     skipped[:, 0] = short[:, 0]
     want = int(per_model[~skipped].sum())
     assert skipped.any() and not skipped[:, [0, -1]].all()
-    assert int(cnt.item()) == want
+    assert int(cnt[0].item()) == want
+    assert int(cnt[1].item()) == int(n.sum())  # the table holds the feasible candidates
