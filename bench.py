@@ -31,7 +31,7 @@ LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {"w1-joint-4096x5": 107407110, "w3-joint-65536x8": 10997892474}
+K2_HBM_TRAFFIC = {"w1-joint-4096x5": 107177599, "w3-joint-65536x8": 10999061322}
 
 
 def _events(n):
