@@ -32,6 +32,9 @@ VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-o
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
 K2_HBM_TRAFFIC = {"w1-joint-4096x5": 107177599, "w3-joint-65536x8": 10999061322}
+# share of the candidate kernel's cycles in which the vector ALU issues (same
+# profiles: SQ_INSTS_VALU * 4 / SIMDs / cycles); it, not HBM, is what holds that kernel
+K1_VALU_BUSY = {"w3-joint-65536x8": 0.882}
 
 
 def _events(n):
@@ -407,7 +410,7 @@ def main():
             "kernel": "k1_candidates", "bound": "hbm", "achieved": m["candidates_GBs"],
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None if m["candidates_GBs"] is None else m["candidates_GBs"] / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": None, "valu_busy": K1_VALU_BUSY.get(m["workload"]),
         },
     }
     if a.workload != 4 and not a.no_two_streams:
