@@ -144,9 +144,9 @@ struct Geo {
     {
         return SHIFT_BIAS - (uint32_t)((PADB + ELT * pos * (64 * NE)) / 4);
     }
-    // `at` is an LDS address (an integer, so that the lane's base and the start
-    // of the copies fold into one register outside the loop)
-    // reads the first NEA of the lane's NE elements
+    // Reads the first NEA of the lane's NE elements.  `at` is an LDS address (an
+    // integer, so that the lane's base and the start of the copies fold into one
+    // register outside the loop).
     template <int NEA>
     static __device__ __forceinline__ void read(uint32_t (&dst)[AD], uint32_t at)
     {
@@ -922,7 +922,6 @@ int cu_count()
 }
 
 constexpr size_t LDS_PER_CU = 160 * 1024;
-
 
 inline size_t wide_lds_bytes(int copies, int waves, int cand_buf)
 {
