@@ -124,8 +124,48 @@ static void check_classes()
     CHECK(class_copies(3, 0x3FF) == 2 && class_copies(3, 0) == 4, "copies mask");
 }
 
+static void check_layout()
+{
+    const int shapes[][6] = {  // N, S, c_max, n_batch, slo_max_us, tick_us
+        {1, 1, 1, 1, 0, 1},        {64, 3, 8, 5, 300000, 1000},   {4096, 5, 16, 7, 1000000, 250},
+        {65536, 8, 32, 8, 4000000, 250}, {7, 2, 512, 16, 32767, 1}, {1000, 4, 3, 3, 8191999, 250}};
+    for (const auto& sh : shapes) {
+        themis_problem_t p{};
+        p.n_inst = sh[0], p.n_stage = sh[1], p.c_max = sh[2], p.n_batch = sh[3];
+        p.slo_max_us = sh[4], p.tick_us = sh[5];
+        const Layout L = make_layout(p);
+        const size_t rows = (size_t)L.N * L.S;
+        const int T = sh[4] / sh[5];
+        CHECK(L.K == sh[2] * sh[3] && L.Kp >= L.K && L.Kp % 8 == 0 && L.Kp < L.K + 8, "N %d", sh[0]);
+        CHECK(L.t_max == T && L.nb == T / BUCKET_CELLS + 1 && L.nbs >= L.nb + 1 && L.nbs % 2 == 0,
+              "N %d", sh[0]);
+        // a lane stores up to four cells at once from any cell <= T; rows stay 256-byte aligned
+        CHECK(L.row_stride >= T + 4 && L.row_stride % 128 == 0, "N %d stride %d", sh[0], L.row_stride);
+        const size_t off[8] = {L.step_off, L.bcum_off, L.frow_off, L.tmeta_off,
+                               L.ans_off,  L.order_off, L.ctrl_off, L.total};
+        const size_t need[7] = {rows * L.Kp * 8,
+                                rows * L.nbs * 2,
+                                rows * (size_t)L.row_stride * 2,
+                                (size_t)L.N * 4,
+                                (size_t)L.N * 8,
+                                (size_t)N_CLS * L.N * 4,
+                                (size_t)2 * N_CLS * 4};
+        CHECK(off[0] == 0, "N %d", sh[0]);
+        for (int r = 0; r < 7; ++r) {
+            CHECK(off[r] % 256 == 0, "N %d region %d", sh[0], r);
+            CHECK(off[r + 1] >= off[r] + need[r] && off[r + 1] < off[r] + need[r] + 256,
+                  "N %d region %d", sh[0], r);
+        }
+    }
+    // the shortcut rule: entries times positions against 24 per wavefront
+    CHECK(worth_shortcut(24, 1, 1) && !worth_shortcut(23, 1, 1) && worth_shortcut(12, 8, 4) &&
+              !worth_shortcut(11, 8, 4) && !worth_shortcut(0, 32, 1),
+          "shortcut rule");
+}
+
 int main()
 {
+    check_layout();
     check_wide(2);
     check_wide(4);
     check_narrow();
