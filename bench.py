@@ -198,7 +198,8 @@ def next_rows(themis, wl, steps, warmup):
     workload of the shapes above: horizontal-only solve and stability test
     (Algorithm 2, Section 5.1.3) and the paper's printed model forms on workload 1;
     the vertical solve with Algorithm 1's fallback on workload 2 with its arrival
-    rates multiplied by U{1..5}, so that the running replicas often do not suffice."""
+    rates multiplied by U{1..5}, so that the running replicas often do not suffice;
+    the trace sweep (workload 4, both passes) with every distinct instance solved once."""
     import numpy as np
     out = {}
     w1 = wl.workload(1)
@@ -246,6 +247,28 @@ def next_rows(themis, wl, steps, warmup):
             "split_between_old_and_new_instances": float(((lv > 0) & (lv < w2.lam)).mean()),
             "remainder_served": float((r["status_h"][(lv > 0) & (lv < w2.lam)] == 0).mean())}
         del bf
+    torch.cuda.empty_cache()
+
+    # the trace sweep with every distinct instance solved once (few distinct rates:
+    # coefficients and objective are shared); NOT the measured hot path, which
+    # solves every instance
+    w4 = wl.workload(4)
+    n_steps = max(2, steps // 4)
+    bj = themis.DeviceBatch(w4)
+    ms_j = _time_calls(lambda: bj.solve_distinct(), n_steps, 1)
+    st, _, _, cfg = bj.results()
+    r_fixed = wl.replicas_carried_forward(st, cfg)
+    bv = themis.DeviceBatch(w4.with_r_fixed(r_fixed))
+    ms_v = _time_calls(lambda: bv.solve_distinct(), n_steps, 1)
+    key = np.concatenate([w4.lam[:, None], r_fixed], axis=1)
+    out["trace_sweep_distinct_instances_only"] = {
+        "workload": w4.name, "ms_per_call": ms_j + ms_v,
+        "instances_per_s": 2 * w4.n_inst / ((ms_j + ms_v) * 1e-3),
+        "joint_pass_ms": ms_j, "vertical_pass_ms": ms_v,
+        "distinct_joint": int(np.unique(w4.lam).size),
+        "distinct_vertical": int(np.unique(key, axis=0).shape[0]),
+        "feasible_fraction": float((bv.results()[0] == 0).mean())}
+    del bj, bv
     torch.cuda.empty_cache()
     return out
 

@@ -280,6 +280,31 @@ int themis_check_stability(const themis_problem_t *p, const int32_t *d_coef,
                            size_t workspace_bytes, void *stream);
 
 /*
+ * Bytes of device workspace themis_solve_distinct needs (0 if `p` is not
+ * acceptable): themis_workspace_bytes(p) plus two words per instance and a
+ * hash table of at least two slots per instance.
+ */
+size_t themis_memo_workspace_bytes(const themis_problem_t *p);
+
+/*
+ * The joint (d_r_fixed NULL) or vertical solve of a batch in which the same
+ * inputs recur, as in a sweep over an arrival-rate trace (Section 6 drives the
+ * system with the per-second rates of one): instances are grouped by their
+ * input words (lambda, slo_us, the replica counts if given, the coefficients
+ * unless shared), one instance per group goes through the three stages, and
+ * the others receive its results.  Outputs are those of themis_solve_joint /
+ * themis_solve_vertical on the same arguments, word for word, invalid
+ * instances included; only the work differs.  The measured hot path does not
+ * use it: there every instance is solved.
+ * d_workspace holds themis_memo_workspace_bytes(p) bytes.
+ */
+int themis_solve_distinct(const themis_problem_t *p, const int32_t *d_coef,
+                          const int32_t *d_lambda, const int32_t *d_slo_us,
+                          const int32_t *d_r_fixed, int32_t *d_status, int32_t *d_cost,
+                          int32_t *d_ticks, int32_t *d_cfg, void *d_workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
  * Stage 1 alone: evaluate every candidate of every model of every instance
  * (the "calculate l, q, h" step of Algorithms 1 and 2, done once instead of
  * once per budget cell) into the workspace.  d_r_fixed NULL = joint.

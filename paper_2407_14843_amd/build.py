@@ -16,7 +16,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(HERE, "libthemis_hip.so")
 SOURCES = ["themis_api.hip", "k1_candidates.hip", "k2_minplus.hip", "k2_steps.hip",
            "k3_backtrack.hip",
-           "k4_fallback.hip", "k5_stability.hip", "lds_probe.hip"]
+           "k4_fallback.hip", "k5_stability.hip", "k6_memo.hip", "lds_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -193,6 +193,44 @@ int themis_solve_vertical_fallback(const themis_problem_t* p, const int32_t* d_c
                 d_status_h, d_cost_h, d_ticks_h, d_cfg_h, w, st, rest);
 }
 
+size_t themis_memo_workspace_bytes(const themis_problem_t* p)
+{
+    if (check(p) != THEMIS_OK) return 0;
+    return make_memo_layout(make_layout(*p)).total;
+}
+
+int themis_solve_distinct(const themis_problem_t* p, const int32_t* d_coef,
+                          const int32_t* d_lambda, const int32_t* d_slo_us,
+                          const int32_t* d_r_fixed, int32_t* d_status, int32_t* d_cost,
+                          int32_t* d_ticks, int32_t* d_cfg, void* d_workspace,
+                          size_t workspace_bytes, void* stream)
+{
+    if (!d_coef || !d_lambda || !d_slo_us || !d_status || !d_cost || !d_ticks || !d_cfg)
+        return THEMIS_ERR_NULL;
+    int rc = check(p);
+    if (rc != THEMIS_OK) return rc;
+    const Layout L = make_layout(*p);
+    const MemoLayout M = make_memo_layout(L);
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0 ||
+        workspace_bytes < M.total)
+        return THEMIS_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* w = static_cast<char*>(d_workspace);
+    if (launch_memo_dedupe(*p, L, M, d_coef, d_lambda, d_slo_us, d_r_fixed, d_status, d_cost,
+                           d_ticks, d_cfg, w, st) != hipSuccess)
+        return THEMIS_ERR_LAUNCH;
+    // one pass over the instances that stand for themselves; the others carry a
+    // rate of zero, which switches them off
+    PassOpts only_distinct;
+    only_distinct.sparse = 1;
+    rc = pass(*p, L, d_coef, (const int32_t*)(w + M.lam_off), d_slo_us, d_r_fixed, d_status, d_cost,
+              d_ticks, d_cfg, w, st, only_distinct);
+    if (rc != THEMIS_OK) return rc;
+    return launch_memo_scatter(L, M, d_status, d_cost, d_ticks, d_cfg, w, st) == hipSuccess
+               ? THEMIS_OK
+               : THEMIS_ERR_LAUNCH;
+}
+
 size_t themis_stability_workspace_bytes(const themis_problem_t* p)
 {
     if (check(p) != THEMIS_OK) return 0;

@@ -294,6 +294,39 @@ inline StabilityLayout make_stability_layout(const Layout& L)
     return B;
 }
 
+// State of the solve that handles every distinct instance once, appended to
+// the workspace after Layout::total:
+//   rep    int32 [N]      index of the instance that stands for this one's inputs
+//   lam    int32 [N]      arrival rates of the pass: 0 unless the instance stands for itself
+//   table  int32 [slots]  hash table of instance indices, slots = power of two >= 2 N
+struct MemoLayout {
+    size_t rep_off, lam_off, table_off, total;
+    uint32_t slots;
+};
+
+inline MemoLayout make_memo_layout(const Layout& L)
+{
+    MemoLayout M{};
+    size_t at = L.total;
+    const size_t n4 = (size_t)L.N * sizeof(int32_t);
+    M.slots = 256u;
+    while (M.slots < 2u * (uint32_t)L.N) M.slots <<= 1;
+    M.rep_off = at;   at = align256(at + n4);
+    M.lam_off = at;   at = align256(at + n4);
+    M.table_off = at; at = align256(at + (size_t)M.slots * sizeof(int32_t));
+    M.total = at;
+    return M;
+}
+
+hipError_t launch_memo_dedupe(const themis_problem_t& p, const Layout& L, const MemoLayout& M,
+                              const int32_t* d_coef, const int32_t* d_lambda,
+                              const int32_t* d_slo_us, const int32_t* d_r_fixed,
+                              int32_t* d_status, int32_t* d_cost, int32_t* d_ticks,
+                              int32_t* d_cfg, char* ws, hipStream_t st);
+hipError_t launch_memo_scatter(const Layout& L, const MemoLayout& M, int32_t* d_status,
+                               int32_t* d_cost, int32_t* d_ticks, int32_t* d_cfg, const char* ws,
+                               hipStream_t st);
+
 hipError_t launch_same_config(const Layout& L, const int32_t* status_now, const int32_t* cfg_now,
                               const int32_t* status_pred, const int32_t* cfg_pred,
                               int32_t* stable, hipStream_t st);

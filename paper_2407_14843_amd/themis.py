@@ -26,6 +26,7 @@ EXPORTS = [
     "themis_solve_joint", "themis_solve_vertical", "themis_solve_horizontal",
     "themis_fallback_workspace_bytes", "themis_solve_vertical_fallback",
     "themis_stability_workspace_bytes", "themis_check_stability",
+    "themis_memo_workspace_bytes", "themis_solve_distinct",
     "themis_stage_candidates",
     "themis_stage_minplus", "themis_stage_backtrack", "themis_export_candidates",
     "themis_count_relaxations", "themis_probe_lds_read", "themis_probe_valu",
@@ -77,6 +78,10 @@ def lib():
         L.themis_stability_workspace_bytes.argtypes = [P]
         L.themis_check_stability.restype = ctypes.c_int
         L.themis_check_stability.argtypes = [P] + [vp] * 10 + [vp, sz, vp]
+        L.themis_memo_workspace_bytes.restype = sz
+        L.themis_memo_workspace_bytes.argtypes = [P]
+        L.themis_solve_distinct.restype = ctypes.c_int
+        L.themis_solve_distinct.argtypes = [P] + [vp] * 8 + [vp, sz, vp]
         L.themis_stage_candidates.restype = ctypes.c_int
         L.themis_stage_candidates.argtypes = [P, vp, vp, vp, vp, vp, sz, vp]
         L.themis_stage_minplus.restype = ctypes.c_int
@@ -207,6 +212,17 @@ def themis_check_stability(p, coef, lam_now, lam_pred, slo_us, cores, stable, st
         _dp(workspace, torch.uint8), workspace.numel(), _stream(stream)))
 
 
+def memo_workspace_bytes(p: ThemisProblem) -> int:
+    return int(lib().themis_memo_workspace_bytes(ctypes.byref(p)))
+
+
+def themis_solve_distinct(p, coef, lam, slo_us, r_fixed, status, cost, ticks, cfg, workspace,
+                          stream=None):
+    _chk("themis_solve_distinct", lib().themis_solve_distinct(
+        ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(r_fixed), _dp(status), _dp(cost),
+        _dp(ticks), _dp(cfg), _dp(workspace, torch.uint8), workspace.numel(), _stream(stream)))
+
+
 def themis_stage_candidates(p, coef, lam, slo_us, r_fixed, workspace, stream=None):
     _chk("themis_stage_candidates", lib().themis_stage_candidates(
         ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(r_fixed),
@@ -278,6 +294,14 @@ class DeviceBatch:
             themis_solve_vertical(self.p, self.coef, self.lam, self.slo_us, self.r_fixed,
                                   self.status, self.cost, self.ticks, self.cfg,
                                   self.workspace, stream)
+
+    def solve_distinct(self, stream=None):
+        """Enqueue the solve that handles every distinct instance once (same outputs)."""
+        if getattr(self, "memo_workspace", None) is None:
+            self.memo_workspace = torch.empty(memo_workspace_bytes(self.p), dtype=torch.uint8,
+                                              device=self.device)
+        themis_solve_distinct(self.p, self.coef, self.lam, self.slo_us, self.r_fixed, self.status,
+                              self.cost, self.ticks, self.cfg, self.memo_workspace, stream)
 
     def solve_horizontal(self, cores=None, stream=None):
         """Enqueue the horizontal-only solve (cores: numpy int [N][S] or None = one core)."""

@@ -143,6 +143,26 @@ def test_stability_workspace_and_argument_checks(T):
         T.ERR_WORKSPACE
 
 
+def test_distinct_solve_workspace_and_argument_checks(T):
+    import ctypes
+    p = T.make_problem(100, 3, 8, [1, 2], 8, 1000, 300_000)
+    # two words per instance and a table of 256 slots (the least power of two >= 2 N)
+    assert T.memo_workspace_bytes(p) >= T.workspace_bytes(p) + 2 * 100 * 4 + 256 * 4
+    big = T.make_problem(70_000, 3, 8, [1, 2], 8, 1000, 300_000)
+    assert T.memo_workspace_bytes(big) >= T.workspace_bytes(big) + 2 * 70_000 * 4 + (1 << 18) * 4
+    f = T.lib().themis_solve_distinct
+    one = ctypes.c_void_p(256)
+    # replica counts are optional (absent = joint); everything else is required
+    assert f(ctypes.byref(p), one, one, one, None, one, one, one, one, one, 256, None) == \
+        T.ERR_WORKSPACE
+    assert f(ctypes.byref(p), one, None, one, None, one, one, one, one, one, 1 << 30, None) == \
+        T.ERR_NULL
+    assert f(ctypes.byref(p), one, one, one, None, one, one, one, None, one, 1 << 30, None) == \
+        T.ERR_NULL
+    assert f(ctypes.byref(p), one, one, one, None, one, one, one, one, ctypes.c_void_p(260),
+             1 << 30, None) == T.ERR_WORKSPACE
+
+
 def test_model_options_accepted(T):
     for qm in (T.QUEUE_PER_REPLICA, T.QUEUE_SHARED, T.QUEUE_WORST_CASE):
         for pf in (T.PROFILE_5, T.PROFILE_EQ1):
