@@ -72,3 +72,32 @@ def test_captured_fallback_replays(T, oracle):
         got = b.fallback_results()
         for k in want:
             assert np.array_equal(got[k], want[k]), f"replay {rep}: {k} differs"
+
+
+def test_captured_distinct_solve_replays(T, oracle):
+    import torch
+    rng = np.random.default_rng(5)
+    base = wl.workload(1, 40)
+    w = base.take(rng.integers(0, base.n_inst, 400))   # most inputs recur
+    want = oracle.solve(w, threads=8)
+    print("[case] graph capture distinct-instance solve", flush=True)
+    b = T.DeviceBatch(w)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        b.solve_distinct(stream=s)             # warm-up (and workspace) outside the capture
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        b.solve_distinct(stream=torch.cuda.current_stream())
+    other = T.DeviceBatch(wl.workload(0))
+    for rep in range(3):
+        for t in (b.status, b.cost, b.ticks, b.cfg):
+            t.fill_(-7)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for name, got, exp in zip(("status", "cost", "ticks", "cfg"), b.results(), want):
+            assert np.array_equal(got, exp), f"replay {rep}: {name} differs"
+        other.solve()                          # eager work between the replays
+        other.results()
