@@ -96,10 +96,21 @@ __device__ __forceinline__ uint32_t lds_address(const void* p)
     return (uint32_t)(uintptr_t)(const AS_LDS char*)p;
 }
 
+// Entry idx of a row of bcum, for a wavefront-uniform idx.  The hardware has no
+// 16-bit scalar loads, and a 16-bit read would become a vector load whose wait
+// also waits for every vector load issued before it (the prefetched entries);
+// so the dword that holds the entry is read through the scalar cache and the
+// half picked.  Rows of bcum start on a dword boundary (their length is even).
+__device__ __forceinline__ int bcum_at(const AS_CONST uint16_t* bc, int idx)
+{
+    const uint32_t pair = reinterpret_cast<const AS_CONST uint32_t*>(bc)[idx >> 1];
+    return (int)((idx & 1) ? pair >> 16 : pair & 0xFFFFu);
+}
+
 // Entries of the row that can reach a position whose last cell is `last_cell`.
 __device__ __forceinline__ int prefix_count(const AS_CONST uint16_t* bc, int last_cell)
 {
-    return bc[(last_cell >> BUCKET_SHIFT) + 1];
+    return bcum_at(bc, (last_cell >> BUCKET_SHIFT) + 1);
 }
 
 // ------------------------------------------------------------------ wide kernel
@@ -359,8 +370,12 @@ __device__ __forceinline__ void publish_position(const uint32_t (&acc)[AD], char
 }
 
 // Entries of one row held in registers on their way from HBM to the LDS
-// staging buffer (loaded before a model's sweeps, stored after them).
-constexpr int PREFETCH = 4;  // entries per thread
+// staging buffer (loaded before a model's sweeps, stored after them).  They are
+// held as loaded and every load is issued whatever the row's length (beyond it,
+// slot 0 is read and dropped): a load under a test of its own, or one whose
+// value is worked on at once, is waited for on the spot, and the sweeps would
+// start after four memory latencies instead of hiding them.
+constexpr int PREFETCH = 2;  // entries per thread
 
 // An entry as the sweep wants it in LDS (see SHIFT_BIAS); the index is dropped.
 // (The padding entries behind a row are only ever fetched, never relaxed: the
@@ -371,7 +386,7 @@ __device__ __forceinline__ uint32_t staged(StepEntry se)
 }
 
 struct RowPrefetch {
-    uint32_t e[PREFETCH];  // staged form
+    StepEntry e[PREFETCH];
     int cnt;  // entries of the row to stage (at most CAND_BUF); 16 padding entries follow
 };
 
@@ -381,28 +396,25 @@ __device__ __forceinline__ void prefetch_row(RowPrefetch& pf, const StepEntry* g
 #pragma unroll
     for (int j = 0; j < PREFETCH; ++j) {
         const int x = (int)threadIdx.x + j * (int)blockDim.x;
-        StepEntry se;
-        se.shift = 0u;
-        se.ck = 0u;
-        if (x < cnt) se = grow[x];
-        pf.e[j] = staged(se);
+        pf.e[j] = grow[x < cnt ? x : 0];  // a row's stretch of the table has eight slots at least
     }
 }
 
 __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntry* grow,
                                            uint32_t* cbuf)
 {
+    StepEntry none;
+    none.shift = 0u;
+    none.ck = 0u;
 #pragma unroll
     for (int j = 0; j < PREFETCH; ++j) {
         const int x = (int)threadIdx.x + j * (int)blockDim.x;
-        if (x < pf.cnt + 16) cbuf[x] = pf.e[j];
+        if (x < pf.cnt + 16) cbuf[x] = staged(x < pf.cnt ? pf.e[j] : none);
     }
     // whatever the registers did not cover
     for (int x = (int)threadIdx.x + PREFETCH * (int)blockDim.x; x < pf.cnt + 16;
          x += (int)blockDim.x) {
-        StepEntry se;
-        se.shift = 0u;
-        se.ck = 0u;
+        StepEntry se = none;
         if (x < pf.cnt) se = grow[x];
         cbuf[x] = staged(se);
     }
@@ -431,7 +443,7 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
     const size_t row = (size_t)i * S + (S - 1);
     const StepEntry* const grow = step_tab + row * Kp;
     uint16_t* const out = frow + row * row_stride;
-    const int n_all = as_constant(bcum + row * nbs)[npos];  // all have lt <= T
+    const int n_all = bcum_at(as_constant(bcum + row * nbs), npos);  // all have lt <= T
     // One dword per cell over the first two copies, with a dword of padding per 32
     // cells: the scan below reads it with a stride of 16 cells per lane, which
     // unpadded lands on two LDS banks.  Every thread scans 16 cells; those beyond
@@ -444,7 +456,7 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
     RowPrefetch pf;
     const StepEntry* grow_next = grow;
     if (S > 1) {
-        const int n_next = as_constant(bcum + (row - 1) * nbs)[npos];
+        const int n_next = bcum_at(as_constant(bcum + (row - 1) * nbs), npos);
         grow_next = step_tab + (row - 1) * Kp;
         prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
     }
@@ -658,7 +670,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
         // wavefront.  With a handful of entries (one-core solves; pruned rows, whose
         // form of the kernel leaves the shortcuts out altogether) the plain sweeps
         // are cheaper than the scan and the searches.
-        const int n_first = as_constant(bcum + ((size_t)i * S + (S - 1)) * nbs)[npos];
+        const int n_first = bcum_at(as_constant(bcum + ((size_t)i * S + (S - 1)) * nbs), npos);
         const bool scan_first = !FIXED && worth_shortcut(n_first, npos, (int)blockDim.x >> 6);
         if (!scan_first) {
             // rows before the first model: cells t < 0 are F_INF, cells t >= 0 are 0
@@ -672,7 +684,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             }
             // entries of the first model
             const size_t row = (size_t)i * S + (S - 1);
-            const int n_all = as_constant(bcum + row * nbs)[npos];
+            const int n_all = bcum_at(as_constant(bcum + row * nbs), npos);
             RowPrefetch pf;
             prefetch_row(pf, step_tab + row * Kp, n_all < cand_buf ? n_all : cand_buf);
             commit_row(pf, step_tab + row * Kp, cbuf);
@@ -689,7 +701,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             const StepEntry* const grow = step_tab + row * Kp;
             const AS_CONST uint16_t* bc = as_constant(bcum + row * nbs);
             uint16_t* const out = frow + row * row_stride;
-            const int n_all = bc[npos];  // entries that reach the top position: all feasible ones
+            const int n_all = bcum_at(bc, npos);  // entries that reach the top position: all feasible ones
 
             if (!FIXED && s == 0 && S > 1 && worth_shortcut(n_all, npos, (int)blockDim.x >> 6)) {
                 answer_from_row_one<COPIES>(ldsb, CSB, cbuf, grow, n_all, cand_buf, T, ans + 2 * i);
@@ -700,7 +712,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             RowPrefetch pf;
             const StepEntry* grow_next = grow;
             if (s > 0) {
-                const int n_next = as_constant(bcum + (row - 1) * nbs)[npos];
+                const int n_next = bcum_at(as_constant(bcum + (row - 1) * nbs), npos);
                 grow_next = step_tab + (row - 1) * Kp;
                 prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
             }
@@ -715,14 +727,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 if (p_hi >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
-                    sweep_live<COPIES, DEPTH>(r_hi, ldsb, ent, bc[p_hi + 1], G::lane_byte(p_hi, lane),
+                    sweep_live<COPIES, DEPTH>(r_hi, ldsb, ent, bcum_at(bc, p_hi + 1), G::lane_byte(p_hi, lane),
                                               G::park(p_hi), G::live_elements(p_hi, T));
                     clamp_position(r_hi);
                 }
                 if (p_lo >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_lo[u] = 0xFFFFFFFFu;
-                    sweep<COPIES, DEPTH>(r_lo, ldsb, ent, bc[p_lo + 1], G::lane_byte(p_lo, lane),
+                    sweep<COPIES, DEPTH>(r_lo, ldsb, ent, bcum_at(bc, p_lo + 1), G::lane_byte(p_lo, lane),
                                   G::park(p_lo));
                     clamp_position(r_lo);
                 }
@@ -736,7 +748,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                     uint32_t acc[AD];
 #pragma unroll
                     for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
-                    sweep_live<COPIES, DEPTH>(acc, ldsb, ent, bc[p + 1], G::lane_byte(p, lane),
+                    sweep_live<COPIES, DEPTH>(acc, ldsb, ent, bcum_at(bc, p + 1), G::lane_byte(p, lane),
                                               G::park(p), G::live_elements(p, T));
                     finish_position<COPIES>(acc, out, p, lane, T);
                 }
@@ -764,7 +776,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                         __syncthreads();
                     }
                     for (int p0 = w; p0 < npos; p0 += nw) {
-                        const int n_p = bc[p0 + 1];
+                        const int n_p = bcum_at(bc, p0 + 1);
                         const int ke = n_p - seg < 0 ? 0 : (n_p - seg < cnt ? n_p - seg : cnt);
                         if (ke <= 0) continue;
                         uint32_t acc[AD];
