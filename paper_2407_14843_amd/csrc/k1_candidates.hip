@@ -326,9 +326,9 @@ __global__ __launch_bounds__(256) void k1_candidates(
         if (cls == NARROW_CLS) {
             cm = 1, sh = 1, add = 0, step = 4u * (NAR_COPY_DW - 1), base = 4u * NAR_CHUNK_DW;
         } else if (class_copies(cls, copies_mask) == 4) {
-            cm = 3, sh = 2, add = 3, step = (uint32_t)wide_copy_bytes(CLS_WAVES[cls]), base = 0;
+            cm = 3, sh = 2, add = 3, step = (uint32_t)wide_copy_bytes(cls_waves(cls)), base = 0;
         } else {
-            cm = 1, sh = 1, add = 1, step = (uint32_t)wide_copy_bytes(CLS_WAVES[cls]), base = 0;
+            cm = 1, sh = 1, add = 1, step = (uint32_t)wide_copy_bytes(cls_waves(cls)), base = 0;
         }
         StepEntry* const out = step_tab + (size_t)row * Kp;
         // Only the feasible candidates are written: they fill the first
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
             // the wide kernel's shortcuts for the model it handles first and for the
             // one it handles last take no relaxations
             if (wide && (s == S - 1 || (s == 0 && S > 1)) &&
-                worth_shortcut((int)n, npos, CLS_WAVES[cls]))
+                worth_shortcut((int)n, npos, cls_waves(cls)))
                 continue;
             for (uint32_t e = threadIdx.x; e < n; e += 256)
                 acc += (unsigned long long)(T + 1) -

@@ -643,7 +643,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     using G = Geo<COPIES>;
     constexpr int DEPTH = 1;
     extern __shared__ uint32_t lds[];
-    const int CSB = wide_copy_bytes(CLS_WAVES[cls]);  // bytes per copy: pad + the longest row
+    const int CSB = wide_copy_bytes(cls_waves(cls));  // bytes per copy: pad + the longest row
     const int SETB = COPIES * CSB;                    // bytes of all copies
     char* const ldsb = reinterpret_cast<char*>(lds);
     // after the copies: a dword for the instance queue, one for the position

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(1024) void k2_steps(
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     // the layout stage 1 made the entries' shifts for (only their latency is used here)
-    const int CSB = wide_copy_bytes(CLS_WAVES[cls]);
+    const int CSB = wide_copy_bytes(cls_waves(cls));
     uint32_t* const cell_min = lds;                      // one dword per budget, see cell_at()
     uint32_t* const hdr = lds + nw * STEP_CELLS_PER_WAVE;  // [STEP_HDR]
     uint32_t* const list = hdr + STEP_HDR;               // [STEP_LIST] tau << 16 | value

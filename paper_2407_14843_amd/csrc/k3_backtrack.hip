@@ -93,13 +93,14 @@ __global__ __launch_bounds__(256) void k3_backtrack(
         // a chain of dependent memory latencies, so loads issued together cost one.
         constexpr int GROUPS = 4;
         for (int e0 = 0; e0 < n; e0 += 64 * GROUPS) {
+            // Every load is issued whatever the lane's entry is (beyond the row's
+            // entries slot 0 is read, beyond the budget left cell 0, and dropped): a
+            // load under a test of its own is waited for before the next is issued.
             StepEntry se[GROUPS];
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
                 const int e = e0 + 64 * g + lane;
-                se[g].shift = 0u;
-                se[g].ck = 0u;
-                if (e < n) se[g] = sp[e];  // every entry below n is feasible
+                se[g] = sp[e < n ? e : 0];  // every entry below n is feasible
             }
             int lt[GROUPS];
             uint32_t rest[GROUPS];
@@ -107,9 +108,12 @@ __global__ __launch_bounds__(256) void k3_backtrack(
             for (int g = 0; g < GROUPS; ++g) {
                 const int e = e0 + 64 * g + lane;
                 lt[g] = e < n ? (int)lt_of_entry(se[g].shift, T, class_map, copies_mask) : t + 1;
-                rest[g] = F_INF;
-                if (lt[g] <= t) rest[g] = (s + 1 < S) ? (uint32_t)next[t - lt[g]] : 0u;
+                rest[g] = 0u;
+                if (s + 1 < S) rest[g] = next[lt[g] <= t ? t - lt[g] : 0];
             }
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g)
+                if (lt[g] > t) rest[g] = F_INF;
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
                 const uint32_t co = se[g].ck & 0xFFFFu;

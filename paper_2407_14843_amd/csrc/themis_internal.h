@@ -47,6 +47,17 @@ constexpr int MAX_CAND = THEMIS_MAX_CANDIDATES; // candidates per model (LDS sta
 constexpr int WIDE_CHUNK = 1024;                 // cells per wavefront
 constexpr int N_WIDE_CLS = 10;
 constexpr int CLS_WAVES[N_WIDE_CLS] = {1, 2, 3, 4, 6, 8, 10, 12, 14, 16};
+// The same table in closed form, for device code: indexing the array with a
+// value not known at compile time is a load from memory, which the walk of
+// stage 3 would wait for once per group of entries.
+__host__ __device__ constexpr int cls_waves(int c) { return c < 4 ? c + 1 : 2 * (c - 1); }
+constexpr bool cls_waves_agree()
+{
+    for (int c = 0; c < N_WIDE_CLS; ++c)
+        if (cls_waves(c) != CLS_WAVES[c]) return false;
+    return true;
+}
+static_assert(cls_waves_agree(), "cls_waves() is CLS_WAVES in closed form");
 constexpr int NARROW_CLS = N_WIDE_CLS;           // class index of the narrow kernel
 constexpr int N_CLS = N_WIDE_CLS + 1;
 constexpr int WIDE_MAX_CELLS = 16 * WIDE_CHUNK;  // 16384
@@ -56,9 +67,8 @@ __host__ __device__ inline int class_of_budget(int T)
     int cells = T + 1;
     if (cells > WIDE_MAX_CELLS) return NARROW_CLS;
     int nw = (cells + WIDE_CHUNK - 1) / WIDE_CHUNK;
-    int c = 0;
-    while (CLS_WAVES[c] < nw) ++c;
-    return c;
+    // the first class with at least nw wavefronts: 1 2 3 4 6 8 10 12 14 16
+    return nw <= 4 ? nw - 1 : (nw + 1) / 2 + 1;
 }
 
 // ---- LDS geometry of the min-plus stage (stage 1 bakes it into StepEntry) --
@@ -230,7 +240,7 @@ __host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, uint64_t 
     const int cls = effective_class(T, class_map);
     if (cls == NARROW_CLS) return narrow_lt_of_shift(shift);
     return wide_lt_of_shift(shift, class_copies(cls, copies_mask),
-                            wide_copy_bytes(CLS_WAVES[cls]));
+                            wide_copy_bytes(cls_waves(cls)));
 }
 
 hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L,
