@@ -90,6 +90,12 @@ __device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
 
 #define AS_LDS __attribute__((address_space(3)))
 
+// The workgroup's dynamic LDS.  Functions kept out of line take their LDS
+// pointers from here, not from their caller: a pointer that crosses a call is
+// a generic one, and every access through it becomes a flat instruction (the
+// volatile publishing stores even one that is waited for on the spot).
+extern __shared__ uint32_t wide_lds[];
+
 // LDS address (byte offset within the workgroup's allocation) of a pointer into it
 __device__ __forceinline__ uint32_t lds_address(const void* p)
 {
@@ -321,32 +327,56 @@ __device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* o
     store_position<COPIES>(acc, out, pos, lane, T);
 }
 
-// Write one lane element of the new row into the shifted LDS copies.  `p` is
-// the element's byte address in copy 0; copy m holds cell t at half-word
-// (PADB/2 + t - m).  volatile: each store must stay a naturally aligned access
-// of exactly this width (merged neighbours would be misaligned).
-__device__ __forceinline__ void publish_quad(char* p, int CSB, uint32_t lo, uint32_t hi)
+// Write one lane element of the new row into the shifted LDS copies.  `at` is
+// the element's LDS address in copy 0; copy m holds cell t at half-word
+// (PADB/2 + t - m).  Each store must stay a naturally aligned access of exactly
+// this width (merged neighbours would be misaligned, and a misaligned LDS access
+// is many times slower), and it must be an LDS instruction: written as volatile
+// stores through ordinary pointers they came out as flat stores, each one waited
+// for before the next.  Hence the instructions themselves.  The compiler does
+// not count them; publish_wait() before the barrier that ends the publishing.
+__device__ __forceinline__ void lds_store_b32(uint32_t at, uint32_t v)
 {
-    const uint32_t mid = __builtin_amdgcn_alignbit(hi, lo, 16);  // cells c1 c2 of c0 c1 | c2 c3
-    u32x2 v;
-    v.x = lo;
-    v.y = hi;
-    *reinterpret_cast<volatile u32x2*>(p) = v;                                 // copy 0
-    *reinterpret_cast<volatile uint16_t*>(p + CSB - 2) = (uint16_t)lo;         // copy 1
-    *reinterpret_cast<volatile uint32_t*>(p + CSB) = mid;
-    *reinterpret_cast<volatile uint16_t*>(p + CSB + 4) = (uint16_t)(hi >> 16);
-    *reinterpret_cast<volatile uint32_t*>(p + 2 * CSB - 4) = lo;               // copy 2
-    *reinterpret_cast<volatile uint32_t*>(p + 2 * CSB) = hi;
-    *reinterpret_cast<volatile uint16_t*>(p + 3 * CSB - 6) = (uint16_t)lo;     // copy 3
-    *reinterpret_cast<volatile uint32_t*>(p + 3 * CSB - 4) = mid;
-    *reinterpret_cast<volatile uint16_t*>(p + 3 * CSB) = (uint16_t)(hi >> 16);
+    asm volatile("ds_write_b32 %0, %1" : : "v"(at), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_store_b64(uint32_t at, uint32_t lo, uint32_t hi)
+{
+    const uint64_t v = ((uint64_t)hi << 32) | lo;
+    asm volatile("ds_write_b64 %0, %1" : : "v"(at), "v"(v) : "memory");
+}
+// the low half of v at `at`, the high half at `at` + gap (a multiple of two)
+template <int GAP>
+__device__ __forceinline__ void lds_store_halves(uint32_t at, uint32_t v)
+{
+    asm volatile("ds_write_b16 %0, %1\n\tds_write_b16_d16_hi %0, %1 offset:%2"
+                 :
+                 : "v"(at), "v"(v), "n"(GAP)
+                 : "memory");
+}
+__device__ __forceinline__ void publish_wait()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
-__device__ __forceinline__ void publish_pair(char* p, int CSB, uint32_t v)
+__device__ __forceinline__ void publish_quad(uint32_t at, int CSB, uint32_t lo, uint32_t hi)
 {
-    *reinterpret_cast<volatile uint32_t*>(p) = v;                              // copy 0
-    *reinterpret_cast<volatile uint16_t*>(p + CSB - 2) = (uint16_t)v;          // copy 1
-    *reinterpret_cast<volatile uint16_t*>(p + CSB) = (uint16_t)(v >> 16);
+    const uint32_t mid = __builtin_amdgcn_alignbit(hi, lo, 16);  // cells c1 c2 of c0 c1 | c2 c3
+    const uint32_t ends = __builtin_amdgcn_perm(hi, lo, 0x07060100u);  // cell c0 | cell c3 << 16
+    const uint32_t a1 = at + (uint32_t)CSB - 2u, a2 = at + 2u * (uint32_t)CSB - 4u,
+                   a3 = at + 3u * (uint32_t)CSB - 6u;
+    lds_store_b64(at, lo, hi);        // copy 0: c0 c1 c2 c3
+    lds_store_halves<6>(a1, ends);    // copy 1: c0 | c1 c2 | c3 from two bytes below
+    lds_store_b32(a1 + 2u, mid);
+    lds_store_b32(a2, lo);            // copy 2: c0 c1 | c2 c3 from four bytes below
+    lds_store_b32(a2 + 4u, hi);
+    lds_store_halves<6>(a3, ends);    // copy 3: c0 | c1 c2 | c3 from six bytes below
+    lds_store_b32(a3 + 2u, mid);
+}
+
+__device__ __forceinline__ void publish_pair(uint32_t at, int CSB, uint32_t v)
+{
+    lds_store_b32(at, v);                                  // copy 0: c0 c1
+    lds_store_halves<2>(at + (uint32_t)CSB - 2u, v);       // copy 1: c0 | c1 from two bytes below
 }
 
 // Write a finished position from the registers of the wavefront that computed
@@ -360,7 +390,7 @@ __device__ __forceinline__ void publish_position(const uint32_t (&acc)[AD], char
     for (int q = 0; q < G::NE; ++q) {
         const int el = pos * (64 * G::NE) + q * 64 + lane;
         if ((G::ELT / 2) * el <= T) {
-            char* const at = ldsb + PADB + G::ELT * el;
+            const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el);
             if constexpr (COPIES == 4)
                 publish_quad(at, CSB, acc[2 * q], acc[2 * q + 1]);
             else
@@ -425,7 +455,7 @@ __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntr
 // loop; every thread of the workgroup calls it.
 template <int COPIES>
 __device__ __attribute__((noinline)) void first_model_by_scan(
-    uint32_t* lds, int CSB, uint32_t* cbuf, const StepEntry* __restrict__ step_tab,
+    int CSB, const StepEntry* __restrict__ step_tab,
     const uint16_t* __restrict__ bcum, uint16_t* __restrict__ frow, int i, int S, int Kp, int nbs,
     int row_stride, int T, int npos, int cand_buf)
 {
@@ -438,7 +468,9 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
     // the least cost per latency; a min-scan over the cells makes the row.
     const int nt = (int)blockDim.x;
     const int tid = threadIdx.x, lane = tid & 63;
-    char* const ldsb = reinterpret_cast<char*>(lds);
+    uint32_t* const lds = wide_lds;
+    char* const ldsb = reinterpret_cast<char*>(wide_lds);
+    uint32_t* const cbuf = reinterpret_cast<uint32_t*>(ldsb + COPIES * CSB + 16);  // as in the kernel
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const size_t row = (size_t)i * S + (S - 1);
     const StepEntry* const grow = step_tab + row * Kp;
@@ -514,7 +546,7 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
                 const uint32_t hi = v[j + 2 * u + 1] < before ? v[j + 2 * u + 1] : before;
                 d[u] = lo | (hi << 16);
             }
-            char* const at = ldsb + PADB + 2 * cell;
+            const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + 2 * cell);
             if constexpr (COPIES == 4) {
                 publish_quad(at, CSB, d[0], d[1]);
                 u32x2 q;
@@ -527,6 +559,7 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
             }
         }
     }
+    publish_wait();
     __syncthreads();  // the wavefront totals in the staging buffer have been read
     if (S > 1) commit_row(pf, grow_next, cbuf);
 }
@@ -534,12 +567,13 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
 // The answer of an instance without its last row (see the call).  Out of line
 // for the same reason as first_model_by_scan(); every thread calls it.
 template <int COPIES>
-__device__ __attribute__((noinline)) void answer_from_row_one(char* ldsb, int CSB,
-                                                              const uint32_t* cbuf,
+__device__ __attribute__((noinline)) void answer_from_row_one(int CSB,
                                                               const StepEntry* __restrict__ grow,
                                                               int n_all, int cand_buf, int T,
                                                               int32_t* __restrict__ answer)
 {
+    char* const ldsb = reinterpret_cast<char*>(wide_lds);
+    const uint32_t* const cbuf = reinterpret_cast<const uint32_t*>(ldsb + COPIES * CSB + 16);
     // Of the last row only two things are ever used: the least cost,
     // f[0][T], and the least budget that attains it.  Both follow from
     // row 1, which is in LDS, without building row 0:
@@ -690,8 +724,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             commit_row(pf, step_tab + row * Kp, cbuf);
             if (tid == 0) *next_pos = npos - 1;
         } else {
-            first_model_by_scan<COPIES>(lds, CSB, cbuf, step_tab, bcum, frow, i, S, Kp, nbs,
-                                        row_stride, T, npos, cand_buf);
+            first_model_by_scan<COPIES>(CSB, step_tab, bcum, frow, i, S, Kp, nbs, row_stride, T,
+                                        npos, cand_buf);
             if (tid == 0) *next_pos = npos - 1;
         }
         __syncthreads();
@@ -704,7 +738,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             const int n_all = bcum_at(bc, npos);  // entries that reach the top position: all feasible ones
 
             if (!FIXED && s == 0 && S > 1 && worth_shortcut(n_all, npos, (int)blockDim.x >> 6)) {
-                answer_from_row_one<COPIES>(ldsb, CSB, cbuf, grow, n_all, cand_buf, T, ans + 2 * i);
+                answer_from_row_one<COPIES>(CSB, grow, n_all, cand_buf, T, ans + 2 * i);
                 break;
             }
 
@@ -819,7 +853,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
             __syncthreads();  // every wavefront is done with the old row; the new one is stored
             for (int el = tid; el * (G::ELT / 2) <= T; el += (int)blockDim.x) {
-                char* const at = ldsb + PADB + G::ELT * el;
+                const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el);
                 if constexpr (COPIES == 4) {
                     const u32x2 v = *reinterpret_cast<const u32x2*>(out + 4 * el);
                     publish_quad(at, CSB, v.x, v.y);
@@ -830,6 +864,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             // hand the next model its entries and its position counter
             commit_row(pf, grow_next, cbuf);
             if (tid == 0) *next_pos = npos - 1;
+            publish_wait();
             __syncthreads();
         }
         __syncthreads();  // last row's reads are done before the LDS is re-initialised
