@@ -31,7 +31,7 @@ LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
 # profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {"w1-joint-4096x5": 124506155, "w3-joint-65536x8": 11673323286}
+K2_HBM_TRAFFIC = {"w1-joint-4096x5": 124836540, "w3-joint-65536x8": 11613581874}
 # share of the candidate kernel's cycles in which the vector ALU issues (same
 # profiles: SQ_INSTS_VALU * 4 / SIMDs / cycles); it, not HBM, is what holds that kernel
 K1_VALU_BUSY = {"w3-joint-65536x8": 0.882}
