@@ -6,14 +6,19 @@ selection and reconstruction) over one batch of synthetic instances whose
 inputs are already resident in HBM.  The steps are timed twice: as single calls
 of the solve entry point (`value`, `ms_per_step`), and stage by stage with HIP
 events between the stages (`kernel_ms`, the roofline figures,
-`ms_per_step_stage_by_stage`).  Prints ONE JSON line.
+`ms_per_step_stage_by_stage`).  The headline workload is the largest of the
+five (workload 3: 65536 pipelines of 8 models); the other four, the exact
+work-reducing forms and the further entry points are timed in the same run and
+reported beside it.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..4] [--others]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 0..4] [--no-others]
 """
 
 from __future__ import annotations
 
 import argparse
+import ctypes
+import hashlib
 import json
 import os
 import sys
@@ -30,11 +35,28 @@ LDS_BYTES_PER_CLK_CU = 128          # ds_read path per compute unit
 LDS_PEAK_GBS = N_CU * LDS_BYTES_PER_CLK_CU * CLOCK_GHZ          # 78643 GB/s
 VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-ops/s
 # HBM bytes per stage-2 pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, see
-# profiles/); None until measured for the kernels as they stand.
-K2_HBM_TRAFFIC = {"w1-joint-4096x5": 124836540, "w3-joint-65536x8": 11613581874}
-# share of the candidate kernel's cycles in which the vector ALU issues (same
-# profiles: SQ_INSTS_VALU * 4 / SIMDs / cycles); it, not HBM, is what holds that kernel
-K1_VALU_BUSY = {"w3-joint-65536x8": 0.882}
+# profiles/*_hbm_bytes.txt): workload -> (bytes, the `bytes_per_launch` of the run
+# the counters were taken on, fingerprint of the kernel sources at that time).
+# `roofline.traffic` is null unless both still match this run.
+K2_HBM_TRAFFIC = {}
+KERNEL_SOURCES = ("k1_candidates.hip", "candidate_eval.h", "k2_minplus.hip", "instance_queue.h",
+                  "themis_internal.h")
+
+
+def kernel_fingerprint():
+    """sha256 (first 16 hex digits) over the sources of stages 1 and 2."""
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2407_14843_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def hbm_traffic(workload, bytes_per_launch):
+    rec = K2_HBM_TRAFFIC.get(workload)
+    if rec is None or rec[1] != bytes_per_launch or rec[2] != kernel_fingerprint():
+        return None
+    return rec[0]
 
 
 def _events(n):
@@ -57,6 +79,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
     copy_ms = 0.0
     k_ms = [0.0, 0.0, 0.0]
     cells = 0
+    formed = 0
     relax = 0
     entries = 0
     solved = 0
@@ -119,11 +142,12 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
         if pi == 0:
             first_results = res
         solved += int((res[0] == 0).sum())
-        cnt = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+        cnt = torch.zeros(3, dtype=torch.int64, device="cuda:0")
         themis.themis_count_relaxations(p, b.workspace, cnt)
         torch.cuda.synchronize()
         relax += int(cnt[0].item())
         entries += int(cnt[1].item())
+        formed += int(cnt[2].item())
         Ti = (wp.slo_us.astype(np.int64) // wp.tick_us)
         cells += int(((Ti + 1) * wp.n_stage).sum())
         del b
@@ -139,8 +163,10 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
         "ms_per_step_stage_by_stage": staged_ms / steps,
         "solves_per_s": n_solves / (ms_per_step * 1e-3),
         "dp_cells_per_s": cells / (ms_per_step * 1e-3),
+        "dp_cells_formed_per_s": formed / (ms_per_step * 1e-3),
         "relaxations_per_s": relax / (ms_per_step * 1e-3),
         "dp_cells": cells,
+        "dp_cells_formed": formed,
         "relaxations_executed": relax,
         "relaxations_nominal": cells * w.n_cand,
         "feasible_fraction": solved / n_solves,
@@ -153,10 +179,8 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
     out["candidates_evaluated"] = w.n_inst * w.n_stage * w.n_cand * len(passes)
     out["candidates_GBs"] = k1_bytes / (k_ms[0] * 1e-3) / 1e9 if k_ms[0] > 0 else None
     # stage 2, LDS bytes: 16-bit cells, so 2 bytes read per relaxation and 2 bytes
-    # written per cell into each of the two row copies; the generic figure for
-    # int32 cells (4 bytes per relaxation, 4 per cell) is kept beside it
-    out["minplus_lds_bytes"] = relax * 2 + cells * 4
-    out["minplus_int32_bytes"] = relax * 4 + cells * 4
+    # written per cell into each of the two row copies
+    out["minplus_lds_bytes"] = relax * 2 + formed * 4
     return out
 
 
@@ -273,46 +297,76 @@ def next_rows(themis, wl, steps, warmup):
     return out
 
 
-def cpu_baseline(wl, idx, max_inst):
-    """The CPU checker, as it stands, timed on this machine's host cores."""
+def cpu_baseline(wl, idx, sample):
+    """The CPU checker, as it stands, timed on this machine's host cores on a seeded
+    sample of the workload's instances (the rate extrapolates linearly: instances
+    are independent)."""
+    import numpy as np
     from oracle import oracle
     oracle.build(force=False)
-    w = wl.workload(idx, max_inst)
+    full = wl.workload(idx)
+    n = min(sample, full.n_inst)
+    pick = np.sort(np.random.default_rng(wl.BASE_SEED + 900 + idx).choice(
+        full.n_inst, size=n, replace=False))
+    w = full.take(pick)
     threads = min(os.cpu_count() or 1, 16)
     oracle.solve(w.head(min(8, w.n_inst)))       # load + touch
-    # the whole workload, three times over (about 15 s of CPU work); the median counts
-    walls = []
-    for _ in range(3):
-        t0 = time.perf_counter()
-        oracle.solve(w, threads=threads)
-        walls.append(time.perf_counter() - t0)
-    dt = sorted(walls)[1]
-    one = w.head(min(256, w.n_inst))
+    t0 = time.perf_counter()
+    oracle.solve(w, threads=threads)
+    dt = time.perf_counter() - t0
+    one = w.head(max(1, n // 32))
     t0 = time.perf_counter()
     oracle.solve(one, threads=1)
     dt1 = time.perf_counter() - t0
     return {"value": w.n_inst / dt, "unit": "solves/s", "cores": threads, "kind": "oracle",
-            "sample": f"first {w.n_inst} instances of {w.name}, instance range sharded over "
-                      f"{threads} threads, median of 3 runs, {dt:.2f} s wall each",
+            "sample": f"{n} of the {full.n_inst} instances of {full.name}, drawn without "
+                      f"replacement (seed {wl.BASE_SEED + 900 + idx}), instance range sharded "
+                      f"over {threads} threads, one run, {dt:.2f} s wall",
             "single_thread_value": one.n_inst / dt1,
-            "single_thread_sample": f"first {one.n_inst} instances, {dt1:.2f} s"}
+            "single_thread_sample": f"first {one.n_inst} instances of that sample, {dt1:.2f} s"}
+
+
+def _probe_lib():
+    """The probe library (LDS read and vector-issue micro-kernels), built beside
+    the solve library but not part of it."""
+    path = os.path.join(ROOT, "paper_2407_14843_amd", "libthemis_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2407_14843_amd.build`")
+    L = ctypes.CDLL(path)
+    vp = ctypes.c_void_p
+    L.probe_lds_read.restype = ctypes.c_int
+    L.probe_lds_read.argtypes = [ctypes.c_int] * 4 + [vp, vp]
+    L.probe_valu.restype = ctypes.c_int
+    L.probe_valu.argtypes = [ctypes.c_int] * 3 + [vp, vp]
+    return L
 
 
 def lds_probe():
-    """Measure LDS read bandwidth for each read width / alignment; prints one JSON line."""
+    """Measure LDS read bandwidth for each read width / alignment and the issue rate
+    of the vector instructions the kernels are made of; prints one JSON line."""
     import torch
-    from paper_2407_14843_amd import themis
+    P = _probe_lib()
     sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     stream = torch.cuda.current_stream()
+    sp, st = ctypes.c_void_p(sink.data_ptr()), ctypes.c_void_p(stream.cuda_stream)
+
+    def lds(width, mis, iters, blocks):
+        rc = P.probe_lds_read(width, mis, iters, blocks, sp, st)
+        assert rc == 0, f"probe_lds_read({width}, {mis}) returned {rc}"
+
+    def valu_op(op, iters, blocks):
+        rc = P.probe_valu(op, iters, blocks, sp, st)
+        assert rc == 0, f"probe_valu({op}) returned {rc}"
+
     blocks, iters = N_CU * 2 * 4, 2000
     res = {}
     for width, mis in ((4, 0), (4, 2), (8, 0), (8, 4), (8, 2), (8, -1), (8, -2), (16, 0), (16, 8),
                        (16, 4), (16, 2)):
-        themis.themis_probe_lds_read(width, mis, 50, blocks, sink, stream)
+        lds(width, mis, 50, blocks)
         torch.cuda.synchronize()
         e0, e1 = _events(2)
         e0.record(stream)
-        themis.themis_probe_lds_read(width, mis, iters, blocks, sink, stream)
+        lds(width, mis, iters, blocks)
         e1.record(stream)
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1)
@@ -332,11 +386,11 @@ def lds_probe():
              "v_add_u32_sdwa (16-bit operand)"]
     vblocks, viters = N_CU * 8 * 4, 4000
     for op, name in enumerate(names):
-        themis.themis_probe_valu(op, 10, vblocks, sink, stream)
+        valu_op(op, 10, vblocks)
         torch.cuda.synchronize()
         e0, e1 = _events(2)
         e0.record(stream)
-        themis.themis_probe_valu(op, viters, vblocks, sink, stream)
+        valu_op(op, viters, vblocks)
         e1.record(stream)
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1)
@@ -348,15 +402,29 @@ def lds_probe():
           flush=True)
 
 
+def _fractions(m):
+    """Roofline fractions of stages 1 and 2 from one run_workload() record."""
+    k2s = m["kernel_ms"]["minplus"] * 1e-3
+    return {
+        "minplus_lds_frac": m["minplus_lds_bytes"] / k2s / 1e9 / LDS_PEAK_GBS,
+        "minplus_valu_frac": m["relaxations_executed"] / k2s / 1e9 / VALU_PEAK_GOPS,
+        "candidates_hbm_frac": (None if m["candidates_GBs"] is None
+                                else m["candidates_GBs"] / HBM_PEAK_GBS),
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=1)
-    ap.add_argument("--others", action="store_true",
-                    help="also time the other numbered workloads (fewer steps)")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=3,
+                    help="the headline workload (default 3, the largest: 65536 x 8)")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the other numbered workloads and the further entry points")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline leg")
+    ap.add_argument("--cpu-sample", type=int, default=2048,
+                    help="instances of the headline workload the CPU baseline solves")
     ap.add_argument("--prune", action="store_true",
                     help="time the solve with dominated candidates pruned as the main figure "
                          "(same answers, fewer relaxations); the default times the dense solve")
@@ -366,7 +434,8 @@ def main():
     ap.add_argument("--no-two-streams", action="store_true",
                     help="skip the leg that issues the steps on two streams")
     ap.add_argument("--no-pruned", action="store_true",
-                    help="skip the extra leg that times the pruned solve beside the dense one")
+                    help="skip the extra legs that time the work-reducing forms beside the "
+                         "dense one")
     ap.add_argument("--copy-calib", action="store_true",
                     help="only run one 1 GiB device-to-device copy kernel (reference point for "
                          "HBM byte counters)")
@@ -416,65 +485,85 @@ def main():
         "data": "synthetic",
         "config": {"workload": m["workload"], "n_inst": m["n_inst"], "n_stage": m["n_stage"],
                    "candidates_per_stage": m["n_cand"], "prune": bool(a.prune)},
+        # nominal cells: every (model, budget) pair of every instance, S * (T + 1)
         "dp_cells_per_s": m["dp_cells_per_s"],
+        # cells whose value the kernels form (the model handled last only yields the answer)
+        "dp_cells_formed_per_s": m["dp_cells_formed_per_s"],
         "relaxations_per_s": m["relaxations_per_s"],
         "feasible_fraction": m["feasible_fraction"],
         "kernel_ms": m["kernel_ms"],
         "roofline": {
             "kernel": "k2_minplus_wide (all class launches of a step)", "bound": "lds",
             "achieved": k2_gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s",
-            "frac": k2_gbs / LDS_PEAK_GBS, "traffic": K2_HBM_TRAFFIC.get(m["workload"]),
+            "frac": k2_gbs / LDS_PEAK_GBS,
+            "traffic": hbm_traffic(m["workload"], m["minplus_lds_bytes"]),
             "bytes_per_launch": m["minplus_lds_bytes"],
-            "int32_equivalent_frac":
-                m["minplus_int32_bytes"] / (k2_ms * 1e-3) / 1e9 / LDS_PEAK_GBS,
             "valu_frac": (m["relaxations_executed"] / (k2_ms * 1e-3) / 1e9) / VALU_PEAK_GOPS,
         },
         "roofline_candidates": {
-            "kernel": "k1_candidates", "bound": "hbm", "achieved": m["candidates_GBs"],
+            "kernel": "k1_candidates (+ input check)", "bound": "hbm",
+            "achieved": m["candidates_GBs"],
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None if m["candidates_GBs"] is None else m["candidates_GBs"] / HBM_PEAK_GBS,
-            "traffic": None, "valu_busy": K1_VALU_BUSY.get(m["workload"]),
+            "traffic": None,
         },
     }
+    errors = {}
+
+    def extra(name, fn):
+        # a failure in a side leg must not cost the headline line
+        try:
+            line[name] = fn()
+        except Exception as e:  # noqa: BLE001
+            errors[name] = f"{type(e).__name__}: {e}"
+            torch.cuda.empty_cache()
+
     if a.workload != 4 and not a.no_two_streams:
-        line["two_streams"] = two_streams(themis, wl, a.workload, a.steps, a.warmup)
+        extra("two_streams", lambda: two_streams(themis, wl, a.workload, a.steps, a.warmup))
     # the same solve with dominated candidates dropped before the recurrence: same
     # answers, a fraction of the relaxations; reported beside the dense figures
     if not a.prune and not a.no_pruned:
-        pr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=1)
-        line["pruned"] = {k: pr[k] for k in (
-            "solves_per_s", "dp_cells_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
-        line["pruned"]["relaxations_dense"] = m["relaxations_executed"]
+        def pruned_leg():
+            pr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=1)
+            out = {k: pr[k] for k in ("solves_per_s", "dp_cells_per_s", "ms_per_step",
+                                      "kernel_ms", "relaxations_executed")}
+            out["relaxations_dense"] = m["relaxations_executed"]
+            out.update(_fractions(pr))
+            return out
+        extra("pruned", pruned_leg)
         # and with the rows of the recurrence kept as step functions (candidates x
         # breakpoints instead of candidates x budgets), alone and with the pruning
         for name, mode in (("step_rows", 2), ("pruned_step_rows", 3)):
-            sr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=mode)
-            line[name] = {k: sr[k] for k in ("solves_per_s", "ms_per_step", "kernel_ms")}
-    if a.others:
-        others = {}
-        for idx in range(5):
-            if idx == a.workload:
-                continue
-            o = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=int(a.prune))
-            others[o["workload"]] = {k: o[k] for k in (
-                "solves_per_s", "dp_cells_per_s", "relaxations_per_s", "ms_per_step",
-                "feasible_fraction", "kernel_ms", "candidates_GBs")}
-            k2s = o["kernel_ms"]["minplus"] * 1e-3
-            others[o["workload"]]["minplus_lds_frac"] = o["minplus_lds_bytes"] / k2s / 1e9 / LDS_PEAK_GBS
-            others[o["workload"]]["minplus_valu_frac"] = (
-                o["relaxations_executed"] / k2s / 1e9 / VALU_PEAK_GOPS)
-            if not a.prune and not a.no_pruned:
-                op = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=1)
-                others[o["workload"]]["pruned"] = {k: op[k] for k in (
-                    "solves_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
-                for name, mode in (("step_rows", 2), ("pruned_step_rows", 3)):
-                    sr = run_workload(themis, wl, idx, max(3, a.steps // 4), 1, prune=mode)
-                    others[o["workload"]][name] = {k: sr[k] for k in (
-                        "solves_per_s", "ms_per_step", "kernel_ms")}
-        line["other_workloads"] = others
-        line["next_rows"] = next_rows(themis, wl, max(3, a.steps // 2), 2)
+            def step_leg(mode=mode):
+                sr = run_workload(themis, wl, a.workload, a.steps, a.warmup, prune=mode)
+                return {k: sr[k] for k in ("solves_per_s", "ms_per_step", "kernel_ms")}
+            extra(name, step_leg)
+    if not a.no_others:
+        def others_leg():
+            others = {}
+            n_steps = max(3, a.steps // 2)
+            for idx in range(5):
+                if idx == a.workload:
+                    continue
+                o = run_workload(themis, wl, idx, n_steps, 2, prune=int(a.prune))
+                rec = {k: o[k] for k in (
+                    "solves_per_s", "dp_cells_per_s", "dp_cells_formed_per_s",
+                    "relaxations_per_s", "ms_per_step", "feasible_fraction", "kernel_ms",
+                    "candidates_GBs")}
+                rec.update(_fractions(o))
+                if not a.prune and not a.no_pruned:
+                    op = run_workload(themis, wl, idx, n_steps, 2, prune=1)
+                    rec["pruned"] = {k: op[k] for k in (
+                        "solves_per_s", "ms_per_step", "kernel_ms", "relaxations_executed")}
+                    rec["pruned"].update(_fractions(op))
+                others[o["workload"]] = rec
+            return others
+        extra("other_workloads", others_leg)
+        extra("next_rows", lambda: next_rows(themis, wl, max(3, a.steps // 2), 2))
     if not a.no_cpu:
-        line["cpu_baseline"] = cpu_baseline(wl, a.workload, 4096)
+        extra("cpu_baseline", lambda: cpu_baseline(wl, a.workload, a.cpu_sample))
+    if errors:
+        line["errors"] = errors
     print(json.dumps(line), flush=True)
 
 

@@ -320,7 +320,14 @@ int themis_stage_candidates(const themis_problem_t *p, const int32_t *d_coef,
  *                           cost[s][k] + f[s+1][t - lt[s][k]],
  * for the tables stage 1 left in the workspace (Section 4.4: add the models
  * one at a time and split each budget between the current model and the
- * rest).  Leaves every row f[s][0..T] in the workspace.
+ * rest).  Leaves the rows f[s][0..T] in the workspace for stage 3, except
+ * that of the model handled last (s = 0) where the stage computes the answer
+ * (least cost, least budget attaining it) directly from row 1: that pair is
+ * left in the workspace instead and stage 3 starts from it.
+ * Call it exactly once after each themis_stage_candidates on the same
+ * workspace: the stage consumes the per-class work queues that stage 1 sets
+ * up, so a second call without a new stage 1 would serve only the first
+ * instances of every queue (and must not be used to time the stage).
  */
 int themis_stage_minplus(const themis_problem_t *p, void *d_workspace,
                          size_t workspace_bytes, void *stream);
@@ -348,7 +355,7 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
 /*
  * Number of min-plus relaxations stage 2 executes for the tables currently
  * in the workspace, summed over all instances, written to d_count[0]
- * (d_count: uint64 [2], device): for every valid instance, model and feasible candidate,
+ * (d_count: uint64 [3], device): for every valid instance, model and feasible candidate,
  * T + 1 - lt, except for two models that take no relaxations when they
  * have candidates enough to make it pay: the one the recurrence starts with
  * (the last of the pipeline), whose row is then a running minimum over its
@@ -358,41 +365,14 @@ int themis_export_candidates(const themis_problem_t *p, const void *d_workspace,
  * THEMIS_PRUNE_STEPS nothing is swept; the count is then that of sweeping
  * every model, the work the step form replaces.)  d_count[1] takes the number
  * of entries those tables hold: the feasible candidates of the valid instances
- * (less the pruned ones), 8 bytes each.  For throughput accounting only.
+ * (less the pruned ones), 8 bytes each.  d_count[2] takes the number of cells
+ * (model, budget) whose value stage 2 forms: T + 1 per model of a valid
+ * instance, less the rows of which only the answer is computed.  For
+ * throughput accounting only.
  */
 int themis_count_relaxations(const themis_problem_t *p, const void *d_workspace,
                              size_t workspace_bytes, unsigned long long *d_count,
                              void *stream);
-
-/*
- * Measurement aid, not part of the solve: launch a kernel in which every lane
- * does nothing but conflict-free LDS reads of `width` bytes (4, 8 or 16) at
- * byte misalignment `misalign` (0, or 2/4/8 where smaller than the width;
- * with width 8, -1 = two adjacent dwords by ds_read2_b32 at 4-byte alignment,
- * -2 = ds_read2st64_b32).
- * One launch reads blocks * 1024 * iters * 4 * width bytes; time it to obtain
- * the LDS read bandwidth the min-plus stage is priced against.  d_sink is
- * one uint32 of device memory.  Unsupported combinations: THEMIS_ERR_SHAPE.
- */
-int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32_t *d_sink,
-                          void *stream);
-
-/*
- * Measurement aid, not part of the solve: launch a kernel in which every lane
- * issues iters * 16 independent vector instructions of one kind and nothing
- * else (op 0 v_pk_add_u16, 1 v_pk_min_u16, 2 v_add_u32, 3 v_min_u32,
- * 4 v_pk_add_u16 / v_pk_min_u16 alternating, 5 v_pk_add_u16 with a scalar
- * operand; 6..20 the instructions of the candidate stage: v_fma_f64,
- * v_mul_f64, v_add_f64, v_floor_f64, v_rcp_f64, v_cvt_f64_u32, v_cvt_u32_f64,
- * v_mul_lo_u32, v_cmp_ge_f64, v_cndmask_b32 on vcc, v_mul_u32_u24,
- * v_cndmask_b32 on a scalar pair, v_max_f64, v_add_f64 with clamp,
- * v_cmp_ge_f64 into a scalar pair; 21..24 address and operand-select forms
- * of the min-plus stage: v_mad_u32_u16, v_pk_add_u16 with op_sel,
- * v_lshl_add_u32, v_add_u32_sdwa).  One launch issues
- * blocks * 256 * iters * 16 lane-instructions; time it to obtain the
- * vector-ALU rates the stages are priced against.  Unknown op: THEMIS_ERR_SHAPE.
- */
-int themis_probe_valu(int op, int iters, int blocks, uint32_t *d_sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -52,7 +52,7 @@
  * Parity pins (tests/test_oracle_pins.py): exhaustive enumeration of Eq. 6
  * in oracle/themis_bruteforce.c on tiny pipelines, a hand-worked example,
  * the separable closed form under a loose SLO, monotonicity and refinement
- * invariants, and an independent push-style transcription of Algorithm 1.
+ * invariants, and a forward recurrence over sparse sets of prefix sums.
  */
 #include <stdint.h>
 #include <stdlib.h>

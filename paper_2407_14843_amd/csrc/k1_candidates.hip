@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     const int32_t* __restrict__ c_fixed, const int32_t* __restrict__ tmeta,
     StepEntry* __restrict__ step_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
     uint32_t S, uint32_t K, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick,
-    double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs, int copies_mask,
+    double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs,
     uint64_t class_map, int sparse, uint32_t c_all, uint32_t cs, uint32_t prune_sh,
     uint32_t prune_bins, uint32_t split)
 {
@@ -325,8 +325,6 @@ __global__ __launch_bounds__(256) void k1_candidates(
         uint32_t cm, sh, add, step, base;
         if (cls == NARROW_CLS) {
             cm = 1, sh = 1, add = 0, step = 4u * (NAR_COPY_DW - 1), base = 4u * NAR_CHUNK_DW;
-        } else if (class_copies(cls, copies_mask) == 4) {
-            cm = 3, sh = 2, add = 3, step = (uint32_t)wide_copy_bytes(cls_waves(cls)), base = 0;
         } else {
             cm = 1, sh = 1, add = 1, step = (uint32_t)wide_copy_bytes(cls_waves(cls)), base = 0;
         }
@@ -347,7 +345,7 @@ __global__ __launch_bounds__(256) void k1_candidates(
     }
 }
 
-__global__ void k_zero64x2(unsigned long long* p) { p[0] = p[1] = 0ull; }
+__global__ void k_zero64x3(unsigned long long* p) { p[0] = p[1] = p[2] = 0ull; }
 
 // Undo the bucket order: separate lt / cost arrays [N][S][K], index k.
 __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ step_tab,
@@ -356,7 +354,7 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
                                                 int32_t* __restrict__ lt,
                                                 int32_t* __restrict__ cost, uint32_t rows,
                                                 uint32_t S, uint32_t K, uint32_t Kp, uint32_t nb,
-                                                uint32_t nbs, int copies_mask, uint64_t class_map)
+                                                uint32_t nbs, uint64_t class_map)
 {
     uint32_t g = blockIdx.x * 256u + threadIdx.x;
     if (g >= rows * Kp) return;
@@ -366,7 +364,7 @@ __global__ __launch_bounds__(256) void k_export(const StepEntry* __restrict__ st
     if (T < 0 || e >= bcum[(size_t)row * nbs + nb]) return;
     const StepEntry se = step_tab[g];
     const uint32_t k = se.ck >> 16;
-    lt[(size_t)row * K + k] = (int32_t)lt_of_entry(se.shift, T, class_map, copies_mask);
+    lt[(size_t)row * K + k] = (int32_t)lt_of_entry(se.shift, T, class_map);
     cost[(size_t)row * K + k] = (int32_t)(se.ck & 0xFFFFu);
 }
 
@@ -386,17 +384,19 @@ __global__ __launch_bounds__(256) void k_fill_minus_one(int32_t* __restrict__ a,
 // handles last (s = 0) are left out when they have entries enough for their
 // shortcuts (see worth_shortcut): the first row is then built by a scatter and
 // a scan, and of the last only the answer is computed.  out[1] takes the number
-// of entries the table holds for those instances (the feasible candidates).
+// of entries the table holds for those instances (the feasible candidates),
+// out[2] the cells (model, budget) whose value stage 2 forms: T + 1 per model,
+// less the model handled last where only the answer is computed.
 __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict__ step_tab,
                                                      const uint16_t* __restrict__ bcum,
                                                      const int32_t* __restrict__ tmeta,
                                                      unsigned long long* __restrict__ out,
                                                      uint32_t N, uint32_t S, uint32_t Kp,
-                                                     uint32_t nb, uint32_t nbs, int copies_mask,
-                                                     uint64_t class_map, int pruned)
+                                                     uint32_t nb, uint32_t nbs,
+                                                     uint64_t class_map, int pruned, int steps)
 {
     __shared__ unsigned long long part[256];
-    unsigned long long acc = 0, entries = 0;
+    unsigned long long acc = 0, entries = 0, formed = 0;
     for (uint32_t i = blockIdx.x; i < N; i += gridDim.x) {
         const int32_t T = tmeta[i];
         if (T < 0) continue;
@@ -408,13 +408,16 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
             const uint32_t n = bcum[row * nbs + nb];
             entries += n;
             // the wide kernel's shortcuts for the model it handles first and for the
-            // one it handles last take no relaxations
-            if (wide && (s == S - 1 || (s == 0 && S > 1)) &&
-                worth_shortcut((int)n, npos, cls_waves(cls)))
-                continue;
+            // one it handles last take no relaxations, and of the last one's row only
+            // the answer is formed (the step-row form never forms that row)
+            const bool shortcut = wide && (s == S - 1 || (s == 0 && S > 1)) &&
+                                  worth_shortcut((int)n, npos, cls_waves(cls));
+            const bool answer_only = s == 0 && ((shortcut && S > 1) || (steps && cls != NARROW_CLS));
+            if (!answer_only) formed += (unsigned long long)(T + 1);
+            if (shortcut) continue;
             for (uint32_t e = threadIdx.x; e < n; e += 256)
                 acc += (unsigned long long)(T + 1) -
-                       lt_of_entry(step_tab[row * Kp + e].shift, T, class_map, copies_mask);
+                       lt_of_entry(step_tab[row * Kp + e].shift, T, class_map);
         }
     }
     part[threadIdx.x] = acc;
@@ -426,6 +429,7 @@ __global__ __launch_bounds__(256) void k_count_relax(const StepEntry* __restrict
     if (threadIdx.x == 0) {
         atomicAdd(out, part[0]);
         atomicAdd(out + 1, entries);  // every thread of the workgroup counted the same rows
+        atomicAdd(out + 2, formed);
     }
 }
 
@@ -490,7 +494,7 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
                            (uint32_t)L.S, (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.c_max,
                            (uint32_t)p.r_max, (uint32_t)p.tick_us,
                            (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
-                           (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask, plan.class_map,
+                           (uint32_t)L.nb, (uint32_t)L.nbs, plan.class_map,
                            opts.sparse, (uint32_t)opts.c_all, cs, prune_sh, prune_bins, split);
         return hipGetLastError();
     };
@@ -522,7 +526,7 @@ hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), d_lt, d_cost, rows, (uint32_t)L.S,
                        (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs,
-                       plan.copies_mask, plan.class_map);
+                       plan.class_map);
     return hipGetLastError();
 }
 
@@ -530,15 +534,15 @@ hipError_t launch_count_relaxations(const themis_problem_t& p, const Layout& L, 
                                     unsigned long long* d_count, hipStream_t st)
 {
     const MinplusPlan plan = make_plan(L);
-    hipLaunchKernelGGL(k_zero64x2, dim3(1), dim3(1), 0, st, d_count);
+    hipLaunchKernelGGL(k_zero64x3, dim3(1), dim3(1), 0, st, d_count);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     uint32_t blocks = (uint32_t)(L.N < 4096 ? L.N : 4096);
     hipLaunchKernelGGL(k_count_relax, dim3(blocks), dim3(256), 0, st,
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), d_count, (uint32_t)L.N, (uint32_t)L.S,
-                       (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs, plan.copies_mask,
-                       plan.class_map, p.prune != THEMIS_PRUNE_NONE);
+                       (uint32_t)L.Kp, (uint32_t)L.nb, (uint32_t)L.nbs, plan.class_map,
+                       p.prune != THEMIS_PRUNE_NONE, (p.prune & THEMIS_PRUNE_STEPS) != 0);
     return hipGetLastError();
 }
 

@@ -26,10 +26,10 @@
 // a shift by lt moves the row by an arbitrary number of 2-byte cells, so the
 // previous row is kept in LDS once per residue of the shift: copy m is the row
 // shifted by m cells, and a candidate reads the copy whose residue fits, always
-// aligned.  Two copies with 32-bit reads (lt mod 2) are the default; four copies
-// with 64-bit reads ((-lt) mod 4) halve the LDS instructions but double the LDS
-// footprint, and the resident wavefronts that costs weigh more (measured).  Rows of
-// more than 16384 cells go to the narrow kernel (two copies, static chunks).
+// aligned.  Two copies with 32-bit reads (lt mod 2) are kept: four copies with
+// 64-bit reads halve the LDS instructions but double the LDS footprint, and the
+// resident wavefronts that costs weigh more (measured).  Rows of more than 16384
+// cells go to the narrow kernel (two copies, static chunks).
 // New values stay in registers while the old row is being read.
 //
 // The row is cut into positions of 512 cells.  A candidate only reaches the
@@ -57,7 +57,6 @@ namespace themis {
 namespace {
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ uint32_t pk_add(uint32_t a, uint32_t b)
 {
@@ -120,23 +119,20 @@ __device__ __forceinline__ int prefix_count(const AS_CONST uint16_t* bc, int las
 }
 
 // ------------------------------------------------------------------ wide kernel
-// COPIES = 4: lane elements are quads (4 cells, 8 bytes), two per position,
-//             read with ds_read_b64 from the copy (-lt) mod 4;
-// COPIES = 2: lane elements are pairs (2 cells, 4 bytes), four per position,
-//             read with ds_read_b32 from the copy lt mod 2.  Half the LDS
-//             bandwidth per clock, but half the LDS footprint, so two
-//             workgroups of the longest rows share a compute unit.
-// Either way a position is 512 cells and a lane keeps 4 dwords of it.
+// Lane elements are pairs (2 cells, 4 bytes), four per position, read with
+// ds_read_b32 from the copy lt mod 2.  A position is 512 cells and a lane keeps
+// 4 dwords of it.
 constexpr int POSC = BUCKET_CELLS;    // cells per position
 constexpr int PADB = WIDE_PAD_BYTES;  // bytes of F_INF in front of every copy
 constexpr int AD = 4;                 // accumulator dwords per lane per position
+constexpr int COPIES = WIDE_COPIES;   // shifted copies of the row
 constexpr int CAND_BUF = 512;         // entries of a row staged in LDS at a time
 // Staged entries (the form the sweep reads from LDS) are one dword: the cost in
 // the high half, and in the low half the shift in dwords plus SHIFT_BIAS, which
-// makes it unsigned (shifts reach from -2 * 16384 bytes to +3 copies).
+// makes it unsigned (shifts reach from -2 * 16384 bytes to +1 copy).
 constexpr uint32_t SHIFT_BIAS = 8192;
 static_assert(4 * SHIFT_BIAS >= 2 * WIDE_MAX_CELLS, "the bias covers the longest shift down");
-static_assert(SHIFT_BIAS + 3 * (WIDE_PAD_BYTES + WIDE_MAX_CELLS * 2) / 4 < 65536,
+static_assert(SHIFT_BIAS + (WIDE_PAD_BYTES + WIDE_MAX_CELLS * 2) / 4 < 65536,
               "biased shifts fit sixteen bits");
 static_assert(4 * SHIFT_BIAS >= WIDE_PAD_BYTES + (WIDE_MAX_CELLS / BUCKET_CELLS - 1) * BUCKET_CELLS * 2,
               "the bias covers the parking shift of the last position");
@@ -145,9 +141,8 @@ static_assert(PADB == POSC * 2, "the pad is as long as one position");
 static_assert(16 * 64 * 16 / 32 * 4 <= 2 * PADB,
               "two copies hold a padded dword per cell of the longest row");
 
-template <int COPIES>
 struct Geo {
-    static constexpr int ELT = COPIES == 4 ? 8 : 4;   // bytes per lane element
+    static constexpr int ELT = 4;                     // bytes per lane element
     static constexpr int NE = AD * 4 / ELT;           // lane elements per position
     // byte offset (inside a copy) of a lane's first element of position pos,
     // less the bias that staged entries carry in their shift
@@ -167,19 +162,9 @@ struct Geo {
     template <int NEA>
     static __device__ __forceinline__ void read(uint32_t (&dst)[AD], uint32_t at)
     {
-        if constexpr (COPIES == 4) {
-            const AS_LDS u32x2* src = (const AS_LDS u32x2*)(size_t)at;
+        const AS_LDS uint32_t* src = (const AS_LDS uint32_t*)(size_t)at;
 #pragma unroll
-            for (int q = 0; q < NEA; ++q) {
-                const u32x2 r = src[q * 64];
-                dst[2 * q] = r.x;
-                dst[2 * q + 1] = r.y;
-            }
-        } else {
-            const AS_LDS uint32_t* src = (const AS_LDS uint32_t*)(size_t)at;
-#pragma unroll
-            for (int u = 0; u < NEA; ++u) dst[u] = src[u * 64];
-        }
+        for (int u = 0; u < NEA; ++u) dst[u] = src[u * 64];
     }
     // Lane elements of position pos that hold any cell <= T (pos is one of the
     // row's positions, so at least one does): element q starts 64 * ELT / 2 cells
@@ -205,12 +190,12 @@ struct Geo {
 // they change nothing.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int COPIES, int D, int NEA = Geo<COPIES>::NE>
+template <int D, int NEA = Geo::NE>
 __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, const uint32_t* ent,
                                       int ke, uint32_t byte_pos, uint32_t park)
 {
     static_assert(D == 1 || D == 3, "the buffer ring must divide the group of four");
-    using G = Geo<COPIES>;
+    using G = Geo;
     constexpr int ADA = NEA * (G::ELT / 4);  // accumulator dwords in use
     if (ke <= 0) return;
     constexpr int NQ = D == 1 ? 2 : 3;  // groups of entries held in registers
@@ -270,45 +255,30 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
 // the position size): the elements beyond T are neither read nor relaxed.  The
 // top position is the one every entry reaches, so on short rows this is a
 // sizeable part of all the work.
-template <int COPIES, int D>
+template <int D>
 __device__ __forceinline__ void sweep_live(uint32_t (&acc)[AD], const char* ldsb,
                                            const uint32_t* ent, int ke, uint32_t byte_pos,
                                            uint32_t park, int nea)
 {
-    using G = Geo<COPIES>;
-    if (nea >= G::NE) {
-        sweep<COPIES, D>(acc, ldsb, ent, ke, byte_pos, park);
-    } else if constexpr (G::NE == 2) {
-        sweep<COPIES, D, 1>(acc, ldsb, ent, ke, byte_pos, park);
-    } else {
-        if (nea == 1)
-            sweep<COPIES, D, 1>(acc, ldsb, ent, ke, byte_pos, park);
-        else if (nea == 2)
-            sweep<COPIES, D, 2>(acc, ldsb, ent, ke, byte_pos, park);
-        else
-            sweep<COPIES, D, 3>(acc, ldsb, ent, ke, byte_pos, park);
-    }
+    if (nea >= Geo::NE)
+        sweep<D>(acc, ldsb, ent, ke, byte_pos, park);
+    else if (nea == 1)
+        sweep<D, 1>(acc, ldsb, ent, ke, byte_pos, park);
+    else if (nea == 2)
+        sweep<D, 2>(acc, ldsb, ent, ke, byte_pos, park);
+    else
+        sweep<D, 3>(acc, ldsb, ent, ke, byte_pos, park);
 }
 
 // Clamp a finished position and store it to the HBM row (cells <= T only).
-template <int COPIES>
 __device__ __forceinline__ void store_position(const uint32_t (&acc)[AD], uint16_t* out, int pos,
                                                int lane, int T)
 {
-    using G = Geo<COPIES>;
+    using G = Geo;
 #pragma unroll
     for (int q = 0; q < G::NE; ++q) {
         const int cell = (G::ELT / 2) * (pos * (64 * G::NE) + q * 64 + lane);
-        if (cell <= T) {
-            if constexpr (COPIES == 4) {
-                u32x2 v;
-                v.x = acc[2 * q];
-                v.y = acc[2 * q + 1];
-                *reinterpret_cast<u32x2*>(out + cell) = v;
-            } else {
-                *reinterpret_cast<uint32_t*>(out + cell) = acc[q];
-            }
-        }
+        if (cell <= T) *reinterpret_cast<uint32_t*>(out + cell) = acc[q];
     }
 }
 
@@ -319,12 +289,11 @@ __device__ __forceinline__ void clamp_position(uint32_t (&acc)[AD])
     for (int u = 0; u < AD; ++u) acc[u] = pk_min(acc[u], F_INF2);
 }
 
-template <int COPIES>
 __device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* out, int pos,
                                                 int lane, int T)
 {
     clamp_position(acc);
-    store_position<COPIES>(acc, out, pos, lane, T);
+    store_position(acc, out, pos, lane, T);
 }
 
 // Write one lane element of the new row into the shifted LDS copies.  `at` is
@@ -338,11 +307,6 @@ __device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* o
 __device__ __forceinline__ void lds_store_b32(uint32_t at, uint32_t v)
 {
     asm volatile("ds_write_b32 %0, %1" : : "v"(at), "v"(v) : "memory");
-}
-__device__ __forceinline__ void lds_store_b64(uint32_t at, uint32_t lo, uint32_t hi)
-{
-    const uint64_t v = ((uint64_t)hi << 32) | lo;
-    asm volatile("ds_write_b64 %0, %1" : : "v"(at), "v"(v) : "memory");
 }
 // the low half of v at `at`, the high half at `at` + gap (a multiple of two)
 template <int GAP>
@@ -358,21 +322,6 @@ __device__ __forceinline__ void publish_wait()
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
-__device__ __forceinline__ void publish_quad(uint32_t at, int CSB, uint32_t lo, uint32_t hi)
-{
-    const uint32_t mid = __builtin_amdgcn_alignbit(hi, lo, 16);  // cells c1 c2 of c0 c1 | c2 c3
-    const uint32_t ends = __builtin_amdgcn_perm(hi, lo, 0x07060100u);  // cell c0 | cell c3 << 16
-    const uint32_t a1 = at + (uint32_t)CSB - 2u, a2 = at + 2u * (uint32_t)CSB - 4u,
-                   a3 = at + 3u * (uint32_t)CSB - 6u;
-    lds_store_b64(at, lo, hi);        // copy 0: c0 c1 c2 c3
-    lds_store_halves<6>(a1, ends);    // copy 1: c0 | c1 c2 | c3 from two bytes below
-    lds_store_b32(a1 + 2u, mid);
-    lds_store_b32(a2, lo);            // copy 2: c0 c1 | c2 c3 from four bytes below
-    lds_store_b32(a2 + 4u, hi);
-    lds_store_halves<6>(a3, ends);    // copy 3: c0 | c1 c2 | c3 from six bytes below
-    lds_store_b32(a3 + 2u, mid);
-}
-
 __device__ __forceinline__ void publish_pair(uint32_t at, int CSB, uint32_t v)
 {
     lds_store_b32(at, v);                                  // copy 0: c0 c1
@@ -381,21 +330,15 @@ __device__ __forceinline__ void publish_pair(uint32_t at, int CSB, uint32_t v)
 
 // Write a finished position from the registers of the wavefront that computed
 // it into the LDS copies (cells beyond T stay as they are; nothing reads them).
-template <int COPIES>
 __device__ __forceinline__ void publish_position(const uint32_t (&acc)[AD], char* ldsb, int CSB,
                                                  int pos, int lane, int T)
 {
-    using G = Geo<COPIES>;
+    using G = Geo;
 #pragma unroll
     for (int q = 0; q < G::NE; ++q) {
         const int el = pos * (64 * G::NE) + q * 64 + lane;
-        if ((G::ELT / 2) * el <= T) {
-            const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el);
-            if constexpr (COPIES == 4)
-                publish_quad(at, CSB, acc[2 * q], acc[2 * q + 1]);
-            else
-                publish_pair(at, CSB, acc[q]);
-        }
+        if ((G::ELT / 2) * el <= T)
+            publish_pair(lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el), CSB, acc[q]);
     }
 }
 
@@ -453,13 +396,11 @@ __device__ __forceinline__ void commit_row(const RowPrefetch& pf, const StepEntr
 // The first model of the recurrence by scatter and scan (see the call).  Kept
 // out of line so that its registers do not weigh on the allocation of the sweep
 // loop; every thread of the workgroup calls it.
-template <int COPIES>
 __device__ __attribute__((noinline)) void first_model_by_scan(
     int CSB, const StepEntry* __restrict__ step_tab,
     const uint16_t* __restrict__ bcum, uint16_t* __restrict__ frow, int i, int S, int Kp, int nbs,
     int row_stride, int T, int npos, int cand_buf)
 {
-    using G = Geo<COPIES>;
     // The model handled first (s = S-1) follows the all-zero row f[S], so its
     // row is a running minimum, f[S-1][t] = least cost among the entries with
     // lt <= t, and costs a scatter and a scan instead of a sweep per entry (in
@@ -492,18 +433,11 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
         grow_next = step_tab + (row - 1) * Kp;
         prefetch_row(pf, grow_next, n_next < cand_buf ? n_next : cand_buf);
     }
-    // the F_INF stretch in front of the copies that cell_min does not cover (those
-    // of the first two are written once it has been read)
-    for (int x = tid; x < PADB / 4; x += nt) {
-#pragma unroll
-        for (int m = 2; m < COPIES; ++m) lds[m * (CSB / 4) + x] = F_INF2;
-    }
     for (int x = tid; x < span; x += nt) cell_min[x] = F_INF;
     __syncthreads();
     for (int e = tid; e < n_all; e += nt) {
         const StepEntry se = grow[e];
-        atomicMin(&cell_min[cell_at((int)wide_lt_of_shift(se.shift, COPIES, CSB))],
-                  se.ck & 0xFFFFu);
+        atomicMin(&cell_min[cell_at((int)wide_lt_of_shift(se.shift, CSB))], se.ck & 0xFFFFu);
     }
     __syncthreads();
     const int c0 = tid * 16;
@@ -536,27 +470,14 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
         before = o < before ? o : before;
     }
 #pragma unroll
-    for (int j = 0; j < 16; j += G::ELT / 2) {
+    for (int j = 0; j < 16; j += 2) {
         const int cell = c0 + j;
         if (cell <= T) {
-            uint32_t d[G::ELT / 4];
-#pragma unroll
-            for (int u = 0; u < G::ELT / 4; ++u) {
-                const uint32_t lo = v[j + 2 * u] < before ? v[j + 2 * u] : before;
-                const uint32_t hi = v[j + 2 * u + 1] < before ? v[j + 2 * u + 1] : before;
-                d[u] = lo | (hi << 16);
-            }
-            const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + 2 * cell);
-            if constexpr (COPIES == 4) {
-                publish_quad(at, CSB, d[0], d[1]);
-                u32x2 q;
-                q.x = d[0];
-                q.y = d[1];
-                *reinterpret_cast<u32x2*>(out + cell) = q;
-            } else {
-                publish_pair(at, CSB, d[0]);
-                *reinterpret_cast<uint32_t*>(out + cell) = d[0];
-            }
+            const uint32_t lo = v[j] < before ? v[j] : before;
+            const uint32_t hi = v[j + 1] < before ? v[j + 1] : before;
+            const uint32_t d = lo | (hi << 16);
+            publish_pair(lds_address(ldsb) + (uint32_t)(PADB + 2 * cell), CSB, d);
+            *reinterpret_cast<uint32_t*>(out + cell) = d;
         }
     }
     publish_wait();
@@ -566,7 +487,6 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
 
 // The answer of an instance without its last row (see the call).  Out of line
 // for the same reason as first_model_by_scan(); every thread calls it.
-template <int COPIES>
 __device__ __attribute__((noinline)) void answer_from_row_one(int CSB,
                                                               const StepEntry* __restrict__ grow,
                                                               int n_all, int cand_buf, int T,
@@ -594,7 +514,7 @@ __device__ __attribute__((noinline)) void answer_from_row_one(int CSB,
     auto entry_of = [&](int x, uint32_t& lt, uint32_t& co) {
         const uint32_t e = x < cand_buf ? cbuf[x] : staged(grow[x]);
         co = e >> 16;
-        lt = wide_lt_of_shift(4u * ((e & 0xFFFFu) - SHIFT_BIAS), COPIES, CSB);
+        lt = wide_lt_of_shift(4u * ((e & 0xFFFFu) - SHIFT_BIAS), CSB);
     };
     auto wave_min_into = [&](uint32_t v, uint32_t* dst) {
 #pragma unroll
@@ -667,14 +587,14 @@ __device__ __attribute__((noinline)) void answer_from_row_one(int CSB,
 // Both forms are compiled for eight wavefronts per SIMD (64 VGPRs): the LDS
 // footprints of the work classes are sized for 32 resident wavefronts per
 // compute unit, which a few registers more would silently cut to 28.
-template <int COPIES, bool FIXED>
+template <bool FIXED>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
     int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int32_t* __restrict__ ans, int N,
     int S, int Kp, int nbs, int row_stride, int cls, int low_cls, int cand_buf)
 {
-    using G = Geo<COPIES>;
+    using G = Geo;
     constexpr int DEPTH = 1;
     extern __shared__ uint32_t lds[];
     const int CSB = wide_copy_bytes(cls_waves(cls));  // bytes per copy: pad + the longest row
@@ -724,7 +644,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             commit_row(pf, step_tab + row * Kp, cbuf);
             if (tid == 0) *next_pos = npos - 1;
         } else {
-            first_model_by_scan<COPIES>(CSB, step_tab, bcum, frow, i, S, Kp, nbs, row_stride, T,
+            first_model_by_scan(CSB, step_tab, bcum, frow, i, S, Kp, nbs, row_stride, T,
                                         npos, cand_buf);
             if (tid == 0) *next_pos = npos - 1;
         }
@@ -738,7 +658,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             const int n_all = bcum_at(bc, npos);  // entries that reach the top position: all feasible ones
 
             if (!FIXED && s == 0 && S > 1 && worth_shortcut(n_all, npos, (int)blockDim.x >> 6)) {
-                answer_from_row_one<COPIES>(CSB, grow, n_all, cand_buf, T, ans + 2 * i);
+                answer_from_row_one(CSB, grow, n_all, cand_buf, T, ans + 2 * i);
                 break;
             }
 
@@ -761,14 +681,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 if (p_hi >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
-                    sweep_live<COPIES, DEPTH>(r_hi, ldsb, ent, bcum_at(bc, p_hi + 1), G::lane_byte(p_hi, lane),
+                    sweep_live<DEPTH>(r_hi, ldsb, ent, bcum_at(bc, p_hi + 1), G::lane_byte(p_hi, lane),
                                               G::park(p_hi), G::live_elements(p_hi, T));
                     clamp_position(r_hi);
                 }
                 if (p_lo >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_lo[u] = 0xFFFFFFFFu;
-                    sweep<COPIES, DEPTH>(r_lo, ldsb, ent, bcum_at(bc, p_lo + 1), G::lane_byte(p_lo, lane),
+                    sweep<DEPTH>(r_lo, ldsb, ent, bcum_at(bc, p_lo + 1), G::lane_byte(p_lo, lane),
                                   G::park(p_lo));
                     clamp_position(r_lo);
                 }
@@ -782,9 +702,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                     uint32_t acc[AD];
 #pragma unroll
                     for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
-                    sweep_live<COPIES, DEPTH>(acc, ldsb, ent, bcum_at(bc, p + 1), G::lane_byte(p, lane),
+                    sweep_live<DEPTH>(acc, ldsb, ent, bcum_at(bc, p + 1), G::lane_byte(p, lane),
                                               G::park(p), G::live_elements(p, T));
-                    finish_position<COPIES>(acc, out, p, lane, T);
+                    finish_position(acc, out, p, lane, T);
                 }
             } else {
                 // a long row goes through the buffer in parts; every wavefront keeps
@@ -794,7 +714,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                     uint32_t acc[AD];
 #pragma unroll
                     for (int u = 0; u < AD; ++u) acc[u] = 0xFFFFFFFFu;
-                    finish_position<COPIES>(acc, out, p0, lane, T);  // start from "none"
+                    finish_position(acc, out, p0, lane, T);  // start from "none"
                 }
                 for (int seg = 0; seg < n_all; seg += cand_buf) {
                     const int cnt = n_all - seg < cand_buf ? n_all - seg : cand_buf;
@@ -817,19 +737,11 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 #pragma unroll
                         for (int q = 0; q < G::NE; ++q) {
                             const int cell = (G::ELT / 2) * (p0 * (64 * G::NE) + q * 64 + lane);
-                            if constexpr (COPIES == 4) {
-                                u32x2 v;
-                                v.x = v.y = F_INF2;
-                                if (cell <= T) v = *reinterpret_cast<const u32x2*>(out + cell);
-                                acc[2 * q] = v.x;
-                                acc[2 * q + 1] = v.y;
-                            } else {
-                                acc[q] = cell <= T ? *reinterpret_cast<const uint32_t*>(out + cell)
-                                                   : F_INF2;
-                            }
+                            acc[q] = cell <= T ? *reinterpret_cast<const uint32_t*>(out + cell)
+                                               : F_INF2;
                         }
-                        sweep<COPIES, DEPTH>(acc, ldsb, ent, ke, G::lane_byte(p0, lane), G::park(p0));
-                        finish_position<COPIES>(acc, out, p0, lane, T);
+                        sweep<DEPTH>(acc, ldsb, ent, ke, G::lane_byte(p0, lane), G::park(p0));
+                        finish_position(acc, out, p0, lane, T);
                     }
                 }
             }
@@ -839,12 +751,12 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 // complete in, and neither barrier waits for them.
                 if (s > 0) {
                     lds_barrier();  // every wavefront is done with the old row
-                    if (p_hi >= 0) publish_position<COPIES>(r_hi, ldsb, CSB, p_hi, lane, T);
-                    if (p_lo >= 0) publish_position<COPIES>(r_lo, ldsb, CSB, p_lo, lane, T);
+                    if (p_hi >= 0) publish_position(r_hi, ldsb, CSB, p_hi, lane, T);
+                    if (p_lo >= 0) publish_position(r_lo, ldsb, CSB, p_lo, lane, T);
                     commit_row(pf, grow_next, cbuf);
                 }
-                if (p_hi >= 0) store_position<COPIES>(r_hi, out, p_hi, lane, T);
-                if (p_lo >= 0) store_position<COPIES>(r_lo, out, p_lo, lane, T);
+                if (p_hi >= 0) store_position(r_hi, out, p_hi, lane, T);
+                if (p_lo >= 0) store_position(r_lo, out, p_lo, lane, T);
                 if (s == 0) break;
                 lds_barrier();
                 continue;
@@ -854,12 +766,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             __syncthreads();  // every wavefront is done with the old row; the new one is stored
             for (int el = tid; el * (G::ELT / 2) <= T; el += (int)blockDim.x) {
                 const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el);
-                if constexpr (COPIES == 4) {
-                    const u32x2 v = *reinterpret_cast<const u32x2*>(out + 4 * el);
-                    publish_quad(at, CSB, v.x, v.y);
-                } else {
-                    publish_pair(at, CSB, *reinterpret_cast<const uint32_t*>(out + 2 * el));
-                }
+                publish_pair(at, CSB, *reinterpret_cast<const uint32_t*>(out + 2 * el));
             }
             // hand the next model its entries and its position counter
             commit_row(pf, grow_next, cbuf);
@@ -970,31 +877,31 @@ int cu_count()
 
 constexpr size_t LDS_PER_CU = 160 * 1024;
 
-inline size_t wide_lds_bytes(int copies, int waves, int cand_buf)
+inline size_t wide_lds_bytes(int waves, int cand_buf)
 {
-    return (size_t)copies * wide_copy_bytes(waves) + 16 + (cand_buf + 16) * sizeof(uint32_t);
+    return (size_t)COPIES * wide_copy_bytes(waves) + 16 + (cand_buf + 16) * sizeof(uint32_t);
 }
 
-inline int wide_groups_per_cu(int copies, int waves, int cand_buf)
+inline int wide_groups_per_cu(int waves, int cand_buf)
 {
-    int per_cu = (int)(LDS_PER_CU / wide_lds_bytes(copies, waves, cand_buf));
+    int per_cu = (int)(LDS_PER_CU / wide_lds_bytes(waves, cand_buf));
     if (per_cu > 32 / waves) per_cu = 32 / waves;
     return per_cu < 1 ? 1 : per_cu;
 }
 
-template <int COPIES, bool FIXED>
+template <bool FIXED>
 hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int low, int cus)
 {
     const int nwc = CLS_WAVES[c];
     const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
-    const size_t lds_bytes = wide_lds_bytes(COPIES, nwc, cand_buf);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_wide<COPIES, FIXED>),
+    const size_t lds_bytes = wide_lds_bytes(nwc, cand_buf);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_wide<FIXED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(LDS_PER_CU - 1024));
     if (e != hipSuccess) return e;
-    long long grid = (long long)cus * wide_groups_per_cu(COPIES, nwc, cand_buf);
+    long long grid = (long long)cus * wide_groups_per_cu(nwc, cand_buf);
     if (grid > L_.N) grid = L_.N;
-    hipLaunchKernelGGL((k2_minplus_wide<COPIES, FIXED>), dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
+    hipLaunchKernelGGL((k2_minplus_wide<FIXED>), dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
                        (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
                        (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
                        (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off),
@@ -1011,7 +918,6 @@ MinplusPlan make_plan(const Layout& L_)
     pl.cus = cu_count();
     pl.top = class_of_budget(L_.t_max);
     pl.top_wide = pl.top == NARROW_CLS ? N_WIDE_CLS - 1 : pl.top;
-    pl.copies_mask = wide_copies_mask();
     // Heads of the class groups (bit c set = class c has a launch of its own).
     // One launch for everything is best until the batch is large and its longest
     // rows need twelve wavefronts or more; then the rows of up to eight chunks get
@@ -1024,8 +930,7 @@ MinplusPlan make_plan(const Layout& L_)
     {
         const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
         const long long resident =
-            (long long)pl.cus * wide_groups_per_cu(class_copies(pl.top_wide, pl.copies_mask),
-                                                   CLS_WAVES[pl.top_wide], cand_buf);
+            (long long)pl.cus * wide_groups_per_cu(CLS_WAVES[pl.top_wide], cand_buf);
         if (CLS_WAVES[pl.top_wide] >= 12 && L_.N >= 16 * resident) heads |= 1u << SECOND_HEAD;
     }
     pl.class_map = 0;
@@ -1064,16 +969,12 @@ hipError_t launch_minplus(const themis_problem_t& p, const Layout& L_, char* ws,
         int low = c;
         while (low > 0 && head_of_class(low - 1, pl.class_map) == c) --low;
         if (p.prune & THEMIS_PRUNE_STEPS) {
-            e = launch_steps_group(L_, ws, st, c, low, pl.cus, class_copies(c, pl.copies_mask));
+            e = launch_steps_group(L_, ws, st, c, low, pl.cus);
             if (e != hipSuccess) return e;
             continue;
         }
-        if (class_copies(c, pl.copies_mask) == 2)
-            e = fixed ? launch_wide_class<2, true>(L_, ws, st, c, low, pl.cus)
-                      : launch_wide_class<2, false>(L_, ws, st, c, low, pl.cus);
-        else
-            e = fixed ? launch_wide_class<4, true>(L_, ws, st, c, low, pl.cus)
-                      : launch_wide_class<4, false>(L_, ws, st, c, low, pl.cus);
+        e = fixed ? launch_wide_class<true>(L_, ws, st, c, low, pl.cus)
+                  : launch_wide_class<false>(L_, ws, st, c, low, pl.cus);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

@@ -30,10 +30,7 @@
 namespace themis {
 namespace {
 
-#ifndef THEMIS_STEP_LIST
-#define THEMIS_STEP_LIST 1024  // a build with a tiny list exercises the path for lists that do not fit
-#endif
-constexpr int STEP_LIST = THEMIS_STEP_LIST;  // breakpoints of a row kept as a list
+constexpr int STEP_LIST = 1024;  // breakpoints of a row kept as a list
 constexpr int STEP_ENTS = 512;   // candidates of a model staged at a time
 constexpr int STEP_RUN = 16;     // most cells a thread scans (1024 cells per wavefront)
 constexpr int STEP_HDR = 64;     // dwords: queue slot, list length, answer, per-wavefront partials
@@ -81,7 +78,7 @@ __global__ __launch_bounds__(1024) void k2_steps(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
     int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int32_t* __restrict__ ans, int N,
-    int S, int Kp, int nbs, int row_stride, int cls, int low_cls, int copies)
+    int S, int Kp, int nbs, int row_stride, int cls, int low_cls)
 {
     extern __shared__ uint32_t lds[];
     const int nt = (int)blockDim.x, nw = nt >> 6;
@@ -157,7 +154,7 @@ __global__ __launch_bounds__(1024) void k2_steps(
             auto stage = [&](int e0, int cnt) {
                 for (int x = tid; x < cnt; x += nt) {
                     const StepEntry se = grow[e0 + x];
-                    ent[x] = (wide_lt_of_shift(se.shift, copies, CSB) << 16) | (se.ck & 0xFFFFu);
+                    ent[x] = (wide_lt_of_shift(se.shift, CSB) << 16) | (se.ck & 0xFFFFu);
                 }
             };
 
@@ -266,7 +263,7 @@ size_t steps_lds_bytes(int waves)
 // One launch for the class group whose longest rows are class `cls` (see
 // make_plan); the instances of classes low .. cls are served.
 hipError_t launch_steps_group(const Layout& L_, char* ws, hipStream_t st, int cls, int low,
-                              int cus, int copies)
+                              int cus)
 {
     const int nw = CLS_WAVES[cls];
     const size_t lds_bytes = steps_lds_bytes(nw);
@@ -284,7 +281,7 @@ hipError_t launch_steps_group(const Layout& L_, char* ws, hipStream_t st, int cl
                        (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
                        (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off),
                        (int32_t*)(ws + L_.ans_off), L_.N, L_.S, L_.Kp, L_.nbs, L_.row_stride, cls,
-                       low, copies);
+                       low);
     return hipGetLastError();
 }
 

@@ -23,7 +23,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     const uint16_t* __restrict__ frow, const int32_t* __restrict__ ans,
     int32_t* __restrict__ status,
     int32_t* __restrict__ cost_out, int32_t* __restrict__ ticks_out, int32_t* __restrict__ cfg,
-    BatchList bl, int N, int S, int Kp, int nbs, int row_stride, int copies_mask, uint64_t class_map,
+    BatchList bl, int N, int S, int Kp, int nbs, int row_stride, uint64_t class_map,
     int sparse)
 {
     const int lane = threadIdx.x & 63;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
                 const int e = e0 + 64 * g + lane;
-                lt[g] = e < n ? (int)lt_of_entry(se[g].shift, T, class_map, copies_mask) : t + 1;
+                lt[g] = e < n ? (int)lt_of_entry(se[g].shift, T, class_map) : t + 1;
                 rest[g] = 0u;
                 if (s + 1 < S) rest[g] = next[lt[g] <= t ? t - lt[g] : 0];
             }
@@ -170,7 +170,7 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
                        (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
                        (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
                        (const int32_t*)(ws + L.ans_off), d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.Kp, L.nbs, L.row_stride,
-                       plan.copies_mask, plan.class_map, opts.sparse);
+                       plan.class_map, opts.sparse);
     return hipGetLastError();
 }
 

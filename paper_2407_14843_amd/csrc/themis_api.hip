@@ -2,27 +2,7 @@
 // launches.  No allocation, no synchronisation, no state.
 #include "themis_internal.h"
 
-#include <cstdlib>
-
 using namespace themis;
-
-namespace themis {
-
-// Every wide class keeps two row copies by default: the smaller LDS footprint
-// buys more resident wavefronts, which pays more than the wider reads of the
-// four-copy layout.  THEMIS_WIDE_COPIES_MASK (bit c = class c keeps two)
-// overrides the choice for tuning runs.
-int wide_copies_mask()
-{
-    static const int mask = [] {
-        const char* e = std::getenv("THEMIS_WIDE_COPIES_MASK");
-        if (e && *e) return (int)std::strtol(e, nullptr, 0) & ((1 << N_WIDE_CLS) - 1);
-        return (1 << N_WIDE_CLS) - 1;
-    }();
-    return mask;
-}
-
-}  // namespace themis
 
 namespace {
 
@@ -98,7 +78,7 @@ int solve(const themis_problem_t* p, const int32_t* d_coef, const int32_t* d_lam
 
 extern "C" {
 
-int themis_version(void) { return 101; }
+int themis_version(void) { return 102; }
 
 int themis_check_problem(const themis_problem_t* p) { return check(p); }
 
@@ -339,26 +319,6 @@ int themis_count_relaxations(const themis_problem_t* p, const void* d_workspace,
                                     static_cast<hipStream_t>(stream)) == hipSuccess
                ? THEMIS_OK
                : THEMIS_ERR_LAUNCH;
-}
-
-int themis_probe_lds_read(int width, int misalign, int iters, int blocks, uint32_t* d_sink,
-                          void* stream)
-{
-    if (!d_sink) return THEMIS_ERR_NULL;
-    if (iters < 1 || blocks < 1 || blocks > 65536) return THEMIS_ERR_SHAPE;
-    hipError_t e = launch_lds_probe(width, misalign, iters, blocks, d_sink,
-                                    static_cast<hipStream_t>(stream));
-    if (e == hipErrorInvalidValue) return THEMIS_ERR_SHAPE;
-    return e == hipSuccess ? THEMIS_OK : THEMIS_ERR_LAUNCH;
-}
-
-int themis_probe_valu(int op, int iters, int blocks, uint32_t* d_sink, void* stream)
-{
-    if (!d_sink) return THEMIS_ERR_NULL;
-    if (iters < 1 || blocks < 1 || blocks > 65536) return THEMIS_ERR_SHAPE;
-    hipError_t e = launch_valu_probe(op, iters, blocks, d_sink, static_cast<hipStream_t>(stream));
-    if (e == hipErrorInvalidValue) return THEMIS_ERR_SHAPE;
-    return e == hipSuccess ? THEMIS_OK : THEMIS_ERR_LAUNCH;
 }
 
 }  // extern "C"

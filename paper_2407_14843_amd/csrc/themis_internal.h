@@ -72,27 +72,21 @@ __host__ __device__ inline int class_of_budget(int T)
 }
 
 // ---- LDS geometry of the min-plus stage (stage 1 bakes it into StepEntry) --
-// Wide kernel: two or four copies of the row, copy m holds cell t at half-word
+// Wide kernel: two copies of the row, copy m holds cell t at half-word
 // (WIDE_PAD_BYTES/2 + t - m); each copy is WIDE_PAD_BYTES of F_INF followed by
 // two positions (2 * 512 cells) per wavefront of the class.
 constexpr int WIDE_PAD_BYTES = BUCKET_CELLS * 2;
+constexpr int WIDE_COPIES = 2;
 
 __host__ __device__ inline int wide_copy_bytes(int waves)
 {
     return WIDE_PAD_BYTES + waves * WIDE_CHUNK * 2;
 }
 
-// Row copies a work class keeps: two (32-bit reads) or four (64-bit reads, twice
-// the LDS footprint).  Two for every class unless the tuning knob says otherwise.
-int wide_copies_mask();  // bit c set: wide class c keeps two copies
-__host__ __device__ inline int class_copies(int cls, int mask) { return (mask >> cls) & 1 ? 2 : 4; }
-
-// Four copies: lt = 4h - m, read copy m, h quads (8 bytes) below the lane's quad.
-// Two copies:  lt = 2h - m, read copy m, h pairs (4 bytes) below the lane's pair.
-__host__ __device__ inline uint32_t wide_shift(uint32_t lt, int copies, int copy_bytes)
+// lt = 2h - m: read copy m, h pairs (4 bytes) below the lane's pair.
+__host__ __device__ inline uint32_t wide_shift(uint32_t lt, int copy_bytes)
 {
-    return copies == 4 ? ((0u - lt) & 3u) * (uint32_t)copy_bytes - 8u * ((lt + 3u) >> 2)
-                       : (lt & 1u) * (uint32_t)copy_bytes - 4u * ((lt + 1u) >> 1);
+    return (lt & 1u) * (uint32_t)copy_bytes - 4u * ((lt + 1u) >> 1);
 }
 
 // Narrow kernel: 16 wavefronts x 1024 dwords; copy A holds cells (2j, 2j+1) in
@@ -110,16 +104,15 @@ __host__ __device__ inline uint32_t narrow_shift(uint32_t lt)
                            : (uint32_t)NAR_CHUNK_DW - h);
 }
 
-// Inverses.  Wide: the term 8h (4h) is less than one copy, so the sign of the
-// offset taken modulo the copy size tells the copy.  Narrow: even shifts lie at
-// or below the pad, odd ones above it.
-__host__ __device__ inline uint32_t wide_lt_of_shift(uint32_t shift, int copies, int copy_bytes)
+// Inverses.  Wide: the term 4h is less than one copy, so the sign of the offset
+// tells the copy.  Narrow: even shifts lie at or below the pad, odd ones above it.
+__host__ __device__ inline uint32_t wide_lt_of_shift(uint32_t shift, int copy_bytes)
 {
     const int32_t sh = (int32_t)shift;
-    // sh = m * copy_bytes - e * h with 0 <= e * h < copy_bytes
-    const int32_t m = (sh > 0) + (sh > copy_bytes) + (sh > 2 * copy_bytes);  // ceil(sh / copy_bytes)
+    // sh = m * copy_bytes - 4 h with 0 <= 4 h < copy_bytes
+    const int32_t m = sh > 0;
     const uint32_t back = (uint32_t)(m * copy_bytes - sh);
-    return copies == 4 ? 4u * (back >> 3) - (uint32_t)m : 2u * (back >> 2) - (uint32_t)m;
+    return 2u * (back >> 2) - (uint32_t)m;
 }
 
 __host__ __device__ inline uint32_t narrow_lt_of_shift(uint32_t shift)
@@ -158,7 +151,6 @@ struct MinplusPlan {
     int top;          // highest class any instance can be in
     int top_wide;     // highest wide class in use
     uint64_t class_map;  // see head_of_class()
-    int copies_mask;  // see wide_copies_mask()
 };
 MinplusPlan make_plan(const Layout& L);
 
@@ -232,15 +224,13 @@ hipError_t launch_minplus(const themis_problem_t& p, const Layout& L, char* ws,
                           hipStream_t st);
 // the min-plus stage with rows as step functions, for one group of classes
 hipError_t launch_steps_group(const Layout& L, char* ws, hipStream_t st, int cls, int low,
-                              int cus, int copies);
+                              int cus);
 // lt of an entry of an instance with budget T (see StepEntry)
-__host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, uint64_t class_map,
-                                                int copies_mask)
+__host__ __device__ inline uint32_t lt_of_entry(uint32_t shift, int T, uint64_t class_map)
 {
     const int cls = effective_class(T, class_map);
     if (cls == NARROW_CLS) return narrow_lt_of_shift(shift);
-    return wide_lt_of_shift(shift, class_copies(cls, copies_mask),
-                            wide_copy_bytes(cls_waves(cls)));
+    return wide_lt_of_shift(shift, wide_copy_bytes(cls_waves(cls)));
 }
 
 hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L,
@@ -345,10 +335,5 @@ hipError_t launch_export_candidates(const Layout& L, const char* ws, int32_t* d_
                                     int32_t* d_cost, hipStream_t st);
 hipError_t launch_count_relaxations(const themis_problem_t& p, const Layout& L, const char* ws,
                                     unsigned long long* d_count, hipStream_t st);
-
-hipError_t launch_lds_probe(int width, int misalign, int iters, int blocks, uint32_t* sink,
-                            hipStream_t st);
-
-hipError_t launch_valu_probe(int op, int iters, int blocks, uint32_t* sink, hipStream_t st);
 
 }  // namespace themis

@@ -1,9 +1,25 @@
-// LDS read-bandwidth probe.  Not part of the solve: it measures the figure the
-// min-plus kernel's roofline is priced against.  Every lane of every wavefront
-// streams ds_read instructions of one width and alignment over a 64 KB window,
-// lanes contiguous (conflict-free), and nothing else; the caller times the
-// launch and divides the bytes read by the duration.
-#include "themis_internal.h"
+// LDS read-bandwidth and vector-issue probes.  Not part of the solve and not
+// part of its library: a small library of its own (libthemis_probe.so) that the
+// benchmark loads to measure the figures the kernels' rooflines are priced
+// against.  Every lane of every wavefront streams instructions of one kind and
+// nothing else; the caller times the launch.
+//
+//   probe_lds_read(width, misalign, iters, blocks, d_sink, stream)
+//     conflict-free LDS reads of `width` bytes (4, 8 or 16) at byte misalignment
+//     `misalign` (0, or 2/4/8 where smaller than the width; with width 8, -1 = two
+//     adjacent dwords by ds_read2_b32 at 4-byte alignment, -2 = ds_read2st64_b32).
+//     One launch reads blocks * 1024 * iters * 4 * width bytes.
+//   probe_valu(op, iters, blocks, d_sink, stream)
+//     iters * 16 independent vector instructions per lane (op 0 v_pk_add_u16,
+//     1 v_pk_min_u16, 2 v_add_u32, 3 v_min_u32, 4 the two packed ones alternating,
+//     5 v_pk_add_u16 with a scalar operand; 6..20 double-precision and integer
+//     instructions of the candidate stage; 21..24 address and operand-select forms
+//     of the min-plus stage).  One launch issues blocks * 256 * iters * 16
+//     lane-instructions.
+// Both return 0, -1 (null sink), -2 (unsupported combination) or -6 (launch
+// refused).  d_sink is one uint32 of device memory; stream a hipStream_t.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace themis {
 namespace {
@@ -232,3 +248,27 @@ hipError_t launch_valu_probe(int op, int iters, int blocks, uint32_t* sink, hipS
 }
 
 }  // namespace themis
+
+extern "C" {
+
+int probe_lds_read(int width, int misalign, int iters, int blocks, uint32_t* d_sink, void* stream)
+{
+    if (!d_sink) return -1;
+    if (iters < 1 || blocks < 1 || blocks > 65536) return -2;
+    hipError_t e = themis::launch_lds_probe(width, misalign, iters, blocks, d_sink,
+                                            static_cast<hipStream_t>(stream));
+    if (e == hipErrorInvalidValue) return -2;
+    return e == hipSuccess ? 0 : -6;
+}
+
+int probe_valu(int op, int iters, int blocks, uint32_t* d_sink, void* stream)
+{
+    if (!d_sink) return -1;
+    if (iters < 1 || blocks < 1 || blocks > 65536) return -2;
+    hipError_t e = themis::launch_valu_probe(op, iters, blocks, d_sink,
+                                             static_cast<hipStream_t>(stream));
+    if (e == hipErrorInvalidValue) return -2;
+    return e == hipSuccess ? 0 : -6;
+}
+
+}  // extern "C"

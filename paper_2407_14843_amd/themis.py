@@ -29,7 +29,7 @@ EXPORTS = [
     "themis_memo_workspace_bytes", "themis_solve_distinct",
     "themis_stage_candidates",
     "themis_stage_minplus", "themis_stage_backtrack", "themis_export_candidates",
-    "themis_count_relaxations", "themis_probe_lds_read", "themis_probe_valu",
+    "themis_count_relaxations",
 ]
 
 
@@ -92,10 +92,6 @@ def lib():
         L.themis_export_candidates.argtypes = [P, vp, sz, vp, vp, vp]
         L.themis_count_relaxations.restype = ctypes.c_int
         L.themis_count_relaxations.argtypes = [P, vp, sz, vp, vp]
-        L.themis_probe_lds_read.restype = ctypes.c_int
-        L.themis_probe_lds_read.argtypes = [ctypes.c_int] * 4 + [vp, vp]
-        L.themis_probe_valu.restype = ctypes.c_int
-        L.themis_probe_valu.argtypes = [ctypes.c_int] * 3 + [vp, vp]
         _lib = L
     return _lib
 
@@ -247,22 +243,11 @@ def themis_export_candidates(p, workspace, lt, cost, stream=None):
 
 
 def themis_count_relaxations(p, workspace, count, stream=None):
-    if count.numel() < 2:
-        raise ValueError("count takes two values: relaxations, table entries")
+    if count.numel() < 3:
+        raise ValueError("count takes three values: relaxations, table entries, cells formed")
     _chk("themis_count_relaxations", lib().themis_count_relaxations(
         ctypes.byref(p), _dp(workspace, torch.uint8), workspace.numel(),
         _dp(count, torch.int64), _stream(stream)))
-
-
-def themis_probe_lds_read(width, misalign, iters, blocks, sink, stream=None):
-    _chk("themis_probe_lds_read", lib().themis_probe_lds_read(
-        int(width), int(misalign), int(iters), int(blocks), _dp(sink, torch.int32),
-        _stream(stream)))
-
-
-def themis_probe_valu(op, iters, blocks, sink, stream=None):
-    _chk("themis_probe_valu", lib().themis_probe_valu(
-        int(op), int(iters), int(blocks), _dp(sink, torch.int32), _stream(stream)))
 
 
 # ---------------------------------------------------------------- conveniences

@@ -227,12 +227,13 @@ def tiny_random(rng: np.random.Generator, variant: int = JOINT, n_inst: int = 1,
 def medium_random(rng: np.random.Generator, variant: int = JOINT) -> Workload:
     """A random batch with a search space of realistic size (up to 32 cores x 8
     batch sizes, up to 9000 grid cells, up to 5 models) that the CPU checker still
-    solves in a fraction of a second; every shape parameter is drawn."""
+    solves in a fraction of a second; every shape parameter is drawn, with no
+    regard to what a solver accepts (S * r_max * c_max can exceed a 16-bit total)."""
     n = int(rng.integers(1, 40))
     S = int(rng.integers(1, 6))
     c_max = int(rng.integers(1, 33))
     batch_sizes = sorted(set(int(x) for x in rng.integers(1, 129, int(rng.integers(1, 9)))))
-    r_max = min(int(rng.integers(1, 32767 // (S * c_max) + 1)), 64)
+    r_max = int(rng.choice([1, 2, 3, 5, 8, 16, 32, 64, 100, 250, 1000]))
     tick = int(rng.choice([100, 250, 500, 1000]))
     slo_max = int(rng.integers(1, 9000)) * tick
     coef = _draw_coef(rng, (n, S), a=(1000, 40000), k=(100, 10000), q=(0, 100), p=(1, 40),

@@ -28,16 +28,17 @@ static int failures = 0;
         }                                                 \
     } while (0)
 
-static void check_wide(int copies)
+static void check_wide()
 {
-    const int elt = copies == 4 ? 8 : 4;  // bytes per lane element
+    const int copies = WIDE_COPIES;
+    const int elt = 4;  // bytes per lane element
     for (int c = 0; c < N_WIDE_CLS; ++c) {
         const int csb = wide_copy_bytes(CLS_WAVES[c]);
         const int cells = CLS_WAVES[c] * WIDE_CHUNK;
         CHECK(csb % elt == 0 && WIDE_PAD_BYTES % elt == 0, "class %d", c);
         for (int lt = 0; lt < cells; ++lt) {
-            const uint32_t shift = wide_shift((uint32_t)lt, copies, csb);
-            CHECK(wide_lt_of_shift(shift, copies, csb) == (uint32_t)lt, "class %d copies %d lt %d", c,
+            const uint32_t shift = wide_shift((uint32_t)lt, csb);
+            CHECK(wide_lt_of_shift(shift, csb) == (uint32_t)lt, "class %d copies %d lt %d", c,
                   copies, lt);
             // elements of the position the entry's bucket starts in, of the last
             // position, and one straddling lt
@@ -115,13 +116,8 @@ static void check_classes()
           "effective classes");
     // an entry is decoded with the geometry of the class that serves the instance
     const int T = 700;  // class 0, served by class 2
-    for (int copies_mask : {0x3FF, 0}) {
-        const int copies = class_copies(2, copies_mask);
-        const uint32_t shift = wide_shift(345u, copies, wide_copy_bytes(CLS_WAVES[2]));
-        CHECK(lt_of_entry(shift, T, map, copies_mask) == 345u, "copies %d", copies);
-    }
-    CHECK(lt_of_entry(narrow_shift(20001u), 30000, map, 0x3FF) == 20001u, "narrow entry");
-    CHECK(class_copies(3, 0x3FF) == 2 && class_copies(3, 0) == 4, "copies mask");
+    CHECK(lt_of_entry(wide_shift(345u, wide_copy_bytes(CLS_WAVES[2])), T, map) == 345u, "wide entry");
+    CHECK(lt_of_entry(narrow_shift(20001u), 30000, map) == 20001u, "narrow entry");
 }
 
 static void check_layout()
@@ -166,8 +162,7 @@ static void check_layout()
 int main()
 {
     check_layout();
-    check_wide(2);
-    check_wide(4);
+    check_wide();
     check_narrow();
     check_classes();
     if (failures) {

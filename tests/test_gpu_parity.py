@@ -221,17 +221,26 @@ def _sample(n, k, seed):
     return np.sort(np.random.default_rng(seed).choice(n, size=k, replace=False))
 
 
-def test_full_workload1_every_instance(T, oracle):
-    w = wl.workload(1)
+def test_full_workload1_every_instance(T, full_checker):
+    w, want = full_checker(1)
     got = gpu_solve(T, w)
-    want = oracle.solve(w, threads=8)
     assert_same(got, want)
+
+
+@pytest.mark.parametrize("idx", [2, 3])
+def test_full_size_every_instance(T, full_checker, idx):
+    """Workloads 2 and 3 at full size, in the launch configuration the benchmark
+    times: every instance against the checker."""
+    w, want = full_checker(idx)
+    got = gpu_solve(T, w)
+    assert_same(got, want)
+    assert (want[0] == 0).mean() > 0.5
 
 
 @pytest.mark.parametrize("idx,k", [(2, 160), (3, 128)])
 def test_full_size_sampled(T, oracle, idx, k):
-    """The launch configuration the benchmark times, checked on a seeded sample
-    of instances (instances are independent, so each is checked exactly)."""
+    """A quick pre-check of the same two batches: a seeded sample of instances
+    against the checker, and properties that hold for every instance."""
     w = wl.workload(idx)
     got = gpu_solve(T, w)
     pick = _sample(w.n_inst, k, idx)
@@ -370,7 +379,7 @@ def test_relaxation_count(T, oracle):
     w = wl.workload(1, 50)
     b = T.DeviceBatch(w)
     T.themis_stage_candidates(b.p, b.coef, b.lam, b.slo_us, None, b.workspace)
-    cnt = torch.zeros(2, dtype=torch.int64, device="cuda:0")
+    cnt = torch.zeros(3, dtype=torch.int64, device="cuda:0")
     T.themis_count_relaxations(b.p, b.workspace, cnt)
     torch.cuda.synchronize()
     lt, _, _ = oracle.candidates(w)
@@ -389,3 +398,7 @@ def test_relaxation_count(T, oracle):
     assert skipped.any() and not skipped[:, [0, -1]].all()
     assert int(cnt[0].item()) == want
     assert int(cnt[1].item()) == int(n.sum())  # the table holds the feasible candidates
+    # cells formed: every row but the first model's where only the answer is computed
+    answer_only = np.zeros_like(short)
+    answer_only[:, 0] = short[:, 0]
+    assert int(cnt[2].item()) == int(((Ti + 1)[:, None] * ~answer_only).sum())

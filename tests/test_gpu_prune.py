@@ -124,17 +124,12 @@ def test_pruned_multi_pass_entry_points(T, oracle):
     same([got[k] for k in keys], [want[k] for k in keys], keys)
 
 
-@pytest.mark.parametrize("idx,k", [(1, 4096), (3, 300)])
-def test_pruned_full_size(T, oracle, idx, k):
-    """Full batch in the launch configuration the benchmark times; the checker
-    covers a sample of instances, the dense GPU path (itself checked against the
-    checker elsewhere) is not consulted."""
-    w = wl.workload(idx)
+@pytest.mark.parametrize("idx", [1, 2, 3])
+def test_pruned_full_size(T, full_checker, idx):
+    """Full batches in the launch configuration the benchmark times: every instance
+    against the checker (the dense GPU path is not consulted)."""
+    w, want = full_checker(idx)
     print(f"[case] pruned full workload {idx} N={w.n_inst}", flush=True)
     b = T.DeviceBatch(w, prune=1)
     b.solve()
-    got = b.results()
-    rng = np.random.default_rng(idx)
-    pick = np.sort(rng.choice(w.n_inst, size=min(k, w.n_inst), replace=False))
-    want = oracle.solve(w.take(pick), threads=16)
-    same([g[pick] for g in got], want)
+    same(b.results(), want)

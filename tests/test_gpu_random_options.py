@@ -32,6 +32,7 @@ def as_joint(w):
 def test_random_options(T, oracle, seed):
     rng = np.random.default_rng(seed)
     seen = set()
+    refused = 0
     for rep in range(80):
         variant = int(rng.integers(0, 2))
         w = wl.medium_random(rng, variant)
@@ -44,6 +45,20 @@ def test_random_options(T, oracle, seed):
         mode = int(rng.integers(0, 4 if variant == wl.VERTICAL else 3))
         print(f"[case] seed {seed} rep {rep} variant {variant} queue {qm} form {form} "
               f"prune {prune} mode {mode} N {w.n_inst} S {w.n_stage} K {w.n_cand}", flush=True)
+        if w.n_stage * w.r_max * w.c_max > 32767:
+            # totals beyond sixteen bits: the library must refuse, and launch nothing
+            import torch
+            p = T.problem_of(w, prune)
+            assert T.check_problem(p) == T.ERR_RANGE and T.workspace_bytes(p) == 0
+            dummy = torch.full((4096,), 77, dtype=torch.int32, device="cuda:0")
+            ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+            with pytest.raises(T.ThemisError) as e:
+                T.themis_solve_joint(p, dummy, dummy, dummy, dummy, dummy, dummy, dummy, ws)
+            assert e.value.rc == T.ERR_RANGE
+            torch.cuda.synchronize()
+            assert (dummy.cpu().numpy() == 77).all()
+            refused += 1
+            continue
         seen.add((mode, prune))
         if mode == 0:
             b = T.DeviceBatch(w, prune=prune)
@@ -75,3 +90,4 @@ def test_random_options(T, oracle, seed):
         for x, (g, e) in enumerate(zip(got, want)):
             assert np.array_equal(g, e), f"output {x} differs in rep {rep}"
     assert len(seen) >= 12
+    print(f"[case] seed {seed}: {refused} problems refused", flush=True)

@@ -66,26 +66,49 @@ def test_step_rows_tiny_random(T, oracle):
     assert (kinds > 0).all(), kinds
 
 
+def _drops_per_row(w, lt, cost, i):
+    """Budgets at which each row f[s][.] of instance i drops, s = S-1 .. 0, from the
+    checker's candidate tables by the recurrence as defined (test helper)."""
+    T, inf = int(w.slo_us[i] // w.tick_us), 1 << 30
+    f, out = np.zeros(T + 1, np.int64), []
+    for s in range(w.n_stage - 1, -1, -1):
+        g = np.full(T + 1, inf, np.int64)
+        for k in np.nonzero(lt[i, s] >= 0)[0]:
+            l, c = int(lt[i, s, k]), int(cost[i, s, k])
+            if l <= T:
+                np.minimum(g[l:], f[:T + 1 - l] + c, out=g[l:])
+        f = np.minimum(g, inf)
+        out.append(int((np.diff(np.concatenate([[inf], f])) < 0).sum()))
+    return out
+
+
 def test_step_rows_long_lists_and_many_candidates(T, oracle):
-    """Costs that make rows drop at very many budgets (more than the list in LDS
-    holds, so the threads scatter from their own stretches), and a model with
+    """Costs that make rows drop at very many budgets (more than the 1024 the list
+    in LDS holds, so the threads scatter from their own stretches), and models with
     more candidates than are staged at a time."""
     rng = np.random.default_rng(8)
-    n, S = 6, 3
-    # many cores and replicas with a fine tick: cost steps nearly every tick
+    n, S, c_max, r_max, tick, slo_max = 6, 7, 64, 72, 20, 327_000
+    # many cores and replicas with a fine tick: the total steps down nearly every tick
     coef = np.stack([rng.integers(lo, hi + 1, size=(n, S)) for lo, hi in
-                     ((200_000, 900_000), (1000, 5000), (0, 3), (64, 64), (200, 2000))],
+                     ((200_000, 900_000), (1000, 5000), (0, 3), (c_max, c_max), (200, 2000))],
                     axis=-1).astype(np.int32)
-    w = wl.Workload("steps-long", wl.JOINT, n, S, 64, [1, 2, 3, 4, 6, 8, 12, 16, 24, 32], 150, 20,
-                    300_000, False, coef, rng.integers(50, 4000, n).astype(np.int32),
-                    rng.integers(200_000, 300_001, n).astype(np.int32))
+    w = wl.Workload("steps-long", wl.JOINT, n, S, c_max, [1, 2, 3, 4, 6, 8, 12, 16, 24, 32],
+                    r_max, tick, slo_max, False, coef, rng.integers(50, 4000, n).astype(np.int32),
+                    rng.integers(slo_max * 3 // 4, slo_max + 1, n).astype(np.int32))
+    lt, cost, _ = oracle.candidates(w)
+    assert ((lt >= 0).sum(axis=2) > 512).any()            # more entries than one staging round
+    drops = np.array([_drops_per_row(w, lt, cost, i) for i in range(n)])   # [n][S], s = S-1 .. 0
+    # a list that outgrows its area before a model that scatters (row s >= 2), and
+    # one before the model of which only the answer is formed (row s = 1)
+    assert (drops[:, :S - 2] > 1024).any() and (drops[:, S - 2] > 1024).any(), drops
+    assert (drops[:, 0] <= 1024).all()                     # (the first rows keep their lists)
+    want = oracle.solve(w, threads=6)
+    assert (want[0] == 0).any()
     for prune in (2, 3):
         print(f"[case] step rows long lists prune={prune} K={w.n_cand}", flush=True)
         b = T.DeviceBatch(w, prune=prune)
         b.solve()
-        want = oracle.solve(w, threads=6)
         same(b.results(), want)
-        assert (want[0] == 0).any()
 
 
 def test_step_rows_other_entry_points(T, oracle):
@@ -110,16 +133,13 @@ def test_step_rows_other_entry_points(T, oracle):
          ("stable",) + NAMES)
 
 
-@pytest.mark.parametrize("idx,k", [(1, 4096), (3, 300)])
-def test_step_rows_full_size(T, oracle, idx, k):
-    """Full batch in the launch configuration the benchmark times; the checker
-    covers a sample of instances."""
-    w = wl.workload(idx)
-    print(f"[case] step rows full workload {idx} N={w.n_inst}", flush=True)
-    b = T.DeviceBatch(w, prune=2)
+@pytest.mark.parametrize("prune", [2, 3])
+@pytest.mark.parametrize("idx", [1, 3])
+def test_step_rows_full_size(T, full_checker, idx, prune):
+    """Full batches in the launch configuration the benchmark times: every instance
+    against the checker."""
+    w, want = full_checker(idx)
+    print(f"[case] step rows full workload {idx} N={w.n_inst} prune={prune}", flush=True)
+    b = T.DeviceBatch(w, prune=prune)
     b.solve()
-    got = b.results()
-    rng = np.random.default_rng(idx)
-    pick = np.sort(rng.choice(w.n_inst, size=min(k, w.n_inst), replace=False))
-    want = oracle.solve(w.take(pick), threads=16)
-    same([g[pick] for g in got], want)
+    same(b.results(), want)

@@ -280,47 +280,39 @@ def test_batch_one_cost_monotone_in_lambda(oracle):
         prev = cur
 
 
-# ---------------------------------------------------------------- paper-form DP
-def _push_style(w, i, lt, cost):
-    """Algorithm 1's loop structure (Section 4.4): models in pipeline order, budgets
-    downward, candidates c ascending then b ascending, boolean reachability dp
-    over EXACT sums plus a best[] total, relaxing forward into dp[s][i + l];
-    then the upward answer scan with strict improvement.  Written with the
-    feasibility filter read as the prose states it."""
-    S, K = w.n_stage, w.n_cand
+# ---------------------------------------------------------------- forward sparse DP
+def _prefix_states(w, i, lt, cost):
+    """Eq. 6 by prefixes: after model s, the set of reachable exact latency sums of
+    models 0..s, each with the least total cores that reaches it (a dictionary,
+    grown model by model from the candidate tables; sums beyond the budget are
+    dropped).  The answer is the least total over the final set and, among the
+    sums attaining it, the least."""
     T = int(w.slo_us[i]) // w.tick_us
-    INF = 10**9
-    dp = [[False] * (T + 1) for _ in range(S)]
-    best = [[INF] * (T + 1) for _ in range(S)]
-    for s in range(S):
-        for t in range(T, -1, -1):
-            if not ((s == 0 and t == 0) or (s != 0 and dp[s - 1][t])):
-                continue
-            for k in range(K):
-                if lt[i, s, k] < 0 or t + lt[i, s, k] > T:
-                    continue
-                tot = cost[i, s, k] + (0 if s == 0 else best[s - 1][t])
-                u = t + lt[i, s, k]
-                if not dp[s][u] or tot < best[s][u]:
-                    dp[s][u] = True
-                    best[s][u] = tot
-    least, ind = INF, -1
-    for t in range(T + 1):
-        if dp[S - 1][t] and best[S - 1][t] < least:
-            least, ind = best[S - 1][t], t
-    return (1, -1, -1) if ind < 0 else (0, least, ind)
+    states = {0: 0}
+    for s in range(w.n_stage):
+        options = [(int(l), int(c)) for l, c in zip(lt[i, s], cost[i, s]) if l >= 0]
+        grown = {}
+        for spent, total in states.items():
+            for l, c in options:
+                if spent + l <= T and total + c < grown.get(spent + l, 10**9):
+                    grown[spent + l] = total + c
+        states = grown
+    if not states:
+        return (1, -1, -1)
+    least = min(states.values())
+    return (0, least, min(t for t, c in states.items() if c == least))
 
 
-def test_push_style_transcription(oracle):
-    """The checker's pull/suffix DP against a forward push-style DP that follows
-    the printed loop order.  Cost and ticks must agree (the printed algorithm's
-    first-found tie-break may legitimately pick another configuration)."""
+def test_forward_sparse_dp_agrees(oracle):
+    """The checker's suffix recurrence over dense rows against a forward recurrence
+    over sparse sets of prefix sums: structurally unlike it (other direction,
+    other state representation), same optimum and same least latency."""
     w = wl.workload(0)
     w.slo_us = (w.slo_us // 3).astype(np.int32)
     lt, cost, _ = oracle.candidates(w)
     st, c, tk, _ = oracle.solve(w)
     for i in range(w.n_inst):
-        assert _push_style(w, i, lt, cost) == (st[i], c[i], tk[i])
+        assert _prefix_states(w, i, lt, cost) == (st[i], c[i], tk[i])
     assert set(st.tolist()) == {0, 1}
 
 
