@@ -46,7 +46,8 @@
  * Conventions common to all entry points
  *   - Pointers named d_* are DEVICE pointers owned by the caller; p is a HOST
  *     pointer.  The library allocates nothing, frees nothing and keeps no
- *     state between calls.
+ *     state between calls (themis_solve_joint_static remembers, per GPU, the
+ *     address of its built-in workspace; nothing else is kept).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Work is enqueued on it; the call returns without synchronising.
  *   - Return value: THEMIS_OK, or a negative THEMIS_ERR_* found on the host
@@ -79,6 +80,10 @@ extern "C" {
 #define THEMIS_ERR_RANGE (-4)     /* cost or tick range exceeds the limits above */
 #define THEMIS_ERR_WORKSPACE (-5) /* workspace missing, misaligned or too small */
 #define THEMIS_ERR_LAUNCH (-6)    /* the HIP runtime refused a launch           */
+#define THEMIS_ERR_TOO_LARGE (-7) /* problem needs more than the built-in scratch */
+
+/* bytes of the built-in workspace of themis_solve_joint_static, per GPU */
+#define THEMIS_STATIC_SCRATCH_BYTES (64u << 20)
 
 /* themis_problem_t.queue_model */
 #define THEMIS_QUEUE_PER_REPLICA 0
@@ -171,6 +176,27 @@ int themis_solve_joint(const themis_problem_t *p, const int32_t *d_coef,
                        int32_t *d_status, int32_t *d_cost, int32_t *d_ticks,
                        int32_t *d_cfg, void *d_workspace, size_t workspace_bytes,
                        void *stream);
+
+/*
+ * themis_solve_joint for callers that cannot allocate device memory or hand
+ * over a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same inputs, outputs and results as
+ * themis_solve_joint; the workspace is an array of
+ * THEMIS_STATIC_SCRATCH_BYTES built into the library's device code (every GPU
+ * the library runs on holds one from the first launch until the process ends).
+ * The call allocates and frees nothing.  A problem whose
+ * themis_workspace_bytes(p) exceeds THEMIS_STATIC_SCRATCH_BYTES is refused
+ * with THEMIS_ERR_TOO_LARGE and nothing is launched.  The first call on a
+ * device looks the array's address up (not an allocation; make that call
+ * outside a stream capture).  All calls on one GPU share the one array: the
+ * next call overwrites what the last one left there, and two calls that
+ * overlap in time on the same GPU (different streams, different threads) race;
+ * callers serialise them, e.g. by using one stream.
+ */
+int themis_solve_joint_static(const themis_problem_t *p, const int32_t *d_coef,
+                              const int32_t *d_lambda, const int32_t *d_slo_us,
+                              int32_t *d_status, int32_t *d_cost, int32_t *d_ticks,
+                              int32_t *d_cfg, void *stream);
 
 /*
  * Vertical-only solve (Algorithm 1): replicas are given, d_r_fixed int32

@@ -1,8 +1,17 @@
 // Host side of the C ABI declared in include/themis.h: argument checks and
-// launches.  No allocation, no synchronisation, no state.
+// launches.  No allocation, no synchronisation; the only state is the per-device
+// address of the built-in scratch array of themis_solve_joint_static.
 #include "themis_internal.h"
 
+#include <mutex>
+
 using namespace themis;
+
+// Workspace of themis_solve_joint_static: one array per GPU, held from the
+// moment the library's code is loaded on that GPU until the process ends.  In
+// host code this name is only a handle for hipGetSymbolAddress; kernels get the
+// address that call returns.
+static __device__ __align__(256) unsigned char scratch[THEMIS_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -74,6 +83,26 @@ int solve(const themis_problem_t* p, const int32_t* d_coef, const int32_t* d_lam
                 static_cast<char*>(ws), static_cast<hipStream_t>(stream), opts);
 }
 
+// Address of `scratch` on the current device, looked up once per device.
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_lock;
+void* scratch_of_device[MAX_DEVICES];
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return THEMIS_ERR_LAUNCH;
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_of_device[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return THEMIS_ERR_LAUNCH;
+        scratch_of_device[dev] = ptr;
+    }
+    *out = scratch_of_device[dev];
+    return THEMIS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -95,6 +124,24 @@ int themis_solve_joint(const themis_problem_t* p, const int32_t* d_coef,
 {
     return solve(p, d_coef, d_lambda, d_slo_us, nullptr, d_status, d_cost, d_ticks, d_cfg,
                  d_workspace, workspace_bytes, stream);
+}
+
+int themis_solve_joint_static(const themis_problem_t* p, const int32_t* d_coef,
+                              const int32_t* d_lambda, const int32_t* d_slo_us,
+                              int32_t* d_status, int32_t* d_cost, int32_t* d_ticks,
+                              int32_t* d_cfg, void* stream)
+{
+    if (!d_coef || !d_lambda || !d_slo_us || !d_status || !d_cost || !d_ticks || !d_cfg)
+        return THEMIS_ERR_NULL;
+    int rc = check(p);
+    if (rc != THEMIS_OK) return rc;
+    const Layout L = make_layout(*p);
+    if (L.total > (size_t)THEMIS_STATIC_SCRATCH_BYTES) return THEMIS_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != THEMIS_OK) return rc;
+    return pass(*p, L, d_coef, d_lambda, d_slo_us, nullptr, d_status, d_cost, d_ticks, d_cfg,
+                static_cast<char*>(ws), static_cast<hipStream_t>(stream), PassOpts());
 }
 
 int themis_solve_vertical(const themis_problem_t* p, const int32_t* d_coef,

@@ -20,10 +20,13 @@ MAX_BATCH = 16
 OK = 0
 SOLVED, INFEASIBLE, INVALID, INTERNAL = 0, 1, 2, 3
 ERR_NULL, ERR_SHAPE, ERR_BATCH, ERR_RANGE, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -3, -4, -5, -6
+ERR_TOO_LARGE = -7
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "themis_version", "themis_check_problem", "themis_workspace_bytes",
-    "themis_solve_joint", "themis_solve_vertical", "themis_solve_horizontal",
+    "themis_solve_joint", "themis_solve_joint_static", "themis_solve_vertical",
+    "themis_solve_horizontal",
     "themis_fallback_workspace_bytes", "themis_solve_vertical_fallback",
     "themis_stability_workspace_bytes", "themis_check_stability",
     "themis_memo_workspace_bytes", "themis_solve_distinct",
@@ -65,6 +68,8 @@ def lib():
         L.themis_workspace_bytes.argtypes = [P]
         L.themis_solve_joint.restype = ctypes.c_int
         L.themis_solve_joint.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.themis_solve_joint_static.restype = ctypes.c_int
+        L.themis_solve_joint_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp]
         L.themis_solve_vertical.restype = ctypes.c_int
         L.themis_solve_vertical.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.themis_solve_horizontal.restype = ctypes.c_int
@@ -164,6 +169,12 @@ def themis_solve_joint(p, coef, lam, slo_us, status, cost, ticks, cfg, workspace
     _chk("themis_solve_joint", lib().themis_solve_joint(
         ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(status), _dp(cost), _dp(ticks),
         _dp(cfg), _dp(workspace, torch.uint8), workspace.numel(), _stream(stream)))
+
+
+def themis_solve_joint_static(p, coef, lam, slo_us, status, cost, ticks, cfg, stream=None):
+    _chk("themis_solve_joint_static", lib().themis_solve_joint_static(
+        ctypes.byref(p), _dp(coef), _dp(lam), _dp(slo_us), _dp(status), _dp(cost), _dp(ticks),
+        _dp(cfg), _stream(stream)))
 
 
 def themis_solve_vertical(p, coef, lam, slo_us, r_fixed, status, cost, ticks, cfg, workspace,
