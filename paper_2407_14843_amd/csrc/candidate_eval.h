@@ -47,6 +47,19 @@ __device__ __forceinline__ double ceil_div_d(double n, double d, double rd)
     return r >= d ? q + 1.0 : q;
 }
 
+// ceil(n / d) for integers 0 <= n <= 2^42, d >= 1, with rd = recip_below(d): one
+// multiply and a ceiling.  Write n = k d + r, 0 <= r < d.  If r = 0, n * rd lies
+// in (k - 1, k] (it is below k by at most k 2^-44 < 1) and rounds to a value in
+// that range, k itself being representable: the ceiling is k.  If r >= 1,
+// n * rd >= (k + 1/d)(1 - 2^-44) = k + (1 - n 2^-44) / d >= k + 0.75 / d, which
+// is above k by far more than half a unit in the last place of k (k 2^-53 <=
+// 2^-11 / d), and at most n / d < k + 1: the product rounds into (k, k + 1] and
+// the ceiling is k + 1.
+__device__ __forceinline__ double ceil_div_small(double n, double rd)
+{
+    return __builtin_ceil(n * rd);
+}
+
 // What every candidate of a row shares.
 struct RowHdr {
     double a, k, q, o;   // profile coefficients
@@ -71,28 +84,42 @@ struct Eval {
     int32_t lt, n;
 };
 
-template <int QUEUE>
-__device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& bh, double d,
-                                               double r_max, double tick, double rtick)
+// SMALL: the row's lambda * SLO is at most 2^42, so every numerator of a
+// candidate that survives the tests is, and the divisions take the short form
+// (a candidate whose last numerator exceeds 2^42 has a quotient above the
+// budget T, since T * lambda * tick <= lambda * SLO, and still gets one: the
+// product is above T by at least 0.75 / (lambda * tick), far more than a
+// rounding).  rd = recip_below(d).
+// NMODE: where the replica count comes from: N_DERIVED (joint), N_GIVEN
+// (vertical, h.n_given), or N_EITHER (h.n_given decides at run time).
+constexpr int N_EITHER = 0, N_DERIVED = 1, N_GIVEN = 2;
+
+template <int QUEUE, bool SMALL, int NMODE>
+__device__ __forceinline__ Eval eval_candidate_rd(const RowHdr& h, const BatchHdr& bh, double d,
+                                                  double rd, double r_max, double tick,
+                                                  double rtick)
 {
-    // Straight-line: every test only clears `ok`, so the lanes of a wavefront
-    // stay together.  A candidate that fails an early test may push later
-    // intermediates past 2^53; they are then inexact but never used.
+    // Straight-line: every test only clears a bit of `ok`, so the lanes of a
+    // wavefront stay together.  A candidate that fails an early test may push
+    // later intermediates past 2^53; they are then inexact but never used.
     const double num = __builtin_fma(h.q, bh.b2, __builtin_fma(h.k, bh.b, h.a));  // < 2^41
-    const double proc = ceil_div_d(num, d, recip_below(d)) + __builtin_fma(h.d, bh.b, h.o);
+    const double proc = ceil_div_small(num, rd) + __builtin_fma(h.d, bh.b, h.o);
     // anything slower than the SLO also exceeds T ticks; cutting it here keeps
     // every later product of a surviving candidate below 2^53
-    bool ok = proc <= h.slo;
+    int ok = (int)(proc <= h.slo);
     const double lp = h.lam * proc;  // < 2^51
-    const bool derive = h.n_given <= 0.0;
+    const bool derive = NMODE == N_DERIVED || (NMODE == N_EITHER && h.n_given <= 0.0);
     // least n with lambda <= n * b / proc; at least 1 since lambda * proc >= 1
-    double n = ceil_div_d(lp, bh.M, bh.rM);
-    n = derive ? n : h.n_given;
+    double n = h.n_given;
+    if (NMODE != N_GIVEN) {
+        const double need = SMALL ? ceil_div_small(lp, bh.rM) : ceil_div_d(lp, bh.M, bh.rM);
+        n = derive ? need : n;
+    }
     // joint: no more than r_max replicas; vertical: the given ones must carry lambda
-    ok = ok && (derive ? lp <= r_max * bh.M : lp <= n * bh.M);
+    // (either way n <= r_max < 2^15 from here on)
+    ok &= (int)(lp <= (derive ? r_max : n) * bh.M);
     // batch-fill wait: per replica (each sees lambda / n) or Eq. 4's shared queue
     const double qn = QUEUE == THEMIS_QUEUE_PER_REPLICA ? bh.w * n : bh.w;  // < 2^45
-    ok = ok && qn <= (h.slo - proc) * h.lam;  // proc + queue <= SLO
     double lt;
     if (QUEUE == THEMIS_QUEUE_WORST_CASE) {
         double queue = ceil_div_d(qn, h.lam, h.rlam);
@@ -101,16 +128,28 @@ __device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& 
         const double x = __builtin_fma(n, bh.M, 1.0e6);
         const double busy = proc - (ceil_div_d(x + 1.0, h.lam, h.rlam) - 1.0);
         queue = busy > queue ? busy : queue;
-        ok = ok && proc + queue <= h.slo;
+        ok &= (int)(proc + queue <= h.slo);
         lt = ceil_div_d(proc + queue, tick, rtick);
     } else {
         // ceil((proc + ceil(qn / lambda)) / tick) = ceil((proc lambda + qn) / (lambda tick)):
-        // one division; numerator <= SLO * lambda < 2^51 for a surviving candidate
-        lt = ceil_div_d(__builtin_fma(proc, h.lam, qn), h.lt_den, h.rlt_den);
+        // one division; numerator < 2^52 for a candidate that passed the tests above.
+        // (lt <= T below also says proc + queue <= SLO, T being floor(SLO / tick).)
+        const double top = __builtin_fma(proc, h.lam, qn);
+        lt = SMALL ? ceil_div_small(top, h.rlt_den) : ceil_div_d(top, h.lt_den, h.rlt_den);
     }
-    ok = ok && lt <= h.T;
+    ok &= (int)(lt <= h.T);
     return Eval{ok ? (int32_t)lt : -1, ok ? (int32_t)n : 0};
 }
+
+template <int QUEUE>
+__device__ __forceinline__ Eval eval_candidate(const RowHdr& h, const BatchHdr& bh, double d,
+                                               double r_max, double tick, double rtick)
+{
+    return eval_candidate_rd<QUEUE, false, N_EITHER>(h, bh, d, recip_below(d), r_max, tick, rtick);
+}
+
+// Whether a row's candidates may take the short divisions (see eval_candidate_rd).
+__device__ __forceinline__ bool row_is_small(const RowHdr& h) { return h.lam * h.slo <= 0x1p42; }
 
 // The row-level and batch-level parts of the above from the raw inputs.
 __device__ __forceinline__ RowHdr make_row_hdr(const int32_t* cf, uint32_t cs, int32_t lambda,

@@ -22,6 +22,8 @@
 #include "candidate_eval.h"
 #include "themis_internal.h"
 
+#include <type_traits>
+
 namespace themis {
 namespace {
 
@@ -34,6 +36,34 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Inclusive prefix sums (MIN = false) or running minima (MIN = true) over segments
+// of `width` consecutive lanes (a power of two; q = lane within its segment), with
+// the data-parallel primitives instead of LDS permutes: shifts by 1, 2, 4, 8 inside
+// each row of 16 lanes (a lane whose source lies outside its row, or its segment,
+// takes the identity), then the last lane of a row of 16 broadcast to the next row
+// (32-lane segments: rows 1 and 3) and lane 31 to rows 2 and 3 (64).
+template <bool MIN, int CTRL, int ROWS>
+__device__ __forceinline__ uint32_t scan_step(uint32_t x, bool keep)
+{
+    uint32_t t = (uint32_t)__builtin_amdgcn_update_dpp(MIN ? -1 : 0, (int)x, CTRL, ROWS, 0xF, false);
+    if (!keep) t = MIN ? 0xFFFFFFFFu : 0u;
+    return MIN ? (t < x ? t : x) : x + t;
+}
+
+template <bool MIN>
+__device__ __forceinline__ uint32_t segmented_scan(uint32_t x, uint32_t q, uint32_t width)
+{
+    // segments shorter than a row of 16: a shift must not reach into the segment before
+    const bool narrow = width < 16u;
+    if (width > 1u) x = scan_step<MIN, 0x111, 0xF>(x, !narrow || q >= 1u);
+    if (width > 2u) x = scan_step<MIN, 0x112, 0xF>(x, !narrow || q >= 2u);
+    if (width > 4u) x = scan_step<MIN, 0x114, 0xF>(x, !narrow || q >= 4u);
+    if (width > 8u) x = scan_step<MIN, 0x118, 0xF>(x, true);
+    if (width > 16u) x = scan_step<MIN, 0x142 /* row_bcast:15 */, 0xA>(x, true);
+    if (width > 32u) x = scan_step<MIN, 0x143 /* row_bcast:31 */, 0xC>(x, true);
+    return x;
 }
 
 __device__ __forceinline__ int in_range(int32_t v, int32_t lo, int32_t hi)
@@ -114,234 +144,401 @@ __global__ void k1_reset_ctrl(int32_t* ctrl)
 
 // Candidate evaluation plus a counting sort of each row by bucket.
 //
-// One thread per (row, batch size), or `split` threads taking alternate cores; a
-// workgroup of 256 threads covers RPW = 256 / (n_batch * split) rows ((instance,
-// model) pairs).  The thread walks its cores c <= c_max: the latency model only
-// depends on min(c, p), so it is evaluated for c <= p and reused (with cost n*c)
-// beyond.  Pass 1 parks every
-// candidate's (lt, cost) in LDS and counts the bucket of the feasible ones; a
-// wavefront scan turns the counts into bucket offsets; pass 2 hands every
-// feasible entry a slot inside its bucket's range and writes it to HBM in the
-// form the min-plus stage reads.  Infeasible candidates are not written at all:
-// a row's entries are its first bcum[row][nb] slots and the rest of the row's
-// stretch of the table is never read.
-// The order inside a bucket is whatever the LDS atomics yield; nothing
+// A wavefront serves RW = 64 / LPR rows ((instance, model) pairs) at a time with
+// LPR lanes each (LPR a power of two), and walks the table in steps of all
+// resident wavefronts: the raw inputs of its next rows are loaded while it works
+// on the current ones.  Within a row, lane q = part * n_batch + j works on batch
+// size j; the `split` (a power of two) parts share that batch size's cores.  A
+// row's lanes never leave the wavefront, so the phases below are separated by
+// wavefront-level LDS fences only: after the shared table of reciprocals is set up
+// there is no workgroup barrier in the kernel.
+//
+// The latency model depends on the cores through min(c, p) only, so a row has
+// at most min(p, c_max) distinct evaluations per batch size ("singles", one per
+// core count up to the cap) and a "tail" of candidates beyond the cap that share
+// the cap's latency and replica count and differ in cost = n * c and index only.
+//
+//   A  every lane evaluates its share of the singles (strided over the parts, two
+//      at a time so that their dependent chains overlap), parks (lt, cost) in LDS
+//      and counts its latency bucket; the lane that evaluates the cap adds the
+//      whole tail to that bucket.
+//   P  (PRUNE) dominated singles are dropped, see below; the tail always is (the
+//      cap's candidate has the same latency and a smaller cost), so a pruned row
+//      is built from the singles alone.
+//   B  one segmented scan per wavefront (data-parallel primitives, no LDS) turns
+//      every row's bucket counts into bucket offsets, which serve as the slot
+//      cursors of phase C.
+//   C  every lane reserves slots: one returning LDS atomic per single and one per
+//      batch size for the whole tail (its entries differ by a constant and are
+//      dealt to the parts in turn, so a tail entry costs an add and a store), and
+//      writes the 8-byte entries into the row's image in LDS, in bucket order.
+//   D  the row's lanes copy the image to HBM, 16 bytes per lane, front to back:
+//      every store instruction writes one contiguous stretch per row.  The
+//      cursors, which now stand at the bucket ends, are the row's bcum.
+// Infeasible candidates are not written at all: a row's entries are its first
+// bcum[row][nb] slots and the rest of the row's stretch of the table is never
+// read.  The order inside a bucket is whatever the LDS atomics yield; nothing
 // downstream depends on it.
 //
-// PRUNE: between the passes, candidates that cannot be part of the answer are
+// PRUNE: between phases A and B, candidates that cannot be part of the answer are
 // turned into infeasible ones, so that the min-plus stage never sees them.  A
 // candidate is dropped when another one of the same row is at least as fast and
 // cheaper, or as cheap and faster, or equal in both with a smaller index: swapping
 // it for that other one in any assignment gives a smaller (cost, ticks, indices)
 // key, so it is in no instance's answer, and since the rows of the recurrence
 // never increase with the budget it attains no minimum that its replacement does
-// not attain as well.  Per row one wavefront fills a table min over candidates of
-// (lt, index) by cost (costs binned by 2^prune_sh when r_max * c_max exceeds the
-// table; then only strictly cheaper bins are compared, which drops fewer
-// candidates but never a needed one), takes its running minimum, and looks every
-// candidate up in it.
+// not attain as well.  The lanes of a row fill a table min over candidates of
+// (lt, index) by cost in the row's image (free until phase C), take its running
+// minimum, and look every candidate up in it.  Where the costs up to the fastest
+// candidate's exceed the table, 2^sh costs share a bin and only strictly cheaper
+// bins are compared, which drops fewer candidates but never a needed one.
 //
 // c_fixed (may be null; then c_all, 0 = free): cores given per row; the model is
-// evaluated for those cores only and every other candidate of the row is marked infeasible.
+// evaluated for those cores only and no other candidate of the row competes.
 // sparse: rows of instances that failed the input check are left untouched.
 constexpr uint32_t STAGE_NONE = 0xFFFFu;  // lt field of an infeasible candidate in LDS
 
-constexpr uint32_t PRUNE_TAB_WORDS = 2560;  // per wavefront, at most: sentinel + cost bins
 constexpr uint32_t PRUNE_KEY_SHIFT = 13;    // key = lt << 13 | index (index < 8192)
 
-template <int QUEUE, bool PRUNE>
-__global__ __launch_bounds__(256) void k1_candidates(
+// LDS words of one row: the image of its table entries (two words each), the
+// parked singles, the bucket counts / cursors, the replica count of the tail.
+struct K1Row {
+    uint32_t image, parked, counts, tail, words;  // offsets in words; total, a multiple of four
+};
+__host__ __device__ inline K1Row k1_row(uint32_t Kp, uint32_t c_max, uint32_t nbat, uint32_t nb)
+{
+    K1Row r;
+    r.image = 0;
+    r.parked = 2 * Kp;
+    r.counts = r.parked + ((c_max * nbat + 3u) & ~3u);
+    r.tail = r.counts + ((nb + 1u + 3u) & ~3u);
+    r.words = r.tail + ((2u * nbat + 3u) & ~3u);  // per batch size: replica count, first slot
+    return r;
+}
+
+typedef uint32_t k1_u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t K1_WAVES = 4;  // wavefronts per workgroup; they share nothing but a table
+
+// The raw inputs of one row, as loaded.  A wavefront loads those of its next rows
+// before it works on the current ones, so that it never waits for them.
+struct K1RowIn {
+    int32_t T, lam, slo, n_given, only;
+    int32_t cf[6];
+};
+
+template <int QUEUE, bool PRUNE, bool DERIVE>
+__global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     const int32_t* __restrict__ c_fixed, const int32_t* __restrict__ tmeta,
     StepEntry* __restrict__ step_tab, uint16_t* __restrict__ bcum, BatchList bl, uint32_t rows,
-    uint32_t S, uint32_t K, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick,
-    double rtick, int coef_shared, uint32_t RPW, uint32_t nb, uint32_t nbs,
-    uint64_t class_map, int sparse, uint32_t c_all, uint32_t cs, uint32_t prune_sh,
-    uint32_t prune_bins, uint32_t split)
+    uint32_t S, uint32_t Kp, uint32_t c_max, uint32_t r_max, uint32_t tick, double rtick,
+    int coef_shared, uint32_t lpr_log2, uint32_t split_log2, uint32_t nb, uint32_t nbs,
+    uint64_t class_map, int sparse, uint32_t c_all, uint32_t cs, uint32_t s_magic,
+    uint32_t n_groups)
 {
     extern __shared__ uint32_t smem[];
-    // per local row: hist[nb + 1], cursor[nb + 1], staging[Kp]
-    const uint32_t HB = nb + 1;
-    const uint32_t row_words = 2 * HB + Kp;
     const uint32_t nbat = (uint32_t)bl.n;
+    const K1Row R = k1_row(Kp, c_max, nbat, nb);
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wv = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t RW = 64u >> lpr_log2;  // rows per wavefront
+    // LDS: recip_below() of the core counts 1..c_max, shared; then per wavefront its rows
+    double* const rcores = reinterpret_cast<double*>(smem);
+    uint32_t* const mine = smem + 2u * ((c_max + 1u) & ~1u) + wv * (RW * R.words);
+    for (uint32_t c = threadIdx.x + 1u; c <= c_max; c += blockDim.x)
+        rcores[c - 1u] = recip_below((double)c);
+    __syncthreads();  // the only workgroup barrier: from here on the wavefronts are on their own
 
-    // `split` threads share the cores of one (row, batch size): thread `part` takes
-    // c = part + 1, part + 1 + split, ...
-    const uint32_t tpr = nbat * split;
-    const uint32_t rl = threadIdx.x / tpr, rem = threadIdx.x - rl * tpr;
-    const uint32_t part = rem / nbat, j = rem - part * nbat;
-    const uint32_t row = blockIdx.x * RPW + rl;
-    bool live = rl < RPW && row < rows;
-    uint32_t* const hist = smem + rl * row_words;
-    uint32_t* const cur = hist + HB;
-    uint32_t* const stage = cur + HB;
+    const uint32_t lpr = 1u << lpr_log2, split = 1u << split_log2;
+    const uint32_t rl = lane >> lpr_log2, q = lane & (lpr - 1u);
+    // q = part * nbat + j; lanes beyond split * nbat only help with phases B and D
+    uint32_t part = 0, j = q;
+    while (j >= nbat) j -= nbat, ++part;  // at most lpr / nbat steps
+    const bool worker = part < split;
+    uint32_t* const image = mine + rl * R.words;
+    uint32_t* const parked = image + R.parked;
+    uint32_t* const counts = image + R.counts;
+    uint32_t* const tail_n = image + R.tail;
+    const BatchHdr bh = make_batch_hdr(bl.b[j]);
 
-    const int32_t T = live ? tmeta[row / S] : -1;
-    if (sparse) {
-        if (!__syncthreads_or(T >= 0)) return;  // nothing to do for any row of this workgroup
-        live = live && T >= 0;
-    }
+    // every load is issued whatever the row (beyond the table the last row is read
+    // and dropped): a load under a test of its own would be waited for on the spot
+    auto load_rows = [&](uint32_t g) {
+        uint32_t row = g * RW + rl;
+        row = row < rows ? row : rows - 1u;
+        const uint32_t i = s_magic ? __umulhi(row, s_magic) : row / S;
+        const uint32_t s = row - i * S;
+        K1RowIn in;
+        in.T = tmeta[i];
+        in.lam = lambda[i];
+        in.slo = slo_us[i];
+        in.n_given = DERIVE ? 0 : r_fixed[row];
+        in.only = c_fixed ? c_fixed[row] : (int32_t)c_all;
+        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * cs) + s * cs;
+#pragma unroll
+        for (int x = 0; x < 5; ++x) in.cf[x] = cf[x];
+        in.cf[5] = cs == 6 ? cf[5] : 0;
+        return in;
+    };
 
-    for (uint32_t x = threadIdx.x; x < RPW * row_words; x += 256u)
-        if (x % row_words < 2 * HB) smem[x] = 0u;
-    __syncthreads();
+    const uint32_t n_wv = blockDim.x >> 6;  // K1_WAVES, or fewer where their rows would not fit
+    const uint32_t g_step = gridDim.x * n_wv;
+    uint32_t g = blockIdx.x * n_wv + wv;
+    if (g >= n_groups) return;
+    K1RowIn next = load_rows(g);
+    for (; g < n_groups; g += g_step) {
+        const K1RowIn in = next;
+        if (g + g_step < n_groups) next = load_rows(g + g_step);
 
-    if (live) {
-        const uint32_t i = row / S, s = row - i * S;
-        if (T >= 0) {
-            const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * cs) + s * cs;
-            const RowHdr h = make_row_hdr(cf, cs, lambda[i], slo_us[i], T, tick,
-                                          r_fixed ? r_fixed[(size_t)i * S + s] : 0);
-            const BatchHdr bh = make_batch_hdr(bl.b[j]);
-            const uint32_t pcap = (uint32_t)cf[3];
-            const uint32_t only = c_fixed ? (uint32_t)c_fixed[row] : c_all;
-            Eval ev{-1, 0};
-            if (only) {
-                const uint32_t d = only < pcap ? only : pcap;
-                ev = eval_candidate<QUEUE>(h, bh, (double)d, (double)r_max, (double)tick, rtick);
-            }
-            bool capped = false;  // ev already is the evaluation at the core cap
-            for (uint32_t c = part + 1; c <= c_max; c += split) {
-                if (!only && !capped) {
+        const uint32_t row = g * RW + rl;
+        bool live = row < rows;
+        const int32_t T = live ? in.T : -1;
+        if (sparse) live = live && T >= 0;
+        if (__ballot(live) == 0ull) continue;  // nothing to do for any row of this wavefront
+        const bool valid = live && T >= 0;
+
+        for (uint32_t x = q; x < R.words - R.counts; x += lpr) counts[x] = 0u;
+        wave_lds_fence();
+
+        // which cores compete: all of 1..c_max, or the given ones only
+        const uint32_t pcap = (uint32_t)in.cf[3];
+        const uint32_t only = (uint32_t)in.only;
+        const uint32_t c_lo = only ? only : 1u;
+        const uint32_t c_hi = only ? only : c_max;
+        // singles: c_lo .. last, each evaluated at min(c, p); tail: the cores beyond
+        const uint32_t reach = pcap > c_lo ? pcap : c_lo;
+        const uint32_t last = c_hi < reach ? c_hi : reach;
+        const uint32_t n_eval = valid ? last - c_lo + 1u : 0u;
+        const uint32_t tail_len = valid ? c_hi - last : 0u;
+        const uint32_t my_evals = worker ? n_eval : 0u;
+        {
+            // A: this lane's singles
+            const RowHdr h = make_row_hdr(in.cf, cs, in.lam, in.slo, T, tick, in.n_given);
+            const bool small = !valid || row_is_small(h);
+            int32_t last_lt = -1;
+            uint32_t last_n = 0;
+            // Two singles per turn: their chains of dependent double-precision
+            // operations are independent of each other, so one fills the other's waits
+            // (the second of a turn may not exist; it is then computed and dropped).
+            auto evaluate = [&](auto small_tag) {
+                auto one = [&](uint32_t c) {
                     const uint32_t d = c < pcap ? c : pcap;
-                    ev = eval_candidate<QUEUE>(h, bh, (double)d, (double)r_max, (double)tick, rtick);
-                    capped = c >= pcap;
+                    return eval_candidate_rd<QUEUE, decltype(small_tag)::value,
+                                             DERIVE ? N_DERIVED : N_GIVEN>(
+                        h, bh, (double)d, rcores[d - 1u], (double)r_max, (double)tick, rtick);
+                };
+                auto word = [](const Eval& ev, uint32_t c) {
+                    return ev.lt < 0 ? STAGE_NONE
+                                     : (uint32_t)ev.lt | (__umul24((uint32_t)ev.n, c) << 16);
+                };
+                for (uint32_t e = part; e < my_evals; e += 2u * split) {
+                    const bool both = e + split < my_evals;
+                    const uint32_t e1 = both ? e + split : e;
+                    const Eval ev0 = one(c_lo + e), ev1 = one(c_lo + e1);
+                    parked[e * nbat + j] = word(ev0, c_lo + e);
+                    if (both) parked[e1 * nbat + j] = word(ev1, c_lo + e1);
+                    if (!PRUNE && ev0.lt >= 0)
+                        atomicAdd(&counts[(uint32_t)ev0.lt >> BUCKET_SHIFT], 1u);
+                    if (!PRUNE && both && ev1.lt >= 0)
+                        atomicAdd(&counts[(uint32_t)ev1.lt >> BUCKET_SHIFT], 1u);
+                    last_lt = ev1.lt;
+                    last_n = (uint32_t)ev1.n;
                 }
-                const bool none = ev.lt < 0 || (only && c != only);
-                const uint32_t w0 = none ? STAGE_NONE
-                                         : (uint32_t)ev.lt | (((uint32_t)ev.n * c) << 16);
-                stage[(c - 1) * nbat + j] = w0;
-                if (!PRUNE && !none) atomicAdd(&hist[(uint32_t)ev.lt >> BUCKET_SHIFT], 1u);
+            };
+            // the short divisions where every row of the wavefront allows them
+            if (__ballot(!small) == 0ull)
+                evaluate(std::true_type{});
+            else
+                evaluate(std::false_type{});
+            // the lane that evaluated the cap answers for the cores beyond it
+            if (my_evals > 0u && ((n_eval - 1u) & (split - 1u)) == part) {
+                tail_n[j] = last_n;
+                if (!PRUNE && tail_len > 0u && last_lt >= 0)
+                    atomicAdd(&counts[(uint32_t)last_lt >> BUCKET_SHIFT], tail_len);
             }
-        } else {
-            for (uint32_t c = part + 1; c <= c_max; c += split) stage[(c - 1) * nbat + j] = STAGE_NONE;
         }
-    }
-    __syncthreads();
-    {
-        // exclusive prefix over the buckets, one row at a time per wavefront;
-        // the offset of bucket nb is the number of feasible entries
-        const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-        for (uint32_t r = wv; r < RPW; r += 4) {
-            const uint32_t grow = blockIdx.x * RPW + r;
-            if (grow >= rows) break;
-            if (sparse && tmeta[grow / S] < 0) continue;
-            uint32_t* const hh = smem + r * row_words;
-            if (PRUNE && tmeta[grow / S] >= 0) {
-                // tab[0] = "nothing cheaper"; tab[1 + bin] = least (lt, index) of the bin,
-                // then of all bins up to it
-                uint32_t* const tab = smem + RPW * row_words + wv * ((prune_bins + 4u) & ~3u);
-                const uint32_t* const stg = hh + 2 * HB;
-                // The fastest candidate (least lt, then least cost) beats everything
-                // that costs more than it does, so only the bins up to its own take
-                // part in the table: usually a small part of the cost range.
-                uint32_t fastest = 0xFFFFFFFFu;  // lt << 16 | cost
-                for (uint32_t kk = lane; kk < K; kk += 64u) {
-                    const uint32_t w0 = stg[kk];
-                    const uint32_t key = (w0 << 16) | (w0 >> 16);
-                    fastest = key < fastest ? key : fastest;
+        wave_lds_fence();
+
+        if (PRUNE) {
+            // P: every row's lanes prune their own row; the row's image, not yet in
+            // use, is the table: tab[0] = "nothing cheaper", tab[1 + bin] = least
+            // (lt, index) of the cost bin, then of all bins up to it.
+            uint32_t* const tab = image;
+            const uint32_t K = n_eval * nbat;  // the row's parked singles, in index order
+            // The fastest candidate (least lt, then least cost) beats everything that
+            // costs more than it does, so only the costs up to its own take part:
+            // usually a small part of the cost range.
+            uint32_t fastest = 0xFFFFFFFFu;  // lt << 16 | cost
+            for (uint32_t kk = q; kk < K; kk += lpr) {
+                const uint32_t w0 = parked[kk];
+                const uint32_t key = (w0 << 16) | (w0 >> 16);
+                fastest = key < fastest ? key : fastest;
+            }
+            fastest = __shfl(segmented_scan<true>(fastest, q, lpr), (int)(lane | (lpr - 1u)), 64);
+            // One cost per bin where the table (the image's 2 Kp words) holds them all,
+            // else 2^sh costs per bin; then only strictly cheaper bins are compared,
+            // which drops fewer candidates but never a needed one.
+            const uint32_t cost_top = fastest & 0xFFFFu;
+            uint32_t sh = 0;
+            while ((cost_top >> sh) + 2u > 2u * Kp) ++sh;
+            // no feasible candidate: lt field 0xFFFF, the table stays empty
+            const uint32_t bins = (fastest >> 16) == STAGE_NONE ? 1u : (cost_top >> sh) + 1u;
+            for (uint32_t x = q; x <= bins; x += lpr) tab[x] = 0xFFFFFFFFu;
+            wave_lds_fence();
+            for (uint32_t kk = q; kk < K; kk += lpr) {
+                const uint32_t w0 = parked[kk], lt = w0 & 0xFFFFu;
+                const uint32_t bin = (w0 >> 16) >> sh;
+                if (lt != STAGE_NONE && bin < bins)
+                    atomicMin(&tab[1u + bin], (lt << PRUNE_KEY_SHIFT) | kk);
+            }
+            wave_lds_fence();
+            {
+                // running minimum over the bins: each lane owns a stretch
+                const uint32_t per = (bins + lpr - 1u) >> lpr_log2;
+                const uint32_t lo = 1u + q * per;
+                const uint32_t hi = lo + per < bins + 1u ? lo + per : bins + 1u;
+                uint32_t m = 0xFFFFFFFFu;
+                for (uint32_t x = lo; x < hi; ++x) m = tab[x] < m ? tab[x] : m;
+                // the minimum of all earlier stretches of the row: inclusive scan, moved
+                // up a lane
+                uint32_t before = segmented_scan<true>(m, q, lpr);
+                before = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)before,
+                                                               0x138 /* wave_shr:1 */, 0xF, 0xF, false);
+                if (q == 0u) before = 0xFFFFFFFFu;
+                for (uint32_t x = lo; x < hi; ++x) {
+                    const uint32_t v0 = tab[x];
+                    before = v0 < before ? v0 : before;
+                    tab[x] = before;
                 }
-#pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) {
-                    const uint32_t o = __shfl_xor(fastest, d, 64);
-                    fastest = o < fastest ? o : fastest;
+            }
+            wave_lds_fence();
+            for (uint32_t kk = q; kk < K; kk += lpr) {
+                const uint32_t w0 = parked[kk], lt = w0 & 0xFFFFu;
+                const uint32_t bin = (w0 >> 16) >> sh;
+                bool keep = lt != STAGE_NONE && bin < bins;
+                if (keep) {
+                    // nothing strictly cheaper is as fast ...
+                    keep = (tab[bin] >> PRUNE_KEY_SHIFT) > lt;
+                    // ... and, where a bin is one cost, nothing as cheap is faster or
+                    // equally fast with a smaller index
+                    if (sh == 0u) keep = keep && tab[1u + bin] == ((lt << PRUNE_KEY_SHIFT) | kk);
                 }
-                // no feasible candidate: lt field 0xFFFF, the bins below stay empty
-                const uint32_t top_bin = (fastest & 0xFFFFu) >> prune_sh;
-                const uint32_t bins = (fastest >> 16) == STAGE_NONE ? 1u
-                                      : (top_bin + 1u < prune_bins ? top_bin + 1u : prune_bins);
-                for (uint32_t x = lane; x <= bins; x += 64u) tab[x] = 0xFFFFFFFFu;
-                wave_lds_fence();
-                for (uint32_t kk = lane; kk < K; kk += 64u) {
-                    const uint32_t w0 = stg[kk], lt = w0 & 0xFFFFu;
-                    const uint32_t bin = (w0 >> 16) >> prune_sh;
-                    if (lt != STAGE_NONE && bin < bins)
-                        atomicMin(&tab[1u + bin], (lt << PRUNE_KEY_SHIFT) | kk);
+                if (!keep) parked[kk] = STAGE_NONE;
+                if (keep) atomicAdd(&counts[lt >> BUCKET_SHIFT], 1u);
+            }
+            wave_lds_fence();
+        }
+
+        {
+            // B: exclusive prefix over each row's buckets 0..nb, all rows of the wavefront
+            // in one segmented scan: lane q of a row owns `per` consecutive buckets.  The
+            // offset of bucket nb (which no candidate falls into) is the number of entries.
+            const uint32_t per = (nb + lpr) >> lpr_log2;  // ceil((nb + 1) / lpr)
+            const uint32_t lo = q * per;
+            uint32_t sum = 0;
+            for (uint32_t x = lo; x < lo + per && x <= nb; ++x) sum += counts[x];
+            const uint32_t incl = segmented_scan<false>(sum, q, lpr);
+            uint32_t run = incl - sum;
+            for (uint32_t x = lo; x < lo + per && x <= nb; ++x) {
+                const uint32_t v = counts[x];
+                counts[x] = run;
+                run += v;
+            }
+        }
+        wave_lds_fence();
+
+        if (!PRUNE && valid && part == 0u && tail_len > 0u) {
+            // one run of slots for the cores beyond the cap of this batch size
+            const uint32_t lt = parked[(n_eval - 1u) * nbat + j] & 0xFFFFu;
+            tail_n[nbat + j] =
+                lt != STAGE_NONE ? atomicAdd(&counts[lt >> BUCKET_SHIFT], tail_len) : 0xFFFFFFFFu;
+        }
+        wave_lds_fence();
+        if (my_evals > 0u || (valid && worker && tail_len > 0u)) {
+            // the LDS geometry the min-plus stage will use for this instance;
+            // wide_shift() / narrow_shift() in one branch-free form:
+            //   shift = base + (lt & 1) * step - (((lt + add) >> 1) << 2)
+            const int cls = effective_class(T, class_map);
+            const bool narrow = cls == NARROW_CLS;
+            const uint32_t add = narrow ? 0u : 1u;
+            const uint32_t step =
+                narrow ? 4u * (NAR_COPY_DW - 1) : (uint32_t)wide_copy_bytes(cls_waves(cls));
+            const uint32_t base = narrow ? 4u * NAR_CHUNK_DW : 0u;
+            auto shift_of = [&](uint32_t lt) {
+                return base + ((lt & 1u) ? step : 0u) - (((lt + add) >> 1) << 2);
+            };
+            StepEntry* const img = reinterpret_cast<StepEntry*>(image);
+            // two singles per turn, so that their LDS round trips overlap
+            for (uint32_t e = part; e < my_evals; e += 2u * split) {
+                const uint32_t e1 = e + split;
+                const uint32_t w0 = parked[e * nbat + j];
+                const uint32_t w1 = e1 < my_evals ? parked[e1 * nbat + j] : STAGE_NONE;
+                const uint32_t lt0 = w0 & 0xFFFFu, lt1 = w1 & 0xFFFFu;
+                uint32_t slot0 = 0, slot1 = 0;
+                if (lt0 != STAGE_NONE) slot0 = atomicAdd(&counts[lt0 >> BUCKET_SHIFT], 1u);
+                if (lt1 != STAGE_NONE) slot1 = atomicAdd(&counts[lt1 >> BUCKET_SHIFT], 1u);
+                if (lt0 != STAGE_NONE) {
+                    StepEntry se;
+                    se.shift = shift_of(lt0);
+                    se.ck = (w0 >> 16) | (((c_lo + e - 1u) * nbat + j) << 16);
+                    img[slot0] = se;
                 }
-                wave_lds_fence();
-                {
-                    // running minimum over the bins: each lane owns a stretch
-                    const uint32_t per = (bins + 63u) / 64u;
-                    const uint32_t lo = 1u + lane * per;
-                    const uint32_t hi = lo + per < bins + 1u ? lo + per : bins + 1u;
-                    uint32_t m = 0xFFFFFFFFu;
-                    for (uint32_t x = lo; x < hi; ++x) m = tab[x] < m ? tab[x] : m;
-                    uint32_t before = m;  // becomes the minimum of all earlier stretches
-#pragma unroll
-                    for (int d = 1; d < 64; d <<= 1) {
-                        const uint32_t t = __shfl_up(before, d, 64);
-                        if ((int)lane >= d) before = t < before ? t : before;
+                if (lt1 != STAGE_NONE) {
+                    StepEntry se;
+                    se.shift = shift_of(lt1);
+                    se.ck = (w1 >> 16) | (((c_lo + e1 - 1u) * nbat + j) << 16);
+                    img[slot1] = se;
+                }
+            }
+            if (!PRUNE && tail_len > 0u) {
+                // The cores beyond the cap: one run of slots per batch size (reserved
+                // above), the run's entries dealt to the parts in turn, so that the
+                // lanes of a batch size write neighbouring slots at a time.
+                const uint32_t slot0 = tail_n[nbat + j];
+                if (slot0 != 0xFFFFFFFFu) {
+                    const uint32_t lt = parked[(n_eval - 1u) * nbat + j] & 0xFFFFu;
+                    const uint32_t n = tail_n[j];
+                    const uint32_t c = c_lo + n_eval + part;  // this lane's first core
+                    StepEntry se;
+                    se.shift = shift_of(lt);
+                    se.ck = __umul24(n, c) | (((c - 1u) * nbat + j) << 16);
+                    const uint32_t per_turn = (n | (nbat << 16)) << split_log2;
+                    for (uint32_t t = part; t < tail_len; t += split) {
+                        img[slot0 + t] = se;
+                        se.ck += per_turn;
                     }
-                    before = __shfl_up(before, 1, 64);
-                    if (lane == 0) before = 0xFFFFFFFFu;
-                    for (uint32_t x = lo; x < hi; ++x) {
-                        const uint32_t v0 = tab[x];
-                        before = v0 < before ? v0 : before;
-                        tab[x] = before;
-                    }
                 }
-                wave_lds_fence();
-                for (uint32_t kk = lane; kk < K; kk += 64u) {
-                    const uint32_t w0 = stg[kk], lt = w0 & 0xFFFFu;
-                    const uint32_t bin = (w0 >> 16) >> prune_sh;
-                    bool keep = lt != STAGE_NONE && bin < bins;
-                    if (keep) {
-                        // nothing strictly cheaper is as fast ...
-                        keep = (tab[bin] >> PRUNE_KEY_SHIFT) > lt;
-                        // ... and, where a bin is one cost, nothing as cheap is faster or
-                        // equally fast with a smaller index
-                        if (prune_sh == 0) keep = keep && tab[1u + bin] == ((lt << PRUNE_KEY_SHIFT) | kk);
-                    }
-                    if (!keep) hh[2 * HB + kk] = STAGE_NONE;
-                    if (keep) atomicAdd(&hh[lt >> BUCKET_SHIFT], 1u);
-                }
-                wave_lds_fence();
-            }
-            const uint32_t v = lane < nb ? hh[lane] : 0u;
-            uint32_t incl = v;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const uint32_t t = __shfl_up(incl, d, 64);
-                if ((int)lane >= d) incl += t;
-            }
-            const uint32_t excl = incl - v;
-            if (lane <= nb) {
-                hh[HB + lane] = excl;
-                bcum[(size_t)grow * nbs + lane] = (uint16_t)excl;
-            }
-            if (lane == 63 && nb == 64) {
-                hh[HB + 64] = incl;
-                bcum[(size_t)grow * nbs + 64] = (uint16_t)incl;
             }
         }
-    }
-    __syncthreads();
-    if (live) {
-        // the LDS geometry the min-plus stage will use for this instance
-        const int cls = T >= 0 ? effective_class(T, class_map) : 0;
-        // wide_shift() / narrow_shift() in one branch-free form:
-        //   shift = base + ((-lt) & cm) * step - (((lt + add) >> sh) << (sh + 1))
-        uint32_t cm, sh, add, step, base;
-        if (cls == NARROW_CLS) {
-            cm = 1, sh = 1, add = 0, step = 4u * (NAR_COPY_DW - 1), base = 4u * NAR_CHUNK_DW;
-        } else {
-            cm = 1, sh = 1, add = 1, step = (uint32_t)wide_copy_bytes(cls_waves(cls)), base = 0;
+        wave_lds_fence();
+
+        // The next rows' inputs have long arrived; taking them here, before any of
+        // this group's stores is issued, keeps the wait for them (which counts every
+        // memory operation issued before it) from waiting for stores.
+        asm volatile("" ::"v"(next.T), "v"(next.lam), "v"(next.slo), "v"(next.n_given),
+                     "v"(next.only), "v"(next.cf[0]), "v"(next.cf[1]), "v"(next.cf[2]),
+                     "v"(next.cf[3]), "v"(next.cf[4]), "v"(next.cf[5]));
+        if (live) {
+            // D: every bucket's cursor now stands at the start of the next bucket, which
+            // is what bcum holds: bcum[0] = 0, bcum[x + 1] = cursor[x]; two per store
+            uint32_t* const bc = reinterpret_cast<uint32_t*>(bcum + (size_t)row * nbs);
+            for (uint32_t y = q; 2u * y <= nb; y += lpr) {
+                const uint32_t lo = y ? counts[2u * y - 1u] : 0u;
+                const uint32_t hi = 2u * y < nb ? counts[2u * y] : 0u;  // the padding half, if any
+                bc[y] = lo | (hi << 16);
+            }
         }
-        StepEntry* const out = step_tab + (size_t)row * Kp;
-        // Only the feasible candidates are written: they fill the first
-        // bcum[row][nb] slots of the row, and nothing reads the table beyond them.
-        for (uint32_t c = part + 1; c <= c_max; c += split) {
-            const uint32_t kk = (c - 1) * nbat + j;
-            const uint32_t w0 = stage[kk];
-            const uint32_t lt = w0 & 0xFFFFu;
-            if (lt == STAGE_NONE) continue;
-            const uint32_t slot = atomicAdd(&cur[lt >> BUCKET_SHIFT], 1u);
-            StepEntry se;
-            se.shift = base + __umul24((0u - lt) & cm, step) - (((lt + add) >> sh) << (sh + 1));
-            se.ck = (w0 >> 16) | (kk << 16);
-            out[slot] = se;
+        if (valid) {
+            // the image goes to HBM front to back, two entries per lane and store
+            // (an odd count takes one slot of padding along; the stretch has room)
+            const uint32_t n_ent = counts[nb];
+            const k1_u32x4* const src = reinterpret_cast<const k1_u32x4*>(image);
+            k1_u32x4* const dst = reinterpret_cast<k1_u32x4*>(step_tab + (size_t)row * Kp);
+            for (uint32_t x = q; 2u * x < n_ent; x += lpr) dst[x] = src[x];
         }
+        wave_lds_fence();  // the next rows reuse this memory
     }
 }
 
@@ -458,56 +655,76 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     if (e != hipSuccess) return e;
 
     const bool prune = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
-    // cost bins of the pruning table: one per cost when r_max * c_max fits, else
-    // 2^prune_sh costs each; one table (sentinel + bins) per wavefront
-    uint32_t prune_sh = 0;
-    const uint32_t cost_top = (uint32_t)p.r_max * (uint32_t)p.c_max;
-    while ((cost_top >> prune_sh) + 2u > PRUNE_TAB_WORDS) ++prune_sh;
-    const uint32_t prune_bins = (cost_top >> prune_sh) + 1u;
-    const uint32_t tab_bytes = prune ? 4u * ((prune_bins + 4u) & ~3u) * (uint32_t)sizeof(uint32_t) : 0u;
-
-    // This kernel is bound by latency (dependent double-precision chains, LDS
-    // atomics, the loads at its start), so it needs wavefronts more than it needs
-    // every lane busy.  Where one thread per (row, batch size) would make a
-    // workgroup hold more than 32 KB of LDS, two threads share the cores of a
-    // (row, batch size): half the rows and LDS per workgroup, twice the workgroups
-    // per compute unit, for one extra model evaluation per thread.
-    const uint32_t row_bytes = (uint32_t)(2 * (L.nb + 1) + L.Kp) * sizeof(uint32_t);
-    // The same split serves small batches, whose workgroups would not fill the chip.
-    const uint32_t rpw1 = 256u / (uint32_t)p.n_batch;
-    const bool few = ((uint32_t)L.N * L.S + rpw1 - 1) / rpw1 < 4u * (uint32_t)plan.cus;
-    const uint32_t split =
-        p.c_max >= 8 && (rpw1 * row_bytes + tab_bytes > 32u * 1024u || few) ? 2u : 1u;
-    // rows per workgroup: as many as 256 threads cover, within 76 KB of LDS
-    uint32_t RPW = 256u / ((uint32_t)p.n_batch * split);
-    if (RPW == 0) RPW = 1;
-    while (RPW > 1 && RPW * row_bytes + tab_bytes > 76u * 1024u) --RPW;
+    // Lanes per row: enough to give every batch size a lane, and beyond that a
+    // share of the cores per lane of about eight (the kernel is bound by vector
+    // issue and by the latency of its dependent double-precision chains, so it
+    // wants many short threads), within what the LDS of a compute unit lets stay
+    // resident: a row's image, parked evaluations and counters are all in LDS.
+    const K1Row R = k1_row((uint32_t)L.Kp, (uint32_t)p.c_max, (uint32_t)p.n_batch, (uint32_t)L.nb);
+    const uint32_t row_bytes = R.words * (uint32_t)sizeof(uint32_t);
+    uint32_t lpr_log2 = 0;
+    while ((1u << lpr_log2) < (uint32_t)p.n_batch) ++lpr_log2;
+    while (lpr_log2 < 6 && ((uint32_t)p.c_max * (uint32_t)p.n_batch >> lpr_log2) > 16u) ++lpr_log2;
+    // rows per wavefront must fit the LDS a workgroup may have
+    while (lpr_log2 < 6 && (64u >> lpr_log2) * row_bytes > 60u * 1024u) ++lpr_log2;
+    // row / S as the high half of row * ceil(2^32 / S): exact while rows * S < 2^32
+    const uint64_t n_rows = (uint64_t)L.N * L.S;
+    const uint32_t s_magic =
+        L.S > 1 && n_rows * (uint64_t)L.S < (1ull << 32) ? (uint32_t)(((1ull << 32) + L.S - 1) / L.S) : 0u;
+    // LDS of a workgroup: a reciprocal per core count, then per wavefront its rows
+    // and its pruning table
+    const uint32_t rc_bytes = 8u * (((uint32_t)p.c_max + 1u) & ~1u);
+    uint32_t waves = K1_WAVES;  // fewer when four wavefronts' rows do not fit
+    auto lds_for = [&](uint32_t w) {
+        return (size_t)rc_bytes + (size_t)w * ((64u >> lpr_log2) * row_bytes);
+    };
+    while (waves > 1 && lds_for(waves) > 150u * 1024u) --waves;
+    if (lds_for(waves) > 150u * 1024u) return hipErrorInvalidValue;
+    uint32_t split_log2 = 0;
+    while (((uint32_t)p.n_batch << (split_log2 + 1)) <= (1u << lpr_log2)) ++split_log2;
+    const uint32_t RW = 64u >> lpr_log2;
     const uint32_t rows = (uint32_t)L.N * L.S;
-    const size_t lds = (size_t)RPW * row_bytes + tab_bytes;
+    const uint32_t n_groups = (rows + RW - 1) / RW;
+    const size_t lds = lds_for(waves);
+    // persistent workgroups: as many as stay resident, each wavefront walking the
+    // row groups with a stride
+    uint32_t per_cu = (uint32_t)(160u * 1024u / lds);
+    if (per_cu > 32u / waves) per_cu = 32u / waves;
+    if (per_cu < 1u) per_cu = 1u;
+    uint32_t grid = (uint32_t)plan.cus * per_cu;
+    if (grid > (n_groups + waves - 1) / waves) grid = (n_groups + waves - 1) / waves;
     auto launch = [&](auto kernel) -> hipError_t {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(kernel, dim3((rows + RPW - 1) / RPW), dim3(256), lds, st, d_coef,
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(64 * waves), lds, st, d_coef,
                            d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, (const int32_t*)tmeta,
                            (StepEntry*)(ws + L.step_off), (uint16_t*)(ws + L.bcum_off), bl, rows,
-                           (uint32_t)L.S, (uint32_t)L.K, (uint32_t)L.Kp, (uint32_t)p.c_max,
+                           (uint32_t)L.S, (uint32_t)L.Kp, (uint32_t)p.c_max,
                            (uint32_t)p.r_max, (uint32_t)p.tick_us,
-                           (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, RPW,
-                           (uint32_t)L.nb, (uint32_t)L.nbs, plan.class_map,
-                           opts.sparse, (uint32_t)opts.c_all, cs, prune_sh, prune_bins, split);
+                           (1.0 / (double)p.tick_us) * (1.0 - 0x1p-45), p.coef_shared, lpr_log2,
+                           split_log2, (uint32_t)L.nb, (uint32_t)L.nbs, plan.class_map,
+                           opts.sparse, (uint32_t)opts.c_all, cs, s_magic, n_groups);
         return hipGetLastError();
     };
-    switch (p.queue_model * 2 + (prune ? 1 : 0)) {
-    case THEMIS_QUEUE_SHARED * 2: return launch(&k1_candidates<THEMIS_QUEUE_SHARED, false>);
-    case THEMIS_QUEUE_SHARED * 2 + 1: return launch(&k1_candidates<THEMIS_QUEUE_SHARED, true>);
-    case THEMIS_QUEUE_WORST_CASE * 2:
-        return launch(&k1_candidates<THEMIS_QUEUE_WORST_CASE, false>);
-    case THEMIS_QUEUE_WORST_CASE * 2 + 1:
-        return launch(&k1_candidates<THEMIS_QUEUE_WORST_CASE, true>);
-    case THEMIS_QUEUE_PER_REPLICA * 2 + 1:
-        return launch(&k1_candidates<THEMIS_QUEUE_PER_REPLICA, true>);
-    default: return launch(&k1_candidates<THEMIS_QUEUE_PER_REPLICA, false>);
+    const bool derive = d_r_fixed == nullptr;
+    switch (p.queue_model * 4 + (prune ? 2 : 0) + (derive ? 1 : 0)) {
+#define K1_CASE(Q, P, D) \
+    case Q * 4 + (P ? 2 : 0) + (D ? 1 : 0): return launch(&k1_candidates<Q, P, D>)
+        K1_CASE(THEMIS_QUEUE_PER_REPLICA, false, false);
+        K1_CASE(THEMIS_QUEUE_PER_REPLICA, false, true);
+        K1_CASE(THEMIS_QUEUE_PER_REPLICA, true, false);
+        K1_CASE(THEMIS_QUEUE_PER_REPLICA, true, true);
+        K1_CASE(THEMIS_QUEUE_SHARED, false, false);
+        K1_CASE(THEMIS_QUEUE_SHARED, false, true);
+        K1_CASE(THEMIS_QUEUE_SHARED, true, false);
+        K1_CASE(THEMIS_QUEUE_SHARED, true, true);
+        K1_CASE(THEMIS_QUEUE_WORST_CASE, false, false);
+        K1_CASE(THEMIS_QUEUE_WORST_CASE, false, true);
+        K1_CASE(THEMIS_QUEUE_WORST_CASE, true, false);
+        K1_CASE(THEMIS_QUEUE_WORST_CASE, true, true);
+#undef K1_CASE
+    default: return hipErrorInvalidValue;
     }
 }
 
