@@ -77,7 +77,7 @@ __device__ __forceinline__ int in_range(int32_t v, int32_t lo, int32_t hi)
 // lanes of a wavefront that fall into the same class share one LDS atomic, and
 // a workgroup reserves its stretch of every class list with one global atomic
 // per class: returning atomics on one address cost tens of nanoseconds each.
-constexpr uint32_t VALIDATE_THREADS = 1024;
+constexpr uint32_t VALIDATE_THREADS = 256;
 
 __global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
@@ -205,14 +205,19 @@ constexpr uint32_t PRUNE_KEY_SHIFT = 13;    // key = lt << 13 | index (index < 8
 struct K1Row {
     uint32_t image, parked, counts, tail, words;  // offsets in words; total, a multiple of four
 };
-__host__ __device__ inline K1Row k1_row(uint32_t Kp, uint32_t c_max, uint32_t nbat, uint32_t nb)
+__host__ __device__ inline K1Row k1_row(uint32_t Kp, uint32_t c_max, uint32_t nbat, uint32_t nb,
+                                        bool in_registers)
 {
     K1Row r;
     r.image = 0;
-    r.parked = 2 * Kp;
-    r.counts = r.parked + ((c_max * nbat + 3u) & ~3u);
+    r.parked = 2 * Kp;  // no room where the lanes keep their singles in registers
+    r.counts = r.parked + (in_registers ? 0u : (c_max * nbat + 3u) & ~3u);
     r.tail = r.counts + ((nb + 1u + 3u) & ~3u);
-    r.words = r.tail + ((2u * nbat + 3u) & ~3u);  // per batch size: replica count, first slot
+    // per batch size: replica count and latency at the cap, first slot of the tail
+    r.words = r.tail + ((3u * nbat + 3u) & ~3u);
+    // an odd number of 16-byte units, so that the rows of a wavefront start on
+    // different LDS banks (a multiple of 64 words would put them all on the same ones)
+    if ((r.words & 4u) == 0u) r.words += 4u;
     return r;
 }
 
@@ -227,8 +232,12 @@ struct K1RowIn {
     int32_t cf[6];
 };
 
-template <int QUEUE, bool PRUNE, bool DERIVE>
-__global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
+// ME > 0: a lane has at most ME singles and keeps them in registers from phase A to
+// phase C (the loops over them are unrolled), so the rows need no room for parked
+// singles and more wavefronts fit a compute unit; ME = 0: they are parked in LDS
+// (any number; the pruning pass needs them there).
+template <int QUEUE, bool PRUNE, bool DERIVE, int ME>
+__global__ __launch_bounds__(64 * K1_WAVES) __attribute__((amdgpu_waves_per_eu(4, 8))) void k1_candidates(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
     const int32_t* __restrict__ c_fixed, const int32_t* __restrict__ tmeta,
@@ -240,7 +249,8 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
 {
     extern __shared__ uint32_t smem[];
     const uint32_t nbat = (uint32_t)bl.n;
-    const K1Row R = k1_row(Kp, c_max, nbat, nb);
+    static_assert(!(PRUNE && ME > 0) && ME % 2 == 0, "pruning works on parked singles");
+    const K1Row R = k1_row(Kp, c_max, nbat, nb, ME > 0);
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wv = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const uint32_t RW = 64u >> lpr_log2;  // rows per wavefront
@@ -313,6 +323,7 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
         const uint32_t n_eval = valid ? last - c_lo + 1u : 0u;
         const uint32_t tail_len = valid ? c_hi - last : 0u;
         const uint32_t my_evals = worker ? n_eval : 0u;
+        uint32_t single[ME > 0 ? ME : 2];  // this lane's singles (ME > 0), as parked
         {
             // A: this lane's singles
             const RowHdr h = make_row_hdr(in.cf, cs, in.lam, in.slo, T, tick, in.n_given);
@@ -333,18 +344,33 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
                     return ev.lt < 0 ? STAGE_NONE
                                      : (uint32_t)ev.lt | (__umul24((uint32_t)ev.n, c) << 16);
                 };
-                for (uint32_t e = part; e < my_evals; e += 2u * split) {
+                auto turn = [&](uint32_t e, uint32_t& w0, uint32_t& w1) {
                     const bool both = e + split < my_evals;
                     const uint32_t e1 = both ? e + split : e;
                     const Eval ev0 = one(c_lo + e), ev1 = one(c_lo + e1);
-                    parked[e * nbat + j] = word(ev0, c_lo + e);
-                    if (both) parked[e1 * nbat + j] = word(ev1, c_lo + e1);
+                    w0 = word(ev0, c_lo + e);
+                    w1 = both ? word(ev1, c_lo + e1) : STAGE_NONE;
                     if (!PRUNE && ev0.lt >= 0)
                         atomicAdd(&counts[(uint32_t)ev0.lt >> BUCKET_SHIFT], 1u);
                     if (!PRUNE && both && ev1.lt >= 0)
                         atomicAdd(&counts[(uint32_t)ev1.lt >> BUCKET_SHIFT], 1u);
                     last_lt = ev1.lt;
                     last_n = (uint32_t)ev1.n;
+                };
+                if constexpr (ME > 0) {
+#pragma unroll
+                    for (int u = 0; u < ME; u += 2) {
+                        const uint32_t e = part + (uint32_t)u * split;
+                        single[u] = single[u + 1] = STAGE_NONE;
+                        if (e < my_evals) turn(e, single[u], single[u + 1]);
+                    }
+                } else {
+                    for (uint32_t e = part; e < my_evals; e += 2u * split) {
+                        uint32_t w0, w1;
+                        turn(e, w0, w1);
+                        parked[e * nbat + j] = w0;
+                        if (e + split < my_evals) parked[(e + split) * nbat + j] = w1;
+                    }
                 }
             };
             // the short divisions where every row of the wavefront allows them
@@ -355,6 +381,7 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
             // the lane that evaluated the cap answers for the cores beyond it
             if (my_evals > 0u && ((n_eval - 1u) & (split - 1u)) == part) {
                 tail_n[j] = last_n;
+                tail_n[2u * nbat + j] = last_lt < 0 ? STAGE_NONE : (uint32_t)last_lt;
                 if (!PRUNE && tail_len > 0u && last_lt >= 0)
                     atomicAdd(&counts[(uint32_t)last_lt >> BUCKET_SHIFT], tail_len);
             }
@@ -451,7 +478,7 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
 
         if (!PRUNE && valid && part == 0u && tail_len > 0u) {
             // one run of slots for the cores beyond the cap of this batch size
-            const uint32_t lt = parked[(n_eval - 1u) * nbat + j] & 0xFFFFu;
+            const uint32_t lt = tail_n[2u * nbat + j];
             tail_n[nbat + j] =
                 lt != STAGE_NONE ? atomicAdd(&counts[lt >> BUCKET_SHIFT], tail_len) : 0xFFFFFFFFu;
         }
@@ -471,10 +498,8 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
             };
             StepEntry* const img = reinterpret_cast<StepEntry*>(image);
             // two singles per turn, so that their LDS round trips overlap
-            for (uint32_t e = part; e < my_evals; e += 2u * split) {
+            auto place = [&](uint32_t e, uint32_t w0, uint32_t w1) {
                 const uint32_t e1 = e + split;
-                const uint32_t w0 = parked[e * nbat + j];
-                const uint32_t w1 = e1 < my_evals ? parked[e1 * nbat + j] : STAGE_NONE;
                 const uint32_t lt0 = w0 & 0xFFFFu, lt1 = w1 & 0xFFFFu;
                 uint32_t slot0 = 0, slot1 = 0;
                 if (lt0 != STAGE_NONE) slot0 = atomicAdd(&counts[lt0 >> BUCKET_SHIFT], 1u);
@@ -491,6 +516,17 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
                     se.ck = (w1 >> 16) | (((c_lo + e1 - 1u) * nbat + j) << 16);
                     img[slot1] = se;
                 }
+            };
+            if constexpr (ME > 0) {
+#pragma unroll
+                for (int u = 0; u < ME; u += 2) {
+                    const uint32_t e = part + (uint32_t)u * split;
+                    if (e < my_evals) place(e, single[u], single[u + 1]);
+                }
+            } else {
+                for (uint32_t e = part; e < my_evals; e += 2u * split)
+                    place(e, parked[e * nbat + j],
+                          e + split < my_evals ? parked[(e + split) * nbat + j] : STAGE_NONE);
             }
             if (!PRUNE && tail_len > 0u) {
                 // The cores beyond the cap: one run of slots per batch size (reserved
@@ -498,7 +534,7 @@ __global__ __launch_bounds__(64 * K1_WAVES) void k1_candidates(
                 // lanes of a batch size write neighbouring slots at a time.
                 const uint32_t slot0 = tail_n[nbat + j];
                 if (slot0 != 0xFFFFFFFFu) {
-                    const uint32_t lt = parked[(n_eval - 1u) * nbat + j] & 0xFFFFu;
+                    const uint32_t lt = tail_n[2u * nbat + j];
                     const uint32_t n = tail_n[j];
                     const uint32_t c = c_lo + n_eval + part;  // this lane's first core
                     StepEntry se;
@@ -655,24 +691,35 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     if (e != hipSuccess) return e;
 
     const bool prune = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
-    // Lanes per row: enough to give every batch size a lane, and beyond that a
-    // share of the cores per lane of about eight (the kernel is bound by vector
-    // issue and by the latency of its dependent double-precision chains, so it
-    // wants many short threads), within what the LDS of a compute unit lets stay
-    // resident: a row's image, parked evaluations and counters are all in LDS.
-    const K1Row R = k1_row((uint32_t)L.Kp, (uint32_t)p.c_max, (uint32_t)p.n_batch, (uint32_t)L.nb);
-    const uint32_t row_bytes = R.words * (uint32_t)sizeof(uint32_t);
+    // Lanes per row: enough to give every batch size a lane, and beyond that enough
+    // to leave a lane about sixteen candidates.  Fewer lanes per row spread the
+    // per-row work (inputs, header, scan, set-up of the phases) over more
+    // candidates; more lanes shorten the threads and let more wavefronts stay
+    // resident, since a row's image and counters live in LDS (measured: sixteen per
+    // lane is the best trade on the shapes of the numbered workloads).
     uint32_t lpr_log2 = 0;
     while ((1u << lpr_log2) < (uint32_t)p.n_batch) ++lpr_log2;
     while (lpr_log2 < 6 && ((uint32_t)p.c_max * (uint32_t)p.n_batch >> lpr_log2) > 16u) ++lpr_log2;
-    // rows per wavefront must fit the LDS a workgroup may have
-    while (lpr_log2 < 6 && (64u >> lpr_log2) * row_bytes > 60u * 1024u) ++lpr_log2;
+    // rows per wavefront must fit the LDS a workgroup may have (sized for the layout
+    // that parks the singles in LDS)
+    const uint32_t parked_row_bytes =
+        k1_row((uint32_t)L.Kp, (uint32_t)p.c_max, (uint32_t)p.n_batch, (uint32_t)L.nb, false).words *
+        (uint32_t)sizeof(uint32_t);
+    while (lpr_log2 < 6 && (64u >> lpr_log2) * parked_row_bytes > 60u * 1024u) ++lpr_log2;
+    uint32_t split_log2 = 0;
+    while (((uint32_t)p.n_batch << (split_log2 + 1)) <= (1u << lpr_log2)) ++split_log2;
+    // Where a lane then has at most sixteen singles (and nothing is pruned) they
+    // stay in registers and the rows need no room for them.
+    const uint32_t lane_singles = ((uint32_t)p.c_max + (1u << split_log2) - 1u) >> split_log2;
+    const int me = prune || lane_singles > 16u ? 0 : lane_singles > 8u ? 16 : 8;
+    const K1Row R = k1_row((uint32_t)L.Kp, (uint32_t)p.c_max, (uint32_t)p.n_batch, (uint32_t)L.nb,
+                           me > 0);
+    const uint32_t row_bytes = R.words * (uint32_t)sizeof(uint32_t);
     // row / S as the high half of row * ceil(2^32 / S): exact while rows * S < 2^32
     const uint64_t n_rows = (uint64_t)L.N * L.S;
     const uint32_t s_magic =
         L.S > 1 && n_rows * (uint64_t)L.S < (1ull << 32) ? (uint32_t)(((1ull << 32) + L.S - 1) / L.S) : 0u;
     // LDS of a workgroup: a reciprocal per core count, then per wavefront its rows
-    // and its pruning table
     const uint32_t rc_bytes = 8u * (((uint32_t)p.c_max + 1u) & ~1u);
     uint32_t waves = K1_WAVES;  // fewer when four wavefronts' rows do not fit
     auto lds_for = [&](uint32_t w) {
@@ -680,8 +727,6 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     };
     while (waves > 1 && lds_for(waves) > 150u * 1024u) --waves;
     if (lds_for(waves) > 150u * 1024u) return hipErrorInvalidValue;
-    uint32_t split_log2 = 0;
-    while (((uint32_t)p.n_batch << (split_log2 + 1)) <= (1u << lpr_log2)) ++split_log2;
     const uint32_t RW = 64u >> lpr_log2;
     const uint32_t rows = (uint32_t)L.N * L.S;
     const uint32_t n_groups = (rows + RW - 1) / RW;
@@ -708,22 +753,24 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
         return hipGetLastError();
     };
     const bool derive = d_r_fixed == nullptr;
-    switch (p.queue_model * 4 + (prune ? 2 : 0) + (derive ? 1 : 0)) {
-#define K1_CASE(Q, P, D) \
-    case Q * 4 + (P ? 2 : 0) + (D ? 1 : 0): return launch(&k1_candidates<Q, P, D>)
-        K1_CASE(THEMIS_QUEUE_PER_REPLICA, false, false);
-        K1_CASE(THEMIS_QUEUE_PER_REPLICA, false, true);
-        K1_CASE(THEMIS_QUEUE_PER_REPLICA, true, false);
-        K1_CASE(THEMIS_QUEUE_PER_REPLICA, true, true);
-        K1_CASE(THEMIS_QUEUE_SHARED, false, false);
-        K1_CASE(THEMIS_QUEUE_SHARED, false, true);
-        K1_CASE(THEMIS_QUEUE_SHARED, true, false);
-        K1_CASE(THEMIS_QUEUE_SHARED, true, true);
-        K1_CASE(THEMIS_QUEUE_WORST_CASE, false, false);
-        K1_CASE(THEMIS_QUEUE_WORST_CASE, false, true);
-        K1_CASE(THEMIS_QUEUE_WORST_CASE, true, false);
-        K1_CASE(THEMIS_QUEUE_WORST_CASE, true, true);
-#undef K1_CASE
+    auto by_singles = [&](auto q_tag, auto d_tag) -> hipError_t {
+        constexpr int Q = decltype(q_tag)::value;
+        constexpr bool D = decltype(d_tag)::value;
+        if (prune) return launch(&k1_candidates<Q, true, D, 0>);
+        if (me == 8) return launch(&k1_candidates<Q, false, D, 8>);
+        if (me == 16) return launch(&k1_candidates<Q, false, D, 16>);
+        return launch(&k1_candidates<Q, false, D, 0>);
+    };
+    auto by_replicas = [&](auto q_tag) -> hipError_t {
+        return derive ? by_singles(q_tag, std::true_type{}) : by_singles(q_tag, std::false_type{});
+    };
+    switch (p.queue_model) {
+    case THEMIS_QUEUE_PER_REPLICA:
+        return by_replicas(std::integral_constant<int, THEMIS_QUEUE_PER_REPLICA>{});
+    case THEMIS_QUEUE_SHARED:
+        return by_replicas(std::integral_constant<int, THEMIS_QUEUE_SHARED>{});
+    case THEMIS_QUEUE_WORST_CASE:
+        return by_replicas(std::integral_constant<int, THEMIS_QUEUE_WORST_CASE>{});
     default: return hipErrorInvalidValue;
     }
 }
