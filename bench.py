@@ -38,7 +38,10 @@ VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-o
 # profiles/*_hbm_bytes.txt): workload -> (bytes, the `bytes_per_launch` of the run
 # the counters were taken on, fingerprint of the kernel sources at that time).
 # `roofline.traffic` is null unless both still match this run.
-K2_HBM_TRAFFIC = {}
+K2_HBM_TRAFFIC = {
+    "w1-joint-4096x5": (125121003, 5247396664, "d5c36bb574f72033"),
+    "w3-joint-65536x8": (11614247286, 1422380424686, "d5c36bb574f72033"),
+}
 KERNEL_SOURCES = ("k1_candidates.hip", "candidate_eval.h", "k2_minplus.hip", "instance_queue.h",
                   "themis_internal.h")
 
