@@ -42,6 +42,11 @@ K2_HBM_TRAFFIC = {
     "w1-joint-4096x5": (125121003, 5247396664, "d5c36bb574f72033"),
     "w3-joint-65536x8": (11614247286, 1422380424686, "d5c36bb574f72033"),
 }
+# the same for stage 1 (input check + candidate kernel): workload -> (bytes, fingerprint)
+K1_HBM_TRAFFIC = {
+    "w1-joint-4096x5": (20049232, "d5c36bb574f72033"),
+    "w3-joint-65536x8": (1057142768, "d5c36bb574f72033"),
+}
 KERNEL_SOURCES = ("k1_candidates.hip", "candidate_eval.h", "k2_minplus.hip", "instance_queue.h",
                   "themis_internal.h")
 
@@ -178,6 +183,7 @@ def run_workload(themis, wl, idx, steps, warmup, n_inst=None, prune=0, copy_leg=
     # stage 1: 8 bytes written per candidate that reaches the table (the feasible
     # ones, less the pruned), + 20 bytes of coefficients read per model
     k1_bytes = entries * 8 + w.n_inst * w.n_stage * 20 * len(passes)
+    out["candidates_bytes"] = k1_bytes
     out["table_entries"] = entries
     out["candidates_evaluated"] = w.n_inst * w.n_stage * w.n_cand * len(passes)
     out["candidates_GBs"] = k1_bytes / (k_ms[0] * 1e-3) / 1e9 if k_ms[0] > 0 else None
@@ -508,7 +514,10 @@ def main():
             "achieved": m["candidates_GBs"],
             "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": None if m["candidates_GBs"] is None else m["candidates_GBs"] / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": (K1_HBM_TRAFFIC[m["workload"]][0]
+                        if m["workload"] in K1_HBM_TRAFFIC and not a.prune
+                        and K1_HBM_TRAFFIC[m["workload"]][1] == kernel_fingerprint() else None),
+            "bytes_per_launch": m["candidates_bytes"],
         },
     }
     errors = {}
