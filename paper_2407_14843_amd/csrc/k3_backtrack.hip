@@ -10,14 +10,17 @@
 // among those with
 //     cost[s][k] + f[s+1][t - lt[s][k]] == f[s][t],
 // which yields the lexicographically smallest optimal assignment, model 0 most
-// significant.  One wavefront per instance: the 64 lanes test 64 table entries
-// at a time (the table is ordered by latency bucket, not by k) and a butterfly
-// reduction picks the smallest k.
+// significant.  LANES lanes per instance (a wavefront, or a half or a quarter of
+// one where the rows have few entries: the walk is a chain of dependent memory
+// latencies, so what matters then is how many instances are in flight): they
+// test LANES table entries at a time (the table is ordered by latency bucket,
+// not by k) and a butterfly reduction picks the smallest k.
 #include "themis_internal.h"
 
 namespace themis {
 namespace {
 
+template <int LANES>
 __global__ __launch_bounds__(256) void k3_backtrack(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum, const int32_t* __restrict__ tmeta,
     const uint16_t* __restrict__ frow, const int32_t* __restrict__ ans,
@@ -26,8 +29,10 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     BatchList bl, int N, int S, int Kp, int nbs, int row_stride, uint64_t class_map,
     int sparse)
 {
-    const int lane = threadIdx.x & 63;
-    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    static_assert(LANES == 16 || LANES == 32 || LANES == 64, "a power-of-two part of a wavefront");
+    const int lane = threadIdx.x & (LANES - 1);
+    const int seg_shift = (int)(threadIdx.x & 63) & ~(LANES - 1);  // first lane of this instance's lanes
+    const int i = (int)((blockIdx.x * 256u + threadIdx.x) / LANES);
     if (i >= N) return;
 
     int32_t* my_cfg = cfg + (size_t)i * S * 3;
@@ -42,7 +47,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     uint32_t best = F_INF;
     if (T >= 0) best = given_t >= 0 ? (uint32_t)ans_cost : (uint32_t)row0[T];
     if (T < 0 || best >= F_INF) {
-        for (int x = lane; x < S * 3; x += 64) my_cfg[x] = 0;
+        for (int x = lane; x < S * 3; x += LANES) my_cfg[x] = 0;
         if (lane == 0) {
             status[i] = T < 0 ? THEMIS_INVALID : THEMIS_INFEASIBLE;
             cost_out[i] = -1;
@@ -53,22 +58,25 @@ __global__ __launch_bounds__(256) void k3_backtrack(
 
     int t_star = given_t;
     if (given_t < 0) {
-        // first t with f[0][t] == best: 64-ary search on a non-increasing row.
+        // first t with f[0][t] == best: LANES-ary search on a non-increasing row.
         // invariant: f[0][hi] == best, and f[0][t] > best for every t < lo.
         int lo = 0, hi = T;
         while (lo < hi) {
-            const int span = hi - lo;  // probes lo + span*lane/64 all lie below hi
-            const int probe = lo + (int)(((long long)span * lane) >> 6);
+            const int span = hi - lo;  // probes lo + span*lane/LANES all lie below hi
+            const int probe = lo + (int)(((long long)span * lane) / LANES);
             const bool hit = row0[probe] == best;
-            const unsigned long long m = __ballot(hit);
+            // the votes of this instance's lanes (other instances of the wavefront may
+            // have left the loop; their bits are zero and are cut off anyway)
+            unsigned long long m = __ballot(hit) >> seg_shift;
+            if (LANES < 64) m &= (1ull << (LANES & 63)) - 1ull;
             if (m == 0ull) {
                 // even the last probe is above best: the answer lies beyond it
-                lo = lo + (int)(((long long)span * 63) >> 6) + 1;
+                lo = lo + (int)(((long long)span * (LANES - 1)) / LANES) + 1;
             } else {
                 const int first = __builtin_ctzll(m);
-                const int new_hi = lo + (int)(((long long)span * first) >> 6);
+                const int new_hi = lo + (int)(((long long)span * first) / LANES);
                 const int new_lo =
-                    first == 0 ? lo : lo + (int)(((long long)span * (first - 1)) >> 6) + 1;
+                    first == 0 ? lo : lo + (int)(((long long)span * (first - 1)) / LANES) + 1;
                 hi = new_hi;
                 lo = new_lo;
             }
@@ -88,25 +96,25 @@ __global__ __launch_bounds__(256) void k3_backtrack(
         // smallest index k among the entries that attain the target; lt and cost
         // ride along in the low bits of the key
         unsigned long long key = ~0ull;
-        // Four groups of 64 entries at a time, in two rounds of independent loads
+        // Four groups of LANES entries at a time, in two rounds of independent loads
         // (the entries, then the cells of the next row they point at): the walk is
         // a chain of dependent memory latencies, so loads issued together cost one.
         constexpr int GROUPS = 4;
-        for (int e0 = 0; e0 < n; e0 += 64 * GROUPS) {
+        for (int e0 = 0; e0 < n; e0 += LANES * GROUPS) {
             // Every load is issued whatever the lane's entry is (beyond the row's
             // entries slot 0 is read, beyond the budget left cell 0, and dropped): a
             // load under a test of its own is waited for before the next is issued.
             StepEntry se[GROUPS];
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
-                const int e = e0 + 64 * g + lane;
+                const int e = e0 + LANES * g + lane;
                 se[g] = sp[e < n ? e : 0];  // every entry below n is feasible
             }
             int lt[GROUPS];
             uint32_t rest[GROUPS];
 #pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
-                const int e = e0 + 64 * g + lane;
+                const int e = e0 + LANES * g + lane;
                 lt[g] = e < n ? (int)lt_of_entry(se[g].shift, T, class_map) : t + 1;
                 rest[g] = 0u;
                 if (s + 1 < S) rest[g] = next[lt[g] <= t ? t - lt[g] : 0];
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
             }
         }
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
+        for (int d = LANES / 2; d >= 1; d >>= 1) {
             const unsigned long long other = __shfl_xor(key, d, 64);
             key = other < key ? other : key;
         }
@@ -166,12 +174,22 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
     bl.n = p.n_batch;
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
     const MinplusPlan plan = make_plan(L);
-    hipLaunchKernelGGL(k3_backtrack, dim3((L.N + 3) / 4), dim3(256), 0, st,
-                       (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
-                       (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
-                       (const int32_t*)(ws + L.ans_off), d_status, d_cost, d_ticks, d_cfg, bl, L.N, L.S, L.Kp, L.nbs, L.row_stride,
-                       plan.class_map, opts.sparse);
-    return hipGetLastError();
+    // Lanes per instance: a wavefront where a row can have hundreds of entries; a
+    // half or a quarter where it cannot, or where dominated candidates were
+    // dropped (a few dozen entries are left at most: the singles of stage 1)
+    const bool pruned = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
+    const int lanes = pruned || L.Kp <= 64 ? 16 : L.Kp <= 128 ? 32 : 64;
+    auto launch = [&](auto kernel, int per_block) {
+        hipLaunchKernelGGL(kernel, dim3((L.N + per_block - 1) / per_block), dim3(256), 0, st,
+                           (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
+                           (const int32_t*)(ws + L.tmeta_off), (const uint16_t*)(ws + L.frow_off),
+                           (const int32_t*)(ws + L.ans_off), d_status, d_cost, d_ticks, d_cfg, bl,
+                           L.N, L.S, L.Kp, L.nbs, L.row_stride, plan.class_map, opts.sparse);
+        return hipGetLastError();
+    };
+    if (lanes == 16) return launch(&k3_backtrack<16>, 16);
+    if (lanes == 32) return launch(&k3_backtrack<32>, 8);
+    return launch(&k3_backtrack<64>, 4);
 }
 
 }  // namespace themis
