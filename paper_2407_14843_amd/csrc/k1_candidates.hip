@@ -79,6 +79,36 @@ __device__ __forceinline__ int in_range(int32_t v, int32_t lo, int32_t hi)
 // per class: returning atomics on one address cost tens of nanoseconds each.
 constexpr uint32_t VALIDATE_THREADS = 256;
 
+// The check of instance i; returns its work class, or -1 when it is refused.
+__device__ __forceinline__ int validate_instance(
+    uint32_t i, const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
+    const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
+    const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta, int32_t* __restrict__ ans,
+    uint32_t S, int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared,
+    uint32_t cs)
+{
+    int32_t lam = lambda[i], slo = slo_us[i];
+    const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * cs);  // cs words per model
+    // no short-circuiting: the loads of all models are independent
+    int ok = in_range(lam, 1, THEMIS_VALUE_MAX) & in_range(slo, 0, slo_max);
+    for (uint32_t z = 0; z < S; ++z) {
+        const int32_t* cz = cf + z * cs;
+        const int32_t a = cz[0], k = cz[1], q = cz[2], pc = cz[3], o = cz[4];
+        if (cs == 6) ok &= in_range(cz[5], 0, THEMIS_VALUE_MAX);
+        ok &= in_range(a, 0, THEMIS_VALUE_MAX) & in_range(k, 0, THEMIS_VALUE_MAX) &
+              in_range(q, 0, THEMIS_VALUE_MAX) & (int)(pc >= 1) & in_range(o, 1, THEMIS_VALUE_MAX);
+        if (r_fixed) ok &= in_range(r_fixed[(size_t)i * S + z], 1, r_max);
+        if (c_fixed) ok &= in_range(c_fixed[(size_t)i * S + z], 1, c_max);
+    }
+    int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
+    tmeta[i] = T;
+    ans[2 * i] = 0;
+    ans[2 * i + 1] = -1;  // until stage 2 says otherwise, stage 3 reads row 0
+    // listed under its own class even when a launch of a higher class will
+    // serve it: that launch walks the lists from the longest rows down
+    return ok ? class_of_budget(T) : -1;
+}
+
 __global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
     const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
     const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
@@ -93,28 +123,9 @@ __global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
 
     uint32_t i = blockIdx.x * VALIDATE_THREADS + threadIdx.x;
     int cls = -1;
-    if (i < N) {
-        int32_t lam = lambda[i], slo = slo_us[i];
-        const int32_t* cf = coef + (coef_shared ? 0 : (size_t)i * S * cs);  // cs words per model
-        // no short-circuiting: the loads of all models are independent
-        int ok = in_range(lam, 1, THEMIS_VALUE_MAX) & in_range(slo, 0, slo_max);
-        for (uint32_t z = 0; z < S; ++z) {
-            const int32_t* cz = cf + z * cs;
-            const int32_t a = cz[0], k = cz[1], q = cz[2], pc = cz[3], o = cz[4];
-            if (cs == 6) ok &= in_range(cz[5], 0, THEMIS_VALUE_MAX);
-            ok &= in_range(a, 0, THEMIS_VALUE_MAX) & in_range(k, 0, THEMIS_VALUE_MAX) &
-                  in_range(q, 0, THEMIS_VALUE_MAX) & (int)(pc >= 1) & in_range(o, 1, THEMIS_VALUE_MAX);
-            if (r_fixed) ok &= in_range(r_fixed[(size_t)i * S + z], 1, r_max);
-            if (c_fixed) ok &= in_range(c_fixed[(size_t)i * S + z], 1, c_max);
-        }
-        int32_t T = ok ? (int32_t)((uint32_t)slo / tick) : -1;
-        tmeta[i] = T;
-        ans[2 * i] = 0;
-        ans[2 * i + 1] = -1;  // until stage 2 says otherwise, stage 3 reads row 0
-        // listed under its own class even when a launch of a higher class will
-        // serve it: that launch walks the lists from the longest rows down
-        if (ok) cls = class_of_budget(T);
-    }
+    if (i < N)
+        cls = validate_instance(i, coef, lambda, slo_us, r_fixed, c_fixed, tmeta, ans, S, r_max,
+                                c_max, tick, slo_max, coef_shared, cs);
     // place inside the workgroup's stretch: wavefront offset + rank among the lanes
     const unsigned lane = threadIdx.x & 63u;
     int within = 0;
@@ -140,6 +151,34 @@ __global__ __launch_bounds__(VALIDATE_THREADS) void k1_validate(
 __global__ void k1_reset_ctrl(int32_t* ctrl)
 {
     if (threadIdx.x < 2 * N_CLS) ctrl[threadIdx.x] = 0;
+}
+
+// The same check for a small batch, by one workgroup that owns the class lists:
+// slots come from LDS counters, and the workgroup writes the class sizes and
+// zeroes the queue cursors itself, so that no launch has to clear them first.
+constexpr uint32_t VALIDATE_SINGLE_THREADS = 1024;
+constexpr uint32_t VALIDATE_SINGLE_MAX = VALIDATE_SINGLE_THREADS;  // beyond one pass, one compute unit is the slower way
+
+__global__ __launch_bounds__(VALIDATE_SINGLE_THREADS) void k1_validate_single(
+    const int32_t* __restrict__ coef, const int32_t* __restrict__ lambda,
+    const int32_t* __restrict__ slo_us, const int32_t* __restrict__ r_fixed,
+    const int32_t* __restrict__ c_fixed, int32_t* __restrict__ tmeta, int32_t* __restrict__ ans,
+    int32_t* __restrict__ order, int32_t* __restrict__ ctrl, uint32_t N, uint32_t S,
+    int32_t r_max, int32_t c_max, uint32_t tick, int32_t slo_max, int coef_shared, uint32_t cs)
+{
+    __shared__ int32_t listed[N_CLS];
+    if (threadIdx.x < N_CLS) listed[threadIdx.x] = 0;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < N; i += VALIDATE_SINGLE_THREADS) {
+        const int cls = validate_instance(i, coef, lambda, slo_us, r_fixed, c_fixed, tmeta, ans, S,
+                                          r_max, c_max, tick, slo_max, coef_shared, cs);
+        if (cls >= 0) order[(size_t)cls * N + atomicAdd(&listed[cls], 1)] = (int32_t)i;
+    }
+    __syncthreads();
+    if (threadIdx.x < N_CLS) {
+        ctrl[threadIdx.x] = listed[threadIdx.x];
+        ctrl[N_CLS + threadIdx.x] = 0;
+    }
 }
 
 // Candidate evaluation plus a counting sort of each row by bucket.
@@ -680,13 +719,20 @@ hipError_t launch_candidates(const themis_problem_t& p, const Layout& L,
     int32_t* tmeta = (int32_t*)(ws + L.tmeta_off);
     int32_t* ctrl = (int32_t*)(ws + L.ctrl_off);
     const MinplusPlan plan = make_plan(L);
-    hipLaunchKernelGGL(k1_reset_ctrl, dim3(1), dim3(64), 0, st, ctrl);
-    hipLaunchKernelGGL(k1_validate, dim3((L.N + VALIDATE_THREADS - 1) / VALIDATE_THREADS),
-                       dim3(VALIDATE_THREADS), 0, st, d_coef,
-                       d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, tmeta,
-                       (int32_t*)(ws + L.ans_off),
-                       (int32_t*)(ws + L.order_off), ctrl, (uint32_t)L.N, (uint32_t)L.S, p.r_max,
-                       p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, cs);
+    if ((uint32_t)L.N <= VALIDATE_SINGLE_MAX) {
+        hipLaunchKernelGGL(k1_validate_single, dim3(1), dim3(VALIDATE_SINGLE_THREADS), 0, st,
+                           d_coef, d_lambda, d_slo_us, d_r_fixed, opts.c_fixed, tmeta,
+                           (int32_t*)(ws + L.ans_off), (int32_t*)(ws + L.order_off), ctrl,
+                           (uint32_t)L.N, (uint32_t)L.S, p.r_max, p.c_max, (uint32_t)p.tick_us,
+                           p.slo_max_us, p.coef_shared, cs);
+    } else {
+        hipLaunchKernelGGL(k1_reset_ctrl, dim3(1), dim3(64), 0, st, ctrl);
+        hipLaunchKernelGGL(k1_validate, dim3((L.N + VALIDATE_THREADS - 1) / VALIDATE_THREADS),
+                           dim3(VALIDATE_THREADS), 0, st, d_coef, d_lambda, d_slo_us, d_r_fixed,
+                           opts.c_fixed, tmeta, (int32_t*)(ws + L.ans_off),
+                           (int32_t*)(ws + L.order_off), ctrl, (uint32_t)L.N, (uint32_t)L.S,
+                           p.r_max, p.c_max, (uint32_t)p.tick_us, p.slo_max_us, p.coef_shared, cs);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 

@@ -270,16 +270,25 @@ __device__ __forceinline__ void sweep_live(uint32_t (&acc)[AD], const char* ldsb
         sweep<D, 3>(acc, ldsb, ent, ke, byte_pos, park);
 }
 
-// Clamp a finished position and store it to the HBM row (cells <= T only).
+// Whether every cell of position pos is a cell of the row (only the top position
+// of a row can be cut short by T).  Uniform over the wavefront.
+__device__ __forceinline__ bool whole_position(int pos, int T) { return (pos + 1) * POSC - 1 <= T; }
+
+// Store a finished position to the HBM row (cells <= T only).
 __device__ __forceinline__ void store_position(const uint32_t (&acc)[AD], uint16_t* out, int pos,
                                                int lane, int T)
 {
     using G = Geo;
+    uint32_t* const at = reinterpret_cast<uint32_t*>(out) + pos * (64 * G::NE) + lane;
+    if (whole_position(pos, T)) {
 #pragma unroll
-    for (int q = 0; q < G::NE; ++q) {
-        const int cell = (G::ELT / 2) * (pos * (64 * G::NE) + q * 64 + lane);
-        if (cell <= T) *reinterpret_cast<uint32_t*>(out + cell) = acc[q];
+        for (int q = 0; q < G::NE; ++q) at[q * 64] = acc[q];
+        return;
     }
+    const int room = T - (G::ELT / 2) * (pos * (64 * G::NE) + lane);  // cells up to T from the lane's first
+#pragma unroll
+    for (int q = 0; q < G::NE; ++q)
+        if ((G::ELT / 2) * q * 64 <= room) at[q * 64] = acc[q];
 }
 
 // F_INF + cost back to F_INF
@@ -304,17 +313,19 @@ __device__ __forceinline__ void finish_position(uint32_t (&acc)[AD], uint16_t* o
 // stores through ordinary pointers they came out as flat stores, each one waited
 // for before the next.  Hence the instructions themselves.  The compiler does
 // not count them; publish_wait() before the barrier that ends the publishing.
+// (OFF: a constant byte offset that rides in the instruction)
+template <int OFF = 0>
 __device__ __forceinline__ void lds_store_b32(uint32_t at, uint32_t v)
 {
-    asm volatile("ds_write_b32 %0, %1" : : "v"(at), "v"(v) : "memory");
+    asm volatile("ds_write_b32 %0, %1 offset:%2" : : "v"(at), "v"(v), "n"(OFF) : "memory");
 }
-// the low half of v at `at`, the high half at `at` + gap (a multiple of two)
-template <int GAP>
+// the low half of v at `at` + OFF, the high half GAP (a multiple of two) above it
+template <int GAP, int OFF = 0>
 __device__ __forceinline__ void lds_store_halves(uint32_t at, uint32_t v)
 {
-    asm volatile("ds_write_b16 %0, %1\n\tds_write_b16_d16_hi %0, %1 offset:%2"
+    asm volatile("ds_write_b16 %0, %1 offset:%2\n\tds_write_b16_d16_hi %0, %1 offset:%3"
                  :
-                 : "v"(at), "v"(v), "n"(GAP)
+                 : "v"(at), "v"(v), "n"(OFF), "n"(OFF + GAP)
                  : "memory");
 }
 __device__ __forceinline__ void publish_wait()
@@ -322,10 +333,13 @@ __device__ __forceinline__ void publish_wait()
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
-__device__ __forceinline__ void publish_pair(uint32_t at, int CSB, uint32_t v)
+// `at`: the element's address in copy 0, less OFF; `at1`: the same in copy 1,
+// two bytes lower
+template <int OFF = 0>
+__device__ __forceinline__ void publish_pair(uint32_t at, uint32_t at1, uint32_t v)
 {
-    lds_store_b32(at, v);                                  // copy 0: c0 c1
-    lds_store_halves<2>(at + (uint32_t)CSB - 2u, v);       // copy 1: c0 | c1 from two bytes below
+    lds_store_b32<OFF>(at, v);         // copy 0: c0 c1
+    lds_store_halves<2, OFF>(at1, v);  // copy 1: c0 | c1 from two bytes below
 }
 
 // Write a finished position from the registers of the wavefront that computed
@@ -334,12 +348,23 @@ __device__ __forceinline__ void publish_position(const uint32_t (&acc)[AD], char
                                                  int pos, int lane, int T)
 {
     using G = Geo;
-#pragma unroll
-    for (int q = 0; q < G::NE; ++q) {
-        const int el = pos * (64 * G::NE) + q * 64 + lane;
-        if ((G::ELT / 2) * el <= T)
-            publish_pair(lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el), CSB, acc[q]);
+    static_assert(G::NE == 4, "unrolled by hand for the offsets");
+    const int el = pos * (64 * G::NE) + lane;
+    const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el);
+    const uint32_t at1 = at + (uint32_t)CSB - 2u;
+    constexpr int STEP = 64 * G::ELT;  // bytes from one lane element to the next
+    if (whole_position(pos, T)) {
+        publish_pair<0 * STEP>(at, at1, acc[0]);
+        publish_pair<1 * STEP>(at, at1, acc[1]);
+        publish_pair<2 * STEP>(at, at1, acc[2]);
+        publish_pair<3 * STEP>(at, at1, acc[3]);
+        return;
     }
+    const int room = T - (G::ELT / 2) * el;  // cells up to T from the lane's first
+    if (0 * 64 * (G::ELT / 2) <= room) publish_pair<0 * STEP>(at, at1, acc[0]);
+    if (1 * 64 * (G::ELT / 2) <= room) publish_pair<1 * STEP>(at, at1, acc[1]);
+    if (2 * 64 * (G::ELT / 2) <= room) publish_pair<2 * STEP>(at, at1, acc[2]);
+    if (3 * 64 * (G::ELT / 2) <= room) publish_pair<3 * STEP>(at, at1, acc[3]);
 }
 
 // Entries of one row held in registers on their way from HBM to the LDS
@@ -476,7 +501,10 @@ __device__ __attribute__((noinline)) void first_model_by_scan(
             const uint32_t lo = v[j] < before ? v[j] : before;
             const uint32_t hi = v[j + 1] < before ? v[j + 1] : before;
             const uint32_t d = lo | (hi << 16);
-            publish_pair(lds_address(ldsb) + (uint32_t)(PADB + 2 * cell), CSB, d);
+            {
+                const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + 2 * cell);
+                publish_pair(at, at + (uint32_t)CSB - 2u, d);
+            }
             *reinterpret_cast<uint32_t*>(out + cell) = d;
         }
     }
@@ -766,7 +794,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             __syncthreads();  // every wavefront is done with the old row; the new one is stored
             for (int el = tid; el * (G::ELT / 2) <= T; el += (int)blockDim.x) {
                 const uint32_t at = lds_address(ldsb) + (uint32_t)(PADB + G::ELT * el);
-                publish_pair(at, CSB, *reinterpret_cast<const uint32_t*>(out + 2 * el));
+                publish_pair(at, at + (uint32_t)CSB - 2u, *reinterpret_cast<const uint32_t*>(out + 2 * el));
             }
             // hand the next model its entries and its position counter
             commit_row(pf, grow_next, cbuf);

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void k3_backtrack(
     BatchList bl, int N, int S, int Kp, int nbs, int row_stride, uint64_t class_map,
     int sparse)
 {
-    static_assert(LANES == 16 || LANES == 32 || LANES == 64, "a power-of-two part of a wavefront");
+    static_assert(LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "a power-of-two part of a wavefront");
     const int lane = threadIdx.x & (LANES - 1);
     const int seg_shift = (int)(threadIdx.x & 63) & ~(LANES - 1);  // first lane of this instance's lanes
     const int i = (int)((blockIdx.x * 256u + threadIdx.x) / LANES);
@@ -178,7 +178,7 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
     // half or a quarter where it cannot, or where dominated candidates were
     // dropped (a few dozen entries are left at most: the singles of stage 1)
     const bool pruned = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
-    const int lanes = pruned || L.Kp <= 64 ? 16 : L.Kp <= 128 ? 32 : 64;
+    const int lanes = pruned ? 8 : L.Kp <= 64 ? 16 : L.Kp <= 128 ? 32 : 64;
     auto launch = [&](auto kernel, int per_block) {
         hipLaunchKernelGGL(kernel, dim3((L.N + per_block - 1) / per_block), dim3(256), 0, st,
                            (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
@@ -187,6 +187,7 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
                            L.N, L.S, L.Kp, L.nbs, L.row_stride, plan.class_map, opts.sparse);
         return hipGetLastError();
     };
+    if (lanes == 8) return launch(&k3_backtrack<8>, 32);
     if (lanes == 16) return launch(&k3_backtrack<16>, 16);
     if (lanes == 32) return launch(&k3_backtrack<32>, 8);
     return launch(&k3_backtrack<64>, 4);
