@@ -599,28 +599,22 @@ __device__ __attribute__((noinline)) void answer_from_row_one(int CSB,
 // every wavefront is done with the old row, the workgroup reads the new one
 // back (it is still in L2) and spreads it over the LDS copies.  (Keeping a
 // second set of copies to publish into directly costs more in occupancy than
-// the round trip through L2 does.)
+// the round trip through L2 does.)  Pruned rows have a kernel of their own,
+// k2_minplus_pruned below.
 //
-// FIXED (used when dominated candidates were pruned, so that a position is a
-// handful of entries and the round trip dominates): every wavefront owns the
-// w-th position from the top and, where the row has more positions than the
-// workgroup has wavefronts, one of the rest, dealt so that the wavefront with
-// the cheapest first position gets the dearest second one; it keeps both
-// results in registers and writes them into the LDS copies itself after the
-// barrier; the HBM row is written for stage 3 only.  It needs more registers
-// than the dealt-out form (a few are spilled to keep eight wavefronts per SIMD),
-// and measured on dense rows it is slower than that form on four of five
-// workloads, hence the two forms.
+// Compiled for eight wavefronts per SIMD (64 VGPRs): the LDS footprints of the
+// work classes are sized for 32 resident wavefronts per compute unit, which a
+// few registers more would silently cut to 28.
 //
-// Both forms are compiled for eight wavefronts per SIMD (64 VGPRs): the LDS
-// footprints of the work classes are sized for 32 resident wavefronts per
-// compute unit, which a few registers more would silently cut to 28.
-template <bool FIXED>
+// `shortcuts`: whether the first and the last model may take their shortcuts
+// (off when this kernel serves a pruned problem that the kernel for pruned rows
+// cannot take: the count of relaxations assumes every model of a pruned problem
+// is swept).
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_minplus_wide(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
     int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int32_t* __restrict__ ans, int N,
-    int S, int Kp, int nbs, int row_stride, int cls, int low_cls, int cand_buf)
+    int S, int Kp, int nbs, int row_stride, int cls, int low_cls, int cand_buf, int shortcuts)
 {
     using G = Geo;
     constexpr int DEPTH = 1;
@@ -649,11 +643,10 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
         // Whether the first and the last model are worth their shortcuts (below)
         // depends on how much sweeping they replace: entries times positions per
-        // wavefront.  With a handful of entries (one-core solves; pruned rows, whose
-        // form of the kernel leaves the shortcuts out altogether) the plain sweeps
+        // wavefront.  With a handful of entries (one-core solves) the plain sweeps
         // are cheaper than the scan and the searches.
         const int n_first = bcum_at(as_constant(bcum + ((size_t)i * S + (S - 1)) * nbs), npos);
-        const bool scan_first = !FIXED && worth_shortcut(n_first, npos, (int)blockDim.x >> 6);
+        const bool scan_first = shortcuts && worth_shortcut(n_first, npos, (int)blockDim.x >> 6);
         if (!scan_first) {
             // rows before the first model: cells t < 0 are F_INF, cells t >= 0 are 0
             for (int x = tid; x < (PADB + npos * POSC * 2) / 4; x += (int)blockDim.x) {
@@ -685,7 +678,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             uint16_t* const out = frow + row * row_stride;
             const int n_all = bcum_at(bc, npos);  // entries that reach the top position: all feasible ones
 
-            if (!FIXED && s == 0 && S > 1 && worth_shortcut(n_all, npos, (int)blockDim.x >> 6)) {
+            if (shortcuts && s == 0 && S > 1 && worth_shortcut(n_all, npos, (int)blockDim.x >> 6)) {
                 answer_from_row_one(CSB, grow, n_all, cand_buf, T, ans + 2 * i);
                 break;
             }
@@ -701,26 +694,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
             const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
             const int nw = (int)blockDim.x >> 6;
-            const int p_hi = npos - 1 - w;
-            const int p_lo = npos - 2 * nw + w;  // negative: none
-            uint32_t r_hi[AD], r_lo[AD];
-            const bool in_regs = FIXED && n_all <= cand_buf;
-            if (in_regs) {
-                if (p_hi >= 0) {
-#pragma unroll
-                    for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
-                    sweep_live<DEPTH>(r_hi, ldsb, ent, bcum_at(bc, p_hi + 1), G::lane_byte(p_hi, lane),
-                                              G::park(p_hi), G::live_elements(p_hi, T));
-                    clamp_position(r_hi);
-                }
-                if (p_lo >= 0) {
-#pragma unroll
-                    for (int u = 0; u < AD; ++u) r_lo[u] = 0xFFFFFFFFu;
-                    sweep<DEPTH>(r_lo, ldsb, ent, bcum_at(bc, p_lo + 1), G::lane_byte(p_lo, lane),
-                                  G::park(p_lo));
-                    clamp_position(r_lo);
-                }
-            } else if (n_all <= cand_buf) {
+            if (n_all <= cand_buf) {
                 // the whole row is in the staging buffer (the usual case)
                 for (;;) {
                     int p = 0;
@@ -773,22 +747,6 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                     }
                 }
             }
-            if (in_regs) {
-                // The row goes to HBM for stage 3 only, after the next model's entries
-                // have been waited for: the stores then have a whole model's sweeps to
-                // complete in, and neither barrier waits for them.
-                if (s > 0) {
-                    lds_barrier();  // every wavefront is done with the old row
-                    if (p_hi >= 0) publish_position(r_hi, ldsb, CSB, p_hi, lane, T);
-                    if (p_lo >= 0) publish_position(r_lo, ldsb, CSB, p_lo, lane, T);
-                    commit_row(pf, grow_next, cbuf);
-                }
-                if (p_hi >= 0) store_position(r_hi, out, p_hi, lane, T);
-                if (p_lo >= 0) store_position(r_lo, out, p_lo, lane, T);
-                if (s == 0) break;
-                lds_barrier();
-                continue;
-            }
             if (s == 0) break;  // nothing reads the LDS copies of the last row
 
             __syncthreads();  // every wavefront is done with the old row; the new one is stored
@@ -801,6 +759,147 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             if (tid == 0) *next_pos = npos - 1;
             publish_wait();
             __syncthreads();
+        }
+        __syncthreads();  // last row's reads are done before the LDS is re-initialised
+    }
+}
+
+// ------------------------------------------------------- kernel for pruned rows
+// With dominated candidates pruned, a row is a handful of entries, a position a
+// few sweeps, and what is fixed per model weighs more than the sweeps.  So:
+//
+//  * every wavefront owns the w-th position from the top and, where the row has
+//    more positions than the workgroup has wavefronts, one of the rest, dealt so
+//    that the wavefront with the cheapest first position gets the dearest second
+//    one; it keeps both results in registers and writes them into the LDS copies
+//    itself after the barrier.  The HBM row is written for stage 3 only, and
+//    nothing here reads it back or waits for its stores.
+//  * the entries of as many of the pipeline's models as fit the staging buffer
+//    together (usually all) are fetched at once: one memory latency per batch of
+//    models, not one per model, whose wait would also wait for the row stores
+//    issued before it (loads and stores retire through one counter).
+//  * lane m of every wavefront keeps what the wavefront needs of the m-th model
+//    in the order of the recurrence (model S-1-m): where its entries start and
+//    how many of them reach each of the wavefront's two positions; a model's
+//    sweeps take them from there with one cross-lane read each.
+//
+// For problems with Kp <= CAND_BUF (any single row fits the buffer) and at most
+// 64 models; the launcher sends the others to k2_minplus_wide.  Measured on
+// dense rows the dealt-out positions of that kernel are faster on four of five
+// workloads, hence the two kernels.
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_minplus_pruned(
+    const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
+    const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
+    int32_t* __restrict__ ctrl, uint16_t* __restrict__ frow, int N, int S, int Kp, int nbs,
+    int row_stride, int cls, int low_cls)
+{
+    using G = Geo;
+    constexpr int DEPTH = 1;
+    extern __shared__ uint32_t lds[];
+    const int CSB = wide_copy_bytes(cls_waves(cls));  // bytes per copy: pad + the longest row
+    const int SETB = COPIES * CSB;                    // bytes of all copies
+    char* const ldsb = reinterpret_cast<char*>(lds);
+    // after the copies: a dword for the instance queue, then (16 bytes on) the
+    // staging buffer for Kp (+16) candidate entries
+    volatile uint32_t* const slot = reinterpret_cast<volatile uint32_t*>(ldsb + SETB);
+    uint32_t* const cbuf = reinterpret_cast<uint32_t*>(ldsb + SETB + 16);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nw = (int)blockDim.x >> 6;
+    StepEntry none;
+    none.shift = 0u;
+    none.ck = 0u;
+
+    const int count = list_length(ctrl, cls, low_cls);
+    int idx = -1;
+    for (;;) {
+        idx = next_index(slot, ctrl + N_CLS + cls, count, idx);
+        if (idx < 0) break;
+        const int i = list_entry(ctrl, order, N, cls, low_cls, idx);
+        const int T = as_constant(tmeta)[i];
+        const int npos = (T + POSC) / POSC;  // positions that hold cells 0..T
+        const int p_hi = npos - 1 - w;       // negative: none
+        const int p_lo = npos - 2 * nw + w;  // negative: none
+
+        int n_all_l = 0, n_hi_l = 0, n_lo_l = 0;
+        if (lane < S) {
+            const uint16_t* const bc = bcum + ((size_t)i * S + (size_t)(S - 1 - lane)) * nbs;
+            n_all_l = bc[npos];  // entries that reach the top position: all feasible ones
+            n_hi_l = bc[p_hi >= 0 ? p_hi + 1 : 0];
+            n_lo_l = bc[p_lo >= 0 ? p_lo + 1 : 0];
+        }
+        // where each model's entries start when all are laid end to end, every row
+        // starting on a group of four
+        const int padded = (n_all_l + 3) & ~3;
+        int end_l = padded;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(end_l, d, 64);
+            if (lane >= d) end_l += o;
+        }
+        const int start_l = end_l - padded;
+
+        // rows before the first model: cells t < 0 are F_INF, cells t >= 0 are 0
+        for (int x = tid; x < (PADB + npos * POSC * 2) / 4; x += (int)blockDim.x) {
+#pragma unroll
+            for (int m = 0; m < COPIES; ++m) {
+                const uint32_t h0 = 2 * x < PADB / 2 - m ? F_INF : 0u;
+                const uint32_t h1 = 2 * x + 1 < PADB / 2 - m ? F_INF : 0u;
+                lds[m * (CSB / 4) + x] = h0 | (h1 << 16);
+            }
+        }
+
+        for (int m0 = 0; m0 < S;) {
+            // the models m0 .. m1-1 fit the buffer together (a single one always does)
+            const int base = __builtin_amdgcn_readlane(start_l, m0);
+            const unsigned long long fit = __ballot(lane >= m0 && lane < S && end_l - base <= Kp);
+            const int m1 = m0 + __builtin_popcountll(fit);
+            for (int m = m0 + w; m < m1; m += nw) {
+                const int n = __builtin_amdgcn_readlane(n_all_l, m);
+                const int at = __builtin_amdgcn_readlane(start_l, m) - base;
+                const StepEntry* const grow = step_tab + ((size_t)i * S + (size_t)(S - 1 - m)) * Kp;
+                for (int e = lane; e < ((n + 3) & ~3); e += 64) {
+                    StepEntry se = none;
+                    if (e < n) se = grow[e];
+                    cbuf[at + e] = staged(se);
+                }
+            }
+            // the sweep fetches entries ahead of the end of its prefix
+            if (tid < 16) cbuf[__builtin_amdgcn_readlane(end_l, m1 - 1) - base + tid] = staged(none);
+            __syncthreads();
+
+            for (int m = m0; m < m1; ++m) {
+                const int s = S - 1 - m;
+                const uint32_t* const ent = cbuf + (__builtin_amdgcn_readlane(start_l, m) - base);
+                uint16_t* const out = frow + ((size_t)i * S + s) * row_stride;
+                uint32_t r_hi[AD], r_lo[AD];
+                if (p_hi >= 0) {
+#pragma unroll
+                    for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
+                    sweep_live<DEPTH>(r_hi, ldsb, ent, __builtin_amdgcn_readlane(n_hi_l, m),
+                                      G::lane_byte(p_hi, lane), G::park(p_hi),
+                                      G::live_elements(p_hi, T));
+                    clamp_position(r_hi);
+                }
+                if (p_lo >= 0) {
+#pragma unroll
+                    for (int u = 0; u < AD; ++u) r_lo[u] = 0xFFFFFFFFu;
+                    sweep<DEPTH>(r_lo, ldsb, ent, __builtin_amdgcn_readlane(n_lo_l, m),
+                                 G::lane_byte(p_lo, lane), G::park(p_lo));
+                    clamp_position(r_lo);
+                }
+                if (s > 0) {  // nothing reads the LDS copies of the last row
+                    lds_barrier();  // every wavefront is done with the old row
+                    if (p_hi >= 0) publish_position(r_hi, ldsb, CSB, p_hi, lane, T);
+                    if (p_lo >= 0) publish_position(r_lo, ldsb, CSB, p_lo, lane, T);
+                }
+                if (p_hi >= 0) store_position(r_hi, out, p_hi, lane, T);
+                if (p_lo >= 0) store_position(r_lo, out, p_lo, lane, T);
+                if (s > 0) lds_barrier();  // the new row is in the copies
+            }
+            m0 = m1;
         }
         __syncthreads();  // last row's reads are done before the LDS is re-initialised
     }
@@ -917,24 +1016,34 @@ inline int wide_groups_per_cu(int waves, int cand_buf)
     return per_cu < 1 ? 1 : per_cu;
 }
 
-template <bool FIXED>
-hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int low, int cus)
+// One launch of a wide kernel for the classes low .. c with the geometry of class
+// c; `pruned_rows`: the kernel for pruned rows (the caller has checked its limits).
+hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, int low, int cus,
+                             bool pruned_rows)
 {
     const int nwc = CLS_WAVES[c];
     const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
     const size_t lds_bytes = wide_lds_bytes(nwc, cand_buf);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k2_minplus_wide<FIXED>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+    const void* const kernel = pruned_rows ? reinterpret_cast<const void*>(&k2_minplus_pruned)
+                                           : reinterpret_cast<const void*>(&k2_minplus_wide);
+    hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(LDS_PER_CU - 1024));
     if (e != hipSuccess) return e;
     long long grid = (long long)cus * wide_groups_per_cu(nwc, cand_buf);
     if (grid > L_.N) grid = L_.N;
-    hipLaunchKernelGGL((k2_minplus_wide<FIXED>), dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
-                       (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
-                       (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
-                       (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off),
-                       (int32_t*)(ws + L_.ans_off), L_.N, L_.S, L_.Kp, L_.nbs, L_.row_stride, c, low,
-                       cand_buf);
+    if (pruned_rows)
+        hipLaunchKernelGGL(k2_minplus_pruned, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
+                           (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
+                           (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
+                           (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off), L_.N, L_.S,
+                           L_.Kp, L_.nbs, L_.row_stride, c, low);
+    else
+        hipLaunchKernelGGL(k2_minplus_wide, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
+                           (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
+                           (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
+                           (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off),
+                           (int32_t*)(ws + L_.ans_off), L_.N, L_.S, L_.Kp, L_.nbs, L_.row_stride, c,
+                           low, cand_buf, L_.fixed_form ? 0 : 1);
     return hipGetLastError();
 }
 
@@ -951,15 +1060,22 @@ MinplusPlan make_plan(const Layout& L_)
     // rows need twelve wavefronts or more; then the rows of up to eight chunks get
     // a launch with the eight-wavefront geometry (four workgroups per compute
     // unit), where short rows leave fewer wavefronts idle.  Measured: more heads
-    // than that lose to the starts and thinning ends of the extra launches.
+    // than that lose to the starts and thinning ends of the extra launches, except
+    // on pruned rows, where a wavefront owns its positions (an idle one is not
+    // made up for by the others taking more): there the twelve- and the
+    // four-wavefront geometries get launches of their own as well.
     unsigned heads = 1u << pl.top_wide;
     constexpr int SECOND_HEAD = 5;  // CLS_WAVES[5] == 8
     static_assert(CLS_WAVES[SECOND_HEAD] == 8, "the second head is the eight-wavefront class");
+    static_assert(CLS_WAVES[7] == 12 && CLS_WAVES[3] == 4, "the further heads for pruned rows");
     {
         const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
         const long long resident =
             (long long)pl.cus * wide_groups_per_cu(CLS_WAVES[pl.top_wide], cand_buf);
-        if (CLS_WAVES[pl.top_wide] >= 12 && L_.N >= 16 * resident) heads |= 1u << SECOND_HEAD;
+        if (CLS_WAVES[pl.top_wide] >= 12 && L_.N >= 16 * resident) {
+            heads |= 1u << SECOND_HEAD;
+            if (L_.fixed_form) heads |= 1u << 7 | 1u << 3;
+        }
     }
     pl.class_map = 0;
     int head = pl.top_wide;
@@ -972,7 +1088,8 @@ MinplusPlan make_plan(const Layout& L_)
 
 hipError_t launch_minplus(const themis_problem_t& p, const Layout& L_, char* ws, hipStream_t st)
 {
-    const bool fixed = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
+    // the kernel for pruned rows stages whole rows and keeps one lane per model
+    const bool pruned_rows = L_.fixed_form != 0 && L_.Kp <= CAND_BUF && L_.S <= 64;
     const MinplusPlan pl = make_plan(L_);
     hipError_t e;
 
@@ -1001,8 +1118,7 @@ hipError_t launch_minplus(const themis_problem_t& p, const Layout& L_, char* ws,
             if (e != hipSuccess) return e;
             continue;
         }
-        e = fixed ? launch_wide_class<true>(L_, ws, st, c, low, pl.cus)
-                  : launch_wide_class<false>(L_, ws, st, c, low, pl.cus);
+        e = launch_wide_class(L_, ws, st, c, low, pl.cus, pruned_rows);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
