@@ -50,6 +50,7 @@
 // own index and then pulls further ones through an atomic cursor until the
 // lists are exhausted, longest rows first, so the launch ends on the short
 // ones.  Usually one launch serves every class; see make_plan().
+#include <type_traits>
 #include "instance_queue.h"
 #include "themis_internal.h"
 
@@ -187,10 +188,14 @@ struct Geo {
 // wavefront always has reads in flight while it works.  The scheduling barriers
 // keep the compiler from undoing that order.  Entries at or beyond ke (the
 // rest of the row, or the padding behind it) are parked on the F_INF pad, where
-// they change nothing.
+// they change nothing; with EXACT (D = 1) the last group of a prefix is instead
+// straight-line code of exactly the entries left, picked by a switch: on pruned
+// rows, where a position is a handful of entries, up to three idle ones at ten
+// instructions each are a measurable share (on dense rows the extra code costs
+// more than it saves).
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int D, int NEA = Geo::NE>
+template <int D, int NEA = Geo::NE, bool EXACT = false>
 __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, const uint32_t* ent,
                                       int ke, uint32_t byte_pos, uint32_t park)
 {
@@ -236,6 +241,18 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // (EXACT) the last REM entries of the prefix
+    auto rest = [&](int cur, auto rem) {
+        constexpr int REM = decltype(rem)::value;
+#pragma unroll
+        for (int z = 0; z < REM; ++z) {
+            const int x = z + D;
+            if (x < REM) issue(q[cur][x & 3], x % (D + 1));
+            __builtin_amdgcn_sched_barrier(0);
+            consume(q[cur][z & 3], z % (D + 1));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
 
     for (int k0 = 0; k0 < ke; k0 += 4 * NQ) {
 #pragma unroll
@@ -244,7 +261,14 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
             if (k >= ke) break;
             if (k + 4 + D <= ke)
                 group(k, r, false);
-            else
+            else if (EXACT && D == 1) {
+                switch (ke - k) {
+                case 1: rest(r, std::integral_constant<int, 1>{}); break;
+                case 2: rest(r, std::integral_constant<int, 2>{}); break;
+                case 3: rest(r, std::integral_constant<int, 3>{}); break;
+                default: rest(r, std::integral_constant<int, 4>{}); break;
+                }
+            } else
                 group(k, r, true);
         }
     }
@@ -255,19 +279,19 @@ __device__ __forceinline__ void sweep(uint32_t (&acc)[AD], const char* ldsb, con
 // the position size): the elements beyond T are neither read nor relaxed.  The
 // top position is the one every entry reaches, so on short rows this is a
 // sizeable part of all the work.
-template <int D>
+template <int D, bool EXACT = false>
 __device__ __forceinline__ void sweep_live(uint32_t (&acc)[AD], const char* ldsb,
                                            const uint32_t* ent, int ke, uint32_t byte_pos,
                                            uint32_t park, int nea)
 {
     if (nea >= Geo::NE)
-        sweep<D>(acc, ldsb, ent, ke, byte_pos, park);
+        sweep<D, Geo::NE, EXACT>(acc, ldsb, ent, ke, byte_pos, park);
     else if (nea == 1)
-        sweep<D, 1>(acc, ldsb, ent, ke, byte_pos, park);
+        sweep<D, 1, EXACT>(acc, ldsb, ent, ke, byte_pos, park);
     else if (nea == 2)
-        sweep<D, 2>(acc, ldsb, ent, ke, byte_pos, park);
+        sweep<D, 2, EXACT>(acc, ldsb, ent, ke, byte_pos, park);
     else
-        sweep<D, 3>(acc, ldsb, ent, ke, byte_pos, park);
+        sweep<D, 3, EXACT>(acc, ldsb, ent, ke, byte_pos, park);
 }
 
 // Whether every cell of position pos is a cell of the row (only the top position
@@ -878,7 +902,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 if (p_hi >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_hi[u] = 0xFFFFFFFFu;
-                    sweep_live<DEPTH>(r_hi, ldsb, ent, __builtin_amdgcn_readlane(n_hi_l, m),
+                    sweep_live<DEPTH, true>(r_hi, ldsb, ent, __builtin_amdgcn_readlane(n_hi_l, m),
                                       G::lane_byte(p_hi, lane), G::park(p_hi),
                                       G::live_elements(p_hi, T));
                     clamp_position(r_hi);
@@ -886,7 +910,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
                 if (p_lo >= 0) {
 #pragma unroll
                     for (int u = 0; u < AD; ++u) r_lo[u] = 0xFFFFFFFFu;
-                    sweep<DEPTH>(r_lo, ldsb, ent, __builtin_amdgcn_readlane(n_lo_l, m),
+                    sweep<DEPTH, Geo::NE, true>(r_lo, ldsb, ent, __builtin_amdgcn_readlane(n_lo_l, m),
                                  G::lane_byte(p_lo, lane), G::park(p_lo));
                     clamp_position(r_lo);
                 }

@@ -94,6 +94,35 @@ def test_pruned_tiny_random(T, oracle):
         same(b.results(), oracle.solve(w))
 
 
+@pytest.mark.parametrize("S", [12, 70])
+def test_pruned_many_models(T, oracle, S):
+    """Pipelines whose pruned rows do not fit the staging buffer of stage 2 together
+    (sixteen candidates per model, so the buffer holds sixteen entries: the models
+    go through it in several batches), and one with more models than a wavefront
+    has lanes (served by the kernel for unpruned rows)."""
+    rng = np.random.default_rng(31 + S)
+    n, c_max, r_max = 48, 4, 60
+    bs = [1, 2, 4, 8]
+    coef = np.stack([rng.integers(lo, hi + 1, size=(n, S)) for lo, hi in
+                     ((200, 6000), (50, 1500), (0, 20), (1, 4), (1, 300))],
+                    axis=-1).astype(np.int32)
+    lam = rng.integers(200, 4000, n).astype(np.int32)
+    slo = rng.integers(20_000, 2_000_000, n).astype(np.int32)
+    w = wl.Workload(f"many-{S}", wl.JOINT, n, S, c_max, bs, r_max, 250, 2_000_000, False, coef,
+                    lam, slo)
+    print(f"[case] pruned, {S} models", flush=True)
+    b = T.DeviceBatch(w, prune=1)
+    assert T.check_problem(b.p) == T.OK
+    lt_g, _ = b.candidates()
+    survivors = (lt_g >= 0).sum(axis=-1)                    # [n, S]
+    padded = ((survivors + 3) // 4 * 4).sum(axis=-1)        # entries of an instance, rows on groups of four
+    assert (padded > 2 * 16).all(), "every instance needs more than two batches"
+    want = oracle.solve(w, threads=8)
+    b.solve()
+    same(b.results(), want)
+    assert (want[0] == 0).sum() > 30
+
+
 def test_pruned_with_binned_costs(T, oracle):
     """r_max * c_max beyond the cost table: costs are binned, fewer candidates
     are dropped, the answers stay the same and no survivor is dominated by a
