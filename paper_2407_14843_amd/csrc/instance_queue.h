@@ -22,23 +22,47 @@ __device__ __forceinline__ const AS_CONST T* as_constant(const T* p)
 }
 
 // Instances are handed to the workgroups of a launch from the launch's list
-// (one class, or several classes one after the other).  The first gridDim.x
-// entries are dealt out by workgroup index; the rest are pulled one at a time
-// through an atomic cursor, so that a workgroup that drew long rows takes fewer.
-// The static first round matters for small batches: read-modify-writes on one
-// address complete at a rate of one per some tens of nanoseconds device-wide, which
-// a launch of thousands of short rows that all begin (and end) with a pull would
-// be bound by.  A launch whose list is no longer than its grid never touches the
-// cursor at all.
-//
+// (one class, or several classes one after the other).  The first rounds are
+// dealt out by workgroup index (round r: entry r * gridDim.x + blockIdx.x); the
+// rest are pulled one at a time through an atomic cursor, so that a workgroup
+// that drew long rows takes fewer.  One round is dealt out: read-modify-writes on
+// one address complete at a rate of one per some tens of nanoseconds device-wide,
+// which a launch of thousands of short rows that all begin (and end) with a pull
+// would be bound by, and a launch whose list is no longer than its grid never
+// touches the cursor at all.  Beyond that, pulling is what keeps the workgroups
+// level: the lists are ordered longest rows first, and dealing out more rounds
+// of unpruned rows was slower on every workload measured.  With SHORT_LISTS_DEALT
+// (the kernel for pruned rows, whose instances take a few microseconds each and
+// differ less) a list of up to four rounds is dealt out entirely.
+template <bool SHORT_LISTS_DEALT = false>
+__device__ __forceinline__ int static_rounds(int count, int grid)
+{
+    return SHORT_LISTS_DEALT && count <= 4 * grid ? (count + grid - 1) / grid : 1;
+}
+
+// The list index that follows `prev` for this workgroup without a pull, or -2
+// when the next one has to be pulled (-1: the list is exhausted).  `prev` is the
+// workgroup's previous index (-1 before the first).
+template <bool SHORT_LISTS_DEALT = false>
+__device__ __forceinline__ int next_static_index(int count, int prev)
+{
+    const int grid = (int)gridDim.x;
+    const int dealt = static_rounds<SHORT_LISTS_DEALT>(count, grid) * grid;  // entries dealt out
+    if (prev < dealt) {
+        const int idx = prev < 0 ? (int)blockIdx.x : prev + grid;
+        if (idx < dealt) return idx < count ? idx : -1;
+    }
+    return dealt < count ? -2 : -1;
+}
+
 // Returns the list index of the workgroup's next instance, or -1 when the list
 // is exhausted; every wavefront of the workgroup gets the same answer.
 // `prev` is the previous answer (-1 before the first call).
 __device__ __forceinline__ int next_index(volatile uint32_t* slot, int32_t* cursor, int count,
                                           int prev)
 {
-    if (prev < 0) return (int)blockIdx.x < count ? (int)blockIdx.x : -1;
-    if (count <= (int)gridDim.x) return -1;
+    const int dealt_idx = next_static_index(count, prev);
+    if (dealt_idx != -2) return dealt_idx;
     if (threadIdx.x == 0) *slot = (uint32_t)atomicAdd(cursor, 1);
     __syncthreads();
     const int idx = (int)gridDim.x + __builtin_amdgcn_readfirstlane((int)*slot);

@@ -836,13 +836,50 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     none.shift = 0u;
     none.ck = 0u;
 
+    // Instances come from the launch's list in the order of next_index().  What
+    // identifies the next instance (list index, instance, budget) is a chain of
+    // dependent memory latencies, several microseconds against the few an instance
+    // of pruned rows takes; so thread 0 fetches it one link per model while the
+    // workgroup works on the current instance, and hands it over through LDS.
     const int count = list_length(ctrl, cls, low_cls);
-    int idx = -1;
-    for (;;) {
-        idx = next_index(slot, ctrl + N_CLS + cls, count, idx);
-        if (idx < 0) break;
-        const int i = list_entry(ctrl, order, N, cls, low_cls, idx);
-        const int T = as_constant(tmeta)[i];
+    int32_t* const cursor = ctrl + N_CLS + cls;
+    int idx = next_static_index<true>(count, -1);  // the first round is never pulled
+    int i = -1, T = 0;
+    if (idx >= 0) {
+        i = list_entry(ctrl, order, N, cls, low_cls, idx);
+        T = as_constant(tmeta)[i];
+    }
+    while (i >= 0) {
+        // thread 0's fetch of the next instance, one link per call (every thread
+        // calls, so that the link count stays uniform; `next` is thread 0's alone)
+        idx = next_static_index<true>(count, idx);
+        int link = 0, next = idx;
+        auto pull_next = [&]() {
+            if (link >= 3) return;
+            if (tid == 0) {
+                if (link == 0) {        // list index
+                    if (next == -2)
+                        next = static_rounds<true>(count, (int)gridDim.x) * (int)gridDim.x +
+                               atomicAdd(cursor, 1);
+                    slot[2] = (uint32_t)next;
+                } else if (link == 1) {  // instance
+                    int at = next;
+                    next = -1;
+                    for (int c = cls; c >= low_cls && at >= 0 && at < count; --c) {
+                        const int n = as_constant(ctrl)[c];
+                        if (at < n) {
+                            next = order[(size_t)c * N + at];
+                            break;
+                        }
+                        at -= n;
+                    }
+                } else {                 // budget
+                    slot[0] = (uint32_t)next;
+                    next = next >= 0 ? tmeta[next] : 0;
+                }
+            }
+            ++link;
+        };
         const int npos = (T + POSC) / POSC;  // positions that hold cells 0..T
         const int p_hi = npos - 1 - w;       // negative: none
         const int p_lo = npos - 2 * nw + w;  // negative: none
@@ -896,6 +933,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 
             for (int m = m0; m < m1; ++m) {
                 const int s = S - 1 - m;
+                pull_next();
                 const uint32_t* const ent = cbuf + (__builtin_amdgcn_readlane(start_l, m) - base);
                 uint16_t* const out = frow + ((size_t)i * S + s) * row_stride;
                 uint32_t r_hi[AD], r_lo[AD];
@@ -925,7 +963,15 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             }
             m0 = m1;
         }
+        // the links a short pipeline left over, then the hand-over
+        pull_next();
+        pull_next();
+        pull_next();
+        if (tid == 0) slot[1] = (uint32_t)next;
         __syncthreads();  // last row's reads are done before the LDS is re-initialised
+        i = __builtin_amdgcn_readfirstlane((int)slot[0]);
+        T = __builtin_amdgcn_readfirstlane((int)slot[1]);
+        idx = __builtin_amdgcn_readfirstlane((int)slot[2]);
     }
 }
 
