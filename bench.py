@@ -39,13 +39,13 @@ VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-o
 # the counters were taken on, fingerprint of the kernel sources at that time).
 # `roofline.traffic` is null unless both still match this run.
 K2_HBM_TRAFFIC = {
-    "w1-joint-4096x5": (125121003, 5247396664, "d5c36bb574f72033"),
-    "w3-joint-65536x8": (11614247286, 1422380424686, "d5c36bb574f72033"),
+    "w1-joint-4096x5": (116194939, 5247396664, "59a1d0c183a30434"),
+    "w3-joint-65536x8": (11098545173, 1422380424686, "59a1d0c183a30434"),
 }
 # the same for stage 1 (input check + candidate kernel): workload -> (bytes, fingerprint)
 K1_HBM_TRAFFIC = {
-    "w1-joint-4096x5": (20049232, "d5c36bb574f72033"),
-    "w3-joint-65536x8": (1057142768, "d5c36bb574f72033"),
+    "w1-joint-4096x5": (20024421, "59a1d0c183a30434"),
+    "w3-joint-65536x8": (1057116152, "59a1d0c183a30434"),
 }
 KERNEL_SOURCES = ("k1_candidates.hip", "candidate_eval.h", "k2_minplus.hip", "instance_queue.h",
                   "themis_internal.h")
@@ -502,7 +502,8 @@ def main():
         "feasible_fraction": m["feasible_fraction"],
         "kernel_ms": m["kernel_ms"],
         "roofline": {
-            "kernel": "k2_minplus_wide (all class launches of a step)", "bound": "lds",
+            "kernel": ("k2_minplus_pruned" if a.prune else "k2_minplus_wide") +
+                      " (all class launches of a step)", "bound": "lds",
             "achieved": k2_gbs, "peak": LDS_PEAK_GBS, "unit": "GB/s",
             "frac": k2_gbs / LDS_PEAK_GBS,
             "traffic": hbm_traffic(m["workload"], m["minplus_lds_bytes"]),
