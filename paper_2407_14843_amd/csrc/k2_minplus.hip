@@ -38,7 +38,7 @@
 // first bcum[p+1] entries of the row: the inner loops run over a prefix with no
 // test per candidate.  Work per position therefore grows with p; the wavefronts
 // of a workgroup take positions from a counter, most expensive first (or, in the
-// form used for pruned rows, own a late and an early position each).  A stretch
+// kernel for pruned rows, own a late and an early position each).  A stretch
 // of F_INF in front of every copy serves the reads that reach below t = 0, and
 // doubles as the harmless target of the entries that pad a group of four beyond
 // the prefix.

@@ -19,10 +19,10 @@ def T():
     return themis
 
 
-def gpu_solve(T, w):
+def gpu_solve(T, w, prune=0):
     print(f"[case] {w.name} N={w.n_inst} S={w.n_stage} K={w.n_cand} variant={w.variant} "
-          f"tick={w.tick_us} slo_max={w.slo_max_us}", flush=True)
-    b = T.DeviceBatch(w)
+          f"tick={w.tick_us} slo_max={w.slo_max_us} prune={prune}", flush=True)
+    b = T.DeviceBatch(w, prune=prune)
     b.solve()
     return b.results()
 
@@ -106,8 +106,8 @@ def test_row_lengths_around_tile_edges(T, oracle, cells):
     w = wl.Workload(f"edge{cells}", wl.JOINT, 6, base.n_stage, base.c_max, base.batch_sizes,
                     base.r_max, tick, slo_max, False, base.coef, base.lam, slo)
     want = oracle.solve(w)
-    got = gpu_solve(T, w)
-    assert_same(got, want)
+    for prune in (0, 1):  # the kernel for unpruned rows, the one for pruned rows
+        assert_same(gpu_solve(T, w, prune), want)
 
 
 def test_invalid_and_degenerate_instances(T, oracle):
@@ -123,8 +123,8 @@ def test_invalid_and_degenerate_instances(T, oracle):
     w.slo_us[9] = 999               # below one tick
     w.lam[10] = 1 << 20             # largest accepted arrival rate
     want = oracle.solve(w)
-    got = gpu_solve(T, w)
-    assert_same(got, want)
+    for prune in (0, 1):
+        assert_same(gpu_solve(T, w, prune), want)
     assert want[0][:11].tolist() == [0, 2, 2, 2, 2, 2, 2, 2, 1, 1, 1]
 
 
