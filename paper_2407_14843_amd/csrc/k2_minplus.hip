@@ -811,6 +811,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
 // 64 models; the launcher sends the others to k2_minplus_wide.  Measured on
 // dense rows the dealt-out positions of that kernel are faster on four of five
 // workloads, hence the two kernels.
+template <bool CHUNKS>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) void k2_minplus_pruned(
     const StepEntry* __restrict__ step_tab, const uint16_t* __restrict__ bcum,
     const int32_t* __restrict__ tmeta, const int32_t* __restrict__ order,
@@ -841,8 +842,24 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     // dependent memory latencies, several microseconds against the few an instance
     // of pruned rows takes; so thread 0 fetches it one link per model while the
     // workgroup works on the current instance, and hands it over through LDS.
+    //
+    // Pulls of short rows are in chunks: the cursor counts instances, and a pull
+    // takes up to pull_max of them at once, fewer as the list runs out (a quarter
+    // of what would be each workgroup's share of the rest), so that the last pulls
+    // are single instances and the workgroups end level.  One address takes a
+    // read-modify-write every twelve nanoseconds or so device-wide: a pull per
+    // instance bounds a launch of many short rows by the cursor alone (86400 rows
+    // of 2000 cells: 1.0 ms whatever the rows cost).  Workgroups of eight
+    // wavefronts or more are few and their instances long: there single pulls
+    // keep them level best, and their instantiation (CHUNKS false) is without the
+    // chunk code, which costs the sweeps two registers (1.7 % there).
+    const int pull_max = 16 / nw < 8 ? 16 / nw : 8;
     const int count = list_length(ctrl, cls, low_cls);
     int32_t* const cursor = ctrl + N_CLS + cls;
+    const int dealt = static_rounds<true>(count, (int)gridDim.x) * (int)gridDim.x;
+    // thread 0's chunk sits in LDS between its uses, not in registers the sweeps need:
+    // (next list index of the chunk) << 4 | (instances left in it)
+    if (CHUNKS && tid == 0) slot[3] = 0u;
     int idx = next_static_index<true>(count, -1);  // the first round is never pulled
     int i = -1, T = 0;
     if (idx >= 0) {
@@ -858,9 +875,20 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
             if (link >= 3) return;
             if (tid == 0) {
                 if (link == 0) {        // list index
-                    if (next == -2)
-                        next = static_rounds<true>(count, (int)gridDim.x) * (int)gridDim.x +
-                               atomicAdd(cursor, 1);
+                    if (next == -2) {
+                        uint32_t chunk = CHUNKS ? slot[3] : 0u;
+                        if (!CHUNKS) {
+                            chunk = (uint32_t)(dealt + atomicAdd(cursor, 1)) << 4 | 1u;
+                        } else if ((chunk & 15u) == 0u) {
+                            // the cursor as last seen: where this workgroup's last chunk ended
+                            const int seen = chunk ? (int)(chunk >> 4) : dealt;
+                            int c = (count - seen) / (4 * (int)gridDim.x);
+                            c = c < 1 ? 1 : (c > pull_max ? pull_max : c);
+                            chunk = (uint32_t)(dealt + atomicAdd(cursor, c)) << 4 | (uint32_t)c;
+                        }
+                        next = (int)(chunk >> 4);
+                        if (CHUNKS) slot[3] = chunk + 15u;  // index + 1, left - 1
+                    }
                     slot[2] = (uint32_t)next;
                 } else if (link == 1) {  // instance
                     int at = next;
@@ -1094,20 +1122,31 @@ hipError_t launch_wide_class(const Layout& L_, char* ws, hipStream_t st, int c, 
     const int nwc = CLS_WAVES[c];
     const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
     const size_t lds_bytes = wide_lds_bytes(nwc, cand_buf);
-    const void* const kernel = pruned_rows ? reinterpret_cast<const void*>(&k2_minplus_pruned)
-                                           : reinterpret_cast<const void*>(&k2_minplus_wide);
+    const bool chunks = nwc < 8;  // see the kernel's pulls
+    const void* const kernel =
+        !pruned_rows ? reinterpret_cast<const void*>(&k2_minplus_wide)
+        : chunks     ? reinterpret_cast<const void*>(&k2_minplus_pruned<true>)
+                     : reinterpret_cast<const void*>(&k2_minplus_pruned<false>);
     hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)(LDS_PER_CU - 1024));
     if (e != hipSuccess) return e;
     long long grid = (long long)cus * wide_groups_per_cu(nwc, cand_buf);
     if (grid > L_.N) grid = L_.N;
-    if (pruned_rows)
-        hipLaunchKernelGGL(k2_minplus_pruned, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
-                           (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
-                           (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
-                           (int32_t*)(ws + L_.ctrl_off), (uint16_t*)(ws + L_.frow_off), L_.N, L_.S,
-                           L_.Kp, L_.nbs, L_.row_stride, c, low);
-    else
+    if (pruned_rows) {
+        auto launch = [&](auto kern) {
+            hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
+                               (const StepEntry*)(ws + L_.step_off),
+                               (const uint16_t*)(ws + L_.bcum_off),
+                               (const int32_t*)(ws + L_.tmeta_off),
+                               (const int32_t*)(ws + L_.order_off), (int32_t*)(ws + L_.ctrl_off),
+                               (uint16_t*)(ws + L_.frow_off), L_.N, L_.S, L_.Kp, L_.nbs,
+                               L_.row_stride, c, low);
+        };
+        if (chunks)
+            launch(&k2_minplus_pruned<true>);
+        else
+            launch(&k2_minplus_pruned<false>);
+    } else
         hipLaunchKernelGGL(k2_minplus_wide, dim3((unsigned)grid), dim3(nwc * 64), lds_bytes, st,
                            (const StepEntry*)(ws + L_.step_off), (const uint16_t*)(ws + L_.bcum_off),
                            (const int32_t*)(ws + L_.tmeta_off), (const int32_t*)(ws + L_.order_off),
