@@ -262,13 +262,15 @@ def test_full_size_sampled(T, oracle, idx, k):
     assert (got[1][~solved] == -1).all() and (got[3][~solved] == 0).all()
 
 
-def test_full_trace_sweep_both_passes(T, oracle):
+@pytest.mark.parametrize("prune", [0, 1])
+def test_full_trace_sweep_both_passes(T, oracle, prune):
     """Workload 4 end to end: joint solve of every second, replicas carried
     forward on the host, vertical-only solve of every second.  The checker
     only needs one solve per distinct arrival rate (coefficients and SLO are
-    shared), which covers every instance exactly."""
+    shared), which covers every instance exactly.  (With pruning this is the
+    case of many short rows, which stage 2 pulls in chunks.)"""
     w = wl.workload(4)
-    got_j = gpu_solve(T, w)
+    got_j = gpu_solve(T, w, prune)
     lam_u, first, inv = np.unique(w.lam, return_index=True, return_inverse=True)
     want_u = oracle.solve(w.take(first), threads=8)
     want_j = tuple(a[inv] for a in want_u)
@@ -276,7 +278,7 @@ def test_full_trace_sweep_both_passes(T, oracle):
     # second pass: inputs come from the checker's joint results, not the GPU's
     r_fixed = wl.replicas_carried_forward(want_j[0], want_j[3])
     wv = w.with_r_fixed(r_fixed)
-    got_v = gpu_solve(T, wv)
+    got_v = gpu_solve(T, wv, prune)
     key = np.concatenate([w.lam[:, None], r_fixed], axis=1)
     _, first_v, inv_v = np.unique(key, axis=0, return_index=True, return_inverse=True)
     want_vu = oracle.solve(wv.take(first_v), threads=8)
