@@ -226,6 +226,45 @@ def two_streams(themis, wl, idx, steps, warmup):
     return {"ms_per_step": ms, "solves_per_s": w.n_inst / (ms * 1e-3)}
 
 
+def small_batches(themis, wl):
+    """Latency of a whole solve on small batches (what a controller that decides for
+    a few pipelines at a time sees), issued call by call and as replays of a HIP
+    graph captured from the same call, which removes the gaps between the
+    solve's launches: microseconds per solve, synchronised after every solve."""
+    import torch
+    out = {}
+    for idx, n in ((0, None), (1, 64), (1, 512)):
+        for prune in (0, 1):
+            w = wl.workload(idx, n)
+            b = themis.DeviceBatch(w, "cuda:0", prune=prune)
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                for _ in range(3):
+                    b.solve(stream=s)
+            s.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                b.solve(stream=torch.cuda.current_stream())
+            reps = 200
+
+            def timed(fn):
+                fn()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    fn()
+                    torch.cuda.synchronize()
+                return (time.perf_counter() - t0) * 1e6 / reps
+
+            with torch.cuda.stream(s):
+                eager = timed(lambda: b.solve(stream=s))
+            replay = timed(g.replay)
+            out[f"{w.name}[{w.n_inst}]" + ("-pruned" if prune else "")] = {
+                "us_per_solve": eager, "us_per_graph_replay": replay}
+    return out
+
+
 def next_rows(themis, wl, steps, warmup):
     """Timings of the entry points beyond the two plain solves, each on a seeded
     workload of the shapes above: horizontal-only solve and stability test
@@ -573,6 +612,7 @@ def main():
             return others
         extra("other_workloads", others_leg)
         extra("next_rows", lambda: next_rows(themis, wl, max(3, a.steps // 2), 2))
+        extra("small_batches", lambda: small_batches(themis, wl))
     if not a.no_cpu:
         extra("cpu_baseline", lambda: cpu_baseline(wl, a.workload, a.cpu_sample))
     if errors:

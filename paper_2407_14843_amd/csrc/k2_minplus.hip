@@ -1164,6 +1164,19 @@ MinplusPlan make_plan(const Layout& L_)
     pl.cus = cu_count();
     pl.top = class_of_budget(L_.t_max);
     pl.top_wide = pl.top == NARROW_CLS ? N_WIDE_CLS - 1 : pl.top;
+    // A batch that fills less than half of the chip even with workgroups of twice
+    // the wavefronts gets that geometry: every wavefront then has one position of a
+    // longest row instead of two, and a solve that is one latency chain (a handful
+    // of instances) is about a quarter shorter.  (Not for step rows, whose kernel
+    // works by budgets, not positions.)
+    if (!L_.step_rows) {
+        int boosted = pl.top_wide;
+        const int want = 2 * CLS_WAVES[pl.top_wide] < 16 ? 2 * CLS_WAVES[pl.top_wide] : 16;
+        while (CLS_WAVES[boosted] < want) ++boosted;
+        const int cand_buf = L_.Kp < CAND_BUF ? L_.Kp : CAND_BUF;
+        if (2LL * L_.N <= (long long)pl.cus * wide_groups_per_cu(CLS_WAVES[boosted], cand_buf))
+            pl.top_wide = boosted;
+    }
     // Heads of the class groups (bit c set = class c has a launch of its own).
     // One launch for everything is best until the batch is large and its longest
     // rows need twelve wavefronts or more; then the rows of up to eight chunks get

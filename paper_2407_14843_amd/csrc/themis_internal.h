@@ -166,7 +166,8 @@ MinplusPlan make_plan(const Layout& L);
 struct Layout {
     size_t step_off, bcum_off, frow_off, tmeta_off, ans_off, order_off, ctrl_off, total;
     int32_t N, S, K, Kp, t_max, row_stride, nb, nbs;
-    int32_t fixed_form;  // stage 2 runs its form for pruned rows (the launch plan depends on it)
+    int32_t fixed_form;  // stage 2 runs its kernel for pruned rows (the launch plan depends on it)
+    int32_t step_rows;   // stage 2 keeps rows as step functions (likewise)
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -180,6 +181,7 @@ inline Layout make_layout(const themis_problem_t& p)
     L.Kp = (L.K + 7) / 8 * 8;
     L.t_max = p.slo_max_us / p.tick_us;
     L.fixed_form = (p.prune & THEMIS_PRUNE_DOMINATED) != 0 && (p.prune & THEMIS_PRUNE_STEPS) == 0;
+    L.step_rows = (p.prune & THEMIS_PRUNE_STEPS) != 0;
     L.nb = (L.t_max >> BUCKET_SHIFT) + 1;
     L.nbs = (L.nb + 1 + 1) / 2 * 2;
     // a lane stores the four cells of a quad at once, so up to three cells

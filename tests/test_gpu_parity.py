@@ -389,10 +389,11 @@ def test_relaxation_count(T, oracle):
     per_model = np.where(lt >= 0, Ti[:, None, None] + 1 - lt, 0).sum(axis=2)     # [N][S]
     # The last model of the pipeline (a running minimum over its candidates) and
     # the first (only the answer is computed) take no relaxations when they have
-    # candidates enough: n * positions >= 24 * wavefronts, and this workload's
-    # rows (up to 4000 ticks) are served by workgroups of four wavefronts.
+    # candidates enough: n * positions >= 24 * wavefronts; this workload's rows (up
+    # to 4000 ticks) need four wavefronts, and a batch this small is served by
+    # workgroups of twice that.
     n = (lt >= 0).sum(axis=2)
-    short = n * (Ti[:, None] // 512 + 1) >= 24 * 4
+    short = n * (Ti[:, None] // 512 + 1) >= 24 * 8
     skipped = np.zeros_like(short)
     skipped[:, -1] = short[:, -1]
     skipped[:, 0] = short[:, 0]
