@@ -824,8 +824,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(8, 8))) vo
     const int CSB = wide_copy_bytes(cls_waves(cls));  // bytes per copy: pad + the longest row
     const int SETB = COPIES * CSB;                    // bytes of all copies
     char* const ldsb = reinterpret_cast<char*>(lds);
-    // after the copies: a dword for the instance queue, then (16 bytes on) the
-    // staging buffer for Kp (+16) candidate entries
+    // after the copies: four dwords of thread 0's about the next instance (instance,
+    // budget, list index; its chunk of the list), then the staging buffer for Kp
+    // (+16) candidate entries
     volatile uint32_t* const slot = reinterpret_cast<volatile uint32_t*>(ldsb + SETB);
     uint32_t* const cbuf = reinterpret_cast<uint32_t*>(ldsb + SETB + 16);
 
