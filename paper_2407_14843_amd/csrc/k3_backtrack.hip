@@ -174,11 +174,12 @@ hipError_t launch_backtrack(const themis_problem_t& p, const Layout& L, int32_t*
     bl.n = p.n_batch;
     for (int j = 0; j < p.n_batch; ++j) bl.b[j] = p.batch_sizes[j];
     const MinplusPlan plan = make_plan(L);
-    // Lanes per instance: a wavefront where a row can have hundreds of entries; a
-    // half or a quarter where it cannot, or where dominated candidates were
-    // dropped (a few dozen entries are left at most: the singles of stage 1)
+    // Lanes per instance: a wavefront where a row can have more than 256 entries; a
+    // half (two rounds of four groups at 256 entries, measured faster than one
+    // round of a whole wavefront) or a quarter where it cannot; an eighth where
+    // dominated candidates were dropped (a few dozen entries are left at most)
     const bool pruned = (p.prune & THEMIS_PRUNE_DOMINATED) != 0;
-    const int lanes = pruned ? 8 : L.Kp <= 64 ? 16 : L.Kp <= 128 ? 32 : 64;
+    const int lanes = pruned ? 8 : L.Kp <= 64 ? 16 : L.Kp <= 256 ? 32 : 64;
     auto launch = [&](auto kernel, int per_block) {
         hipLaunchKernelGGL(kernel, dim3((L.N + per_block - 1) / per_block), dim3(256), 0, st,
                            (const StepEntry*)(ws + L.step_off), (const uint16_t*)(ws + L.bcum_off),
