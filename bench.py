@@ -39,13 +39,13 @@ VALU_PEAK_GOPS = N_CU * 64 * CLOCK_GHZ                          # 39322 G lane-o
 # the counters were taken on, fingerprint of the kernel sources at that time).
 # `roofline.traffic` is null unless both still match this run.
 K2_HBM_TRAFFIC = {
-    "w1-joint-4096x5": (116144623, 5247396664, "dc14bc4491f9ff0e"),
-    "w3-joint-65536x8": (11101698742, 1422380424686, "dc14bc4491f9ff0e"),
+    "w1-joint-4096x5": (116046179, 5247396664, "dc14bc4491f9ff0e"),
+    "w3-joint-65536x8": (11099767522, 1422380424686, "dc14bc4491f9ff0e"),
 }
 # the same for stage 1 (input check + candidate kernel): workload -> (bytes, fingerprint)
 K1_HBM_TRAFFIC = {
-    "w1-joint-4096x5": (20026295, "dc14bc4491f9ff0e"),
-    "w3-joint-65536x8": (1056598018, "dc14bc4491f9ff0e"),
+    "w1-joint-4096x5": (20024054, "dc14bc4491f9ff0e"),
+    "w3-joint-65536x8": (1056689776, "dc14bc4491f9ff0e"),
 }
 KERNEL_SOURCES = ("k1_candidates.hip", "candidate_eval.h", "k2_minplus.hip", "instance_queue.h",
                   "themis_internal.h")
